@@ -1,0 +1,93 @@
+"""SAMA on the data-reweighting bilevel problem (Sec. 4.1):
+
+    base:  theta*(lambda) = argmin (1/B_eff) sum_i mask_i w(l_i; lambda) l_i(theta)     on noisy data
+    meta:  lambda* = argmin mean CE on clean data at theta*(lambda)
+
+one `unroll` of base steps followed by one meta step (Sec. 2, Sec. 3.2).  Float64 throughout.
+Readings where the paper is silent are marked "reading:" below.
+"""
+import numpy as np
+from . import optim, sama_core, wnet
+
+SGD, ADAM = 0, 1
+
+
+class SamaOracle:
+    def __init__(self, model, theta0, lambda0, *, base_opt=ADAM, base_lr=1e-3, beta1=0.9, beta2=0.999,
+                 adam_eps=1e-8, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999, meta_eps=1e-8,
+                 alpha=1.0, adapt_mode=optim.ADAPT_ADAM):
+        self.model = model
+        self.theta = np.array(theta0, dtype=np.float64)
+        self.lam = np.array(lambda0, dtype=np.float64)
+        n = self.theta.size
+        self.m = np.zeros(n); self.v = np.zeros(n); self.g = np.zeros(n)
+        self.t = 0
+        self.meta_m = np.zeros(self.lam.size); self.meta_v = np.zeros(self.lam.size)
+        self.meta_t = 0
+        self.base_opt, self.base_lr, self.beta1, self.beta2, self.adam_eps = base_opt, base_lr, beta1, beta2, adam_eps
+        self.meta_lr, self.meta_beta1, self.meta_beta2, self.meta_eps = meta_lr, meta_beta1, meta_beta2, meta_eps
+        self.alpha, self.adapt_mode = alpha, adapt_mode
+        self.status = 0                # 1 after a meta step skipped for ||v|| = 0 / non-finite
+
+    # ------------------------------------------------------------------ base level
+    def base_step(self, x, y, mask=None):
+        """One step of the base solver u on L_base.  w_i is a constant of the backward pass
+        (reading: no gradient through the weight net's input, the Meta-Weight-Net convention);
+        normalisation is 1/B_eff, B_eff = sum mask (reading of 1/|D_noisy|).  Returns L_base."""
+        mask = np.ones(len(y)) if mask is None else np.asarray(mask, dtype=np.float64)
+        l = self.model.losses(self.theta, x, y)
+        w = wnet.weights(l, self.lam)
+        coef = mask * w / mask.sum()
+        l, g = self.model.loss_grad(self.theta, x, y, coef)
+        self.g = g
+        self.t += 1
+        if self.base_opt == ADAM:
+            self.theta, self.m, self.v = optim.adam_update(self.theta, self.m, self.v, g, self.t, self.base_lr,
+                                                           self.beta1, self.beta2, self.adam_eps)
+        else:
+            self.theta = optim.sgd_update(self.theta, g, self.base_lr)
+        return float(np.sum(coef * l))
+
+    # ------------------------------------------------------------------ meta level
+    def adaptation(self):
+        """du/dg on the diagonal from the LAST base step's gradient and its post-update moments
+        (reading: no extra backward pass is spent on re-evaluating g at the updated theta, in
+        keeping with the three-pass count of Sec. 3.3)."""
+        if self.adapt_mode == optim.ADAPT_NONE:
+            return np.ones_like(self.g)
+        if self.base_opt == ADAM:
+            return optim.adam_adaptation(self.g, self.m, self.v, self.t, self.base_lr, self.beta1, self.beta2,
+                                         self.adam_eps)
+        return optim.sgd_adaptation(self.g, self.base_lr)
+
+    def glam(self, theta, x, y, mask=None):
+        """dL_base(theta, lambda)/dlambda: a forward pass for l_i(theta), then the weight net's backward."""
+        l = self.model.losses(theta, x, y)
+        return wnet.base_loss_grad_lambda(l, self.lam, mask)
+
+    def meta_grad(self, xt, yt, xm, ym, mask_t=None, mask_m=None):
+        """Eq. 5 on the current state; changes nothing.  Returns dict(h, eps, v, g_meta, glam_p, glam_m).
+        reading: the theta+- passes reuse the train batch (xt, yt) that produced g."""
+        if self.t == 0:
+            raise RuntimeError("meta_grad before any base step")
+        mm = np.ones(len(ym)) if mask_m is None else np.asarray(mask_m, dtype=np.float64)
+        _, g_meta = self.model.loss_grad(self.theta, xm, ym, mm / mm.sum())        # direct gradient, Eq. 1
+        v = sama_core.perturbation(self.adaptation(), g_meta)
+        eps = sama_core.step_size(v, self.alpha)
+        h, gp, gm = sama_core.central_difference(lambda th: self.glam(th, xt, yt, mask_t), self.theta, v, eps)
+        return dict(h=h, eps=eps, v=v, g_meta=g_meta, glam_p=gp, glam_m=gm)
+
+    def meta_step(self, xt, yt, xm, ym, mask_t=None, mask_m=None):
+        """meta_grad, then Adam on lambda with h (Table 4), then theta <- theta - eps v (end of Sec. 3.2).
+        reading: the nudge leaves the base moments and step count alone; a zero / non-finite ||v||
+        skips both updates and raises `status`."""
+        r = self.meta_grad(xt, yt, xm, ym, mask_t, mask_m)
+        if r["eps"] == 0.0 or not np.all(np.isfinite(r["h"])):
+            self.status = 1
+            return r
+        self.meta_t += 1
+        self.lam, self.meta_m, self.meta_v = optim.adam_update(self.lam, self.meta_m, self.meta_v, r["h"],
+                                                               self.meta_t, self.meta_lr, self.meta_beta1,
+                                                               self.meta_beta2, self.meta_eps)
+        self.theta = sama_core.nudge(self.theta, r["v"], r["eps"])
+        return r

@@ -1,0 +1,91 @@
+"""Pins for oracle/optim.py: the Adam adaptation (App. C) against a central difference of the
+Adam update itself, closed-form special cases, and the SGD reduction (Sec. 3.2)."""
+import numpy as np
+from datagen import CounterRNG
+from oracle import optim
+
+
+def _u(g, m, v, t, lr, b1, b2, eps):
+    """u(g) = theta - theta' for one Adam step, through the oracle's update routine."""
+    th = np.zeros_like(g)
+    th2, _, _ = optim.adam_update(th, m, v, g, t, lr, b1, b2, eps)
+    return th - th2
+
+
+def _cases(seed, n=400):
+    r = CounterRNG(seed)
+    g = r.normal(1, n)
+    m = 0.3 * r.normal(2, n)
+    v = (0.5 * r.normal(3, n)) ** 2 + 1e-3
+    return g, m, v
+
+
+def test_adam_update_textbook_scalar():
+    # two steps of Adam on a scalar by hand (Kingma & Ba Alg. 1)
+    th, m, v = 1.0, 0.0, 0.0
+    lr, b1, b2, eps = 0.1, 0.9, 0.999, 1e-8
+    for t, g in ((1, 0.5), (2, -0.25)):
+        m = b1 * m + (1 - b1) * g
+        v = b2 * v + (1 - b2) * g * g
+        th = th - lr * (m / (1 - b1**t)) / (np.sqrt(v / (1 - b2**t)) + eps)
+    A = (np.array([1.0]), np.array([0.0]), np.array([0.0]))
+    for t, g in ((1, 0.5), (2, -0.25)):
+        A = optim.adam_update(A[0], A[1], A[2], np.array([g]), t, lr, b1, b2, eps)
+    assert abs(A[0][0] - th) < 1e-15
+    # first step from zero moments moves by lr * sign(g)
+    th1, _, _ = optim.adam_update(np.zeros(3), np.zeros(3), np.zeros(3), np.array([2.0, -3.0, 0.1]), 1, 0.01, 0.9, 0.999, 0.0)
+    assert np.allclose(th1, [-0.01, 0.01, -0.01], atol=1e-15)
+
+
+def test_adaptation_matches_central_difference_eps0():
+    for seed, t in ((1, 1), (2, 3), (3, 50), (4, 5000)):
+        g, m, v = _cases(seed)
+        lr, b1, b2 = 1e-3, 0.9, 0.999
+        m2 = b1 * m + (1 - b1) * g
+        v2 = b2 * v + (1 - b2) * g * g
+        D = optim.adam_adaptation(g, m2, v2, t, lr, b1, b2, 0.0)
+        h = 1e-5
+        fd = (_u(g + h, m, v, t, lr, b1, b2, 0.0) - _u(g - h, m, v, t, lr, b1, b2, 0.0)) / (2 * h)
+        assert np.max(np.abs(D - fd)) <= 1e-7 * np.max(np.abs(fd))
+
+
+def test_adaptation_eps_term():
+    g, m, v = _cases(5)
+    lr, b1, b2, eps, t = 1e-3, 0.9, 0.999, 1e-3, 7         # large eps_A so that the term is visible
+    m2 = b1 * m + (1 - b1) * g
+    v2 = b2 * v + (1 - b2) * g * g
+    h = 1e-5
+    fd = (_u(g + h, m, v, t, lr, b1, b2, eps) - _u(g - h, m, v, t, lr, b1, b2, eps)) / (2 * h)
+    D_exact = optim.adam_adaptation(g, m2, v2, t, lr, b1, b2, eps, keep_eps_term=True)
+    assert np.max(np.abs(D_exact - fd)) <= 1e-7 * np.max(np.abs(fd))
+    # the default form drops exactly (1-b1) eps s / (s (c2 s + eps)^2) and nothing else
+    D = optim.adam_adaptation(g, m2, v2, t, lr, b1, b2, eps)
+    c1, c2, s = 1 / (1 - b1**t), 1 / np.sqrt(1 - b2**t), np.sqrt(v2)
+    assert np.allclose(D_exact - D, lr * c1 * (1 - b1) * eps / (c2 * s + eps) ** 2, rtol=1e-8, atol=0)
+    # and at the default eps_A = 1e-8 the two agree to O(eps_A / s)
+    De = optim.adam_adaptation(g, m2, v2, t, lr, b1, b2, 1e-8, keep_eps_term=True)
+    Dd = optim.adam_adaptation(g, m2, v2, t, lr, b1, b2, 1e-8)
+    assert np.max(np.abs(De - Dd)) <= 1e-6 * np.max(np.abs(De))
+
+
+def test_adaptation_special_cases():
+    g = np.array([0.7, -1.3, 2.0])
+    lr, b1, b2 = 0.01, 0.9, 0.999
+    # first step from zero moments: u = lr sign(g), so du/dg = 0
+    D = optim.adam_adaptation(g, (1 - b1) * g, (1 - b2) * g * g, 1, lr, b1, b2, 0.0)
+    assert np.max(np.abs(D)) < 1e-15
+    # no history at all (s = 0): defined as 0, not inf/nan
+    D0 = optim.adam_adaptation(np.zeros(4), np.zeros(4), np.zeros(4), 3, lr, b1, b2, 1e-8)
+    assert np.all(D0 == 0.0)
+    # beta2 -> 1 with a frozen second moment: u = lr c1 m'/(c2 sqrt(v)) is linear in g with slope lr c1 (1-b1)/(c2 sqrt v)
+    v = np.array([0.5, 2.0, 4.0]); m = np.array([0.1, 0.2, -0.3]); t = 4
+    b2x = 1.0 - 1e-12
+    D2 = optim.adam_adaptation(g, b1 * m + (1 - b1) * g, b2x * v + (1 - b2x) * g * g, t, lr, b1, b2x, 0.0)
+    c1, c2 = 1 / (1 - b1**t), 1 / np.sqrt(1 - b2x**t)
+    assert np.allclose(D2, lr * c1 * (1 - b1) / (c2 * np.sqrt(v)), rtol=1e-6)
+
+
+def test_sgd_reduction():
+    g = np.arange(5.0)
+    assert np.all(optim.sgd_adaptation(g, 0.3) == 0.3)
+    assert np.allclose(optim.sgd_update(np.ones(5), g, 0.1), 1.0 - 0.1 * g)

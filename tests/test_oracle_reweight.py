@@ -1,0 +1,179 @@
+"""Pins for the assembled recipe (oracle/reweight.py + sama_core) on tiny problems: brute-force second
+derivatives of the scalar base loss, the exact implicit-function hypergradient (Eq. 1-2) by re-solving the
+base problem, the SGD invariant (Sec. 3.1-3.2) and the bookkeeping of the meta step (end of Sec. 3.2)."""
+import numpy as np
+import pytest
+from datagen import CounterRNG, make_workload, init_theta, init_lambda
+from oracle import models, wnet, optim, sama_core
+from oracle.reweight import SamaOracle, SGD, ADAM
+
+
+def _tiny(seed=41, B=24, Bm=10, F=5, C=3, H=4):
+    r = CounterRNG(seed)
+    model = models.MLP((F, C))
+    x = r.normal(1, B * F).reshape(B, F); y = r.integers(2, B, C)
+    xm = r.normal(3, Bm * F).reshape(Bm, F); ym = r.integers(4, Bm, C)
+    th = 0.5 * r.normal(5, model.n)
+    lam = np.concatenate([r.normal(6, H), np.abs(r.normal(7, H)), r.normal(8, H), [0.1]])
+    return model, x, y, xm, ym, th, lam
+
+
+def _after_steps(orc, x, y, k=3):
+    for _ in range(k):
+        orc.base_step(x, y)
+    return orc
+
+
+def test_glam_is_the_lambda_gradient_of_the_scalar_base_loss():
+    model, x, y, xm, ym, th, lam = _tiny()
+    mask = (np.arange(len(y)) % 5 != 0).astype(np.uint8)
+    orc = SamaOracle(model, th, lam)
+    got = orc.glam(th, x, y, mask)
+    L = lambda l: wnet.base_loss(model.losses(th, x, y), l, mask)
+    fd = np.array([(L(lam + 1e-6 * e) - L(lam - 1e-6 * e)) / 2e-6 for e in np.eye(len(lam))])
+    assert np.allclose(got, fd, rtol=1e-6, atol=1e-9)
+
+
+def test_fd_product_is_the_mixed_partial_times_v():
+    """h = -(d2 L_base / dlambda dtheta) v up to O(eps^2): the mixed partial is taken by brute force as a
+    four-point difference of the scalar L_base, and halving alpha divides the error by four."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    orc = _after_steps(SamaOracle(model, th, lam, base_lr=1e-2, alpha=0.2), x, y)
+    r = orc.meta_grad(x, y, xm, ym)
+    v, theta = r["v"], orc.theta
+    L = lambda t_, l_: wnet.base_loss(model.losses(t_, x, y), l_)
+    tau, dl = 1e-4 / np.linalg.norm(v), 1e-4
+    Mv = np.array([(L(theta + tau * v, lam + dl * e) - L(theta + tau * v, lam - dl * e)
+                    - L(theta - tau * v, lam + dl * e) + L(theta - tau * v, lam - dl * e)) / (4 * tau * dl)
+                   for e in np.eye(len(lam))])
+    errs = []
+    for alpha in (0.04, 0.02, 0.01):
+        orc.alpha = alpha
+        h = orc.meta_grad(x, y, xm, ym)["h"]
+        errs.append(np.linalg.norm(h + Mv))
+    assert errs[2] < 5e-3 * np.linalg.norm(Mv)
+    assert 3.0 < errs[0] / errs[1] < 5.0 and 3.0 < errs[1] / errs[2] < 5.0
+
+
+def test_exact_hypergradient_by_resolving_the_base_problem():
+    """Direct per-sample weights sigma(lam_i) on a tiny L2-regularised logistic regression: theta*(lambda) by
+    Newton with a brute-force Hessian; dL_meta/dlambda by differencing L_meta(theta*(lambda)).  Eq. 5's
+    central difference with v = H^-1 dL_meta/dtheta reproduces it (Eq. 1-2), and with the identity in
+    place of H^-1 (Eq. 3) it equals -M dL_meta/dtheta with M taken by brute force."""
+    model, x, y, xm, ym, th, _ = _tiny(seed=43, B=12)
+    B, n, rho = len(y), model.n, 0.05
+    lam = CounterRNG(44).normal(1, B)
+    sig = lambda z: 1 / (1 + np.exp(-z))
+    grad = lambda t_, l_: model.loss_grad(t_, x, y, sig(l_) / B)[1] + rho * t_
+
+    def hess(t_, l_):
+        return np.array([(grad(t_ + 1e-5 * e, l_) - grad(t_ - 1e-5 * e, l_)) / 2e-5 for e in np.eye(n)])
+
+    def solve(l_):
+        t_ = th.copy()
+        for _ in range(30):
+            t_ = t_ - np.linalg.solve(hess(t_, l_), grad(t_, l_))
+        assert np.linalg.norm(grad(t_, l_)) < 1e-10
+        return t_
+    ts = solve(lam)
+    Lmeta = lambda t_: model.losses(t_, xm, ym).mean()
+    exact = np.array([(Lmeta(solve(lam + 1e-4 * e)) - Lmeta(solve(lam - 1e-4 * e))) / 2e-4 for e in np.eye(B)])
+    gmeta = model.loss_grad(ts, xm, ym, np.full(len(ym), 1 / len(ym)))[1]
+    glam = lambda t_: sig(lam) * (1 - sig(lam)) * model.losses(t_, x, y) / B       # dL_base/dlam_i
+    Hinv_g = np.linalg.solve(hess(ts, lam), gmeta)
+    h_full, _, _ = sama_core.hypergradient(glam, ts, np.ones(n), Hinv_g, 1e-3)
+    assert np.allclose(h_full, exact, rtol=2e-4, atol=1e-7)
+    # identity approximation: -M g_meta, M_i = (1/B) sigma'(lam_i) dl_i/dtheta by brute force on each l_i
+    M = np.array([[sig(lam[i]) * (1 - sig(lam[i])) / B *
+                   (model.losses(ts + 1e-6 * e, x[i:i + 1], y[i:i + 1])[0] - model.losses(ts - 1e-6 * e, x[i:i + 1], y[i:i + 1])[0]) / 2e-6
+                   for e in np.eye(n)] for i in range(B)])
+    h_id, _, _ = sama_core.hypergradient(glam, ts, np.ones(n), gmeta, 1e-3)
+    assert np.allclose(h_id, -M @ gmeta, rtol=1e-5, atol=1e-9)
+    assert h_id @ exact > 0                                           # a descent direction for the true objective
+
+
+def test_sgd_invariant():
+    """With an SGD base solver the adaptation is the scalar step size: theta+-, eps*||v|| are independent of
+    gamma and h(gamma) = gamma h(1); SAMA-NA under Adam is the same thing with gamma = 1."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    outs = {}
+    for tag, kw in (("g1", dict(base_opt=SGD, base_lr=1.0)), ("g2", dict(base_opt=SGD, base_lr=0.037)),
+                    ("na", dict(base_opt=ADAM, base_lr=0.5, adapt_mode=optim.ADAPT_NONE))):
+        o = SamaOracle(model, th, lam, alpha=0.3, **kw)
+        o.base_step(x, y)
+        o.theta = th + 0.01                      # identical evaluation point for all three
+        outs[tag] = (o, o.meta_grad(x, y, xm, ym))
+    r1, r2, rna = outs["g1"][1], outs["g2"][1], outs["na"][1]
+    assert np.allclose(r2["v"], 0.037 * r1["v"], rtol=1e-14)
+    assert np.allclose(r2["eps"] * 0.037, r1["eps"], rtol=1e-13)
+    assert np.allclose(r2["glam_p"], r1["glam_p"], rtol=1e-11) and np.allclose(r2["glam_m"], r1["glam_m"], rtol=1e-11)
+    assert np.allclose(r2["h"], 0.037 * r1["h"], rtol=1e-9, atol=1e-15)
+    assert np.allclose(rna["h"], r1["h"], rtol=1e-12) and np.allclose(rna["v"], r1["g_meta"], rtol=0, atol=0)
+
+
+def test_meta_step_bookkeeping():
+    model, x, y, xm, ym, th, lam = _tiny()
+    orc = _after_steps(SamaOracle(model, th, lam, base_lr=1e-2, meta_lr=1e-3, alpha=0.7), x, y, k=4)
+    th0, m0, v0, t0, lam0 = orc.theta.copy(), orc.m.copy(), orc.v.copy(), orc.t, orc.lam.copy()
+    r0 = orc.meta_grad(x, y, xm, ym)
+    assert np.array_equal(orc.theta, th0) and np.array_equal(orc.lam, lam0) and orc.meta_t == 0     # pure
+    r = orc.meta_step(x, y, xm, ym)
+    assert np.array_equal(r["h"], r0["h"])
+    assert abs(np.linalg.norm(r["eps"] * r["v"]) - 0.7) < 1e-13
+    assert np.array_equal(orc.theta, th0 - r["eps"] * r["v"])
+    assert abs(np.linalg.norm(orc.theta - th0) - 0.7) < 1e-12
+    assert np.array_equal(orc.m, m0) and np.array_equal(orc.v, v0) and orc.t == t0
+    # first Adam step on lambda moves every entry by lr * h/(|h| + eps_A sqrt-corrected) ~ lr sign(h)
+    step = lam0 - orc.lam
+    nzh = np.abs(r["h"]) > 1e-6
+    assert np.allclose(step[nzh], 1e-3 * np.sign(r["h"][nzh]), rtol=1e-2)
+    assert orc.meta_t == 1 and orc.status == 0
+    # the direction is the adapted direct gradient
+    D = optim.adam_adaptation(orc.g, orc.m, orc.v, orc.t, 1e-2, 0.9, 0.999, 1e-8)
+    assert np.array_equal(r["v"], D * r["g_meta"])
+
+
+def test_first_step_direction_is_degenerate_and_skipped():
+    """After a single Adam step from zero moments u = lr sign(g) and du/dg = 0 (up to rounding noise): the
+    oracle must either skip (v = 0) or return a finite result; a forced zero direction raises the flag."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    orc = SamaOracle(model, th, lam)
+    orc.base_step(x, y)
+    orc.g[...] = 0; orc.m[...] = 0; orc.v[...] = 0
+    th0, lam0 = orc.theta.copy(), orc.lam.copy()
+    r = orc.meta_step(x, y, xm, ym)
+    assert r["eps"] == 0.0 and np.all(r["h"] == 0) and orc.status == 1
+    assert np.array_equal(orc.theta, th0) and np.array_equal(orc.lam, lam0) and orc.meta_t == 0
+    with pytest.raises(RuntimeError):
+        SamaOracle(model, th, lam).meta_grad(x, y, xm, ym)
+
+
+def test_masked_samples_are_bit_irrelevant():
+    model, x, y, xm, ym, th, lam = _tiny()
+    mask = np.ones(len(y), dtype=np.uint8); mask[[1, 7, 8]] = 0
+    mm = np.ones(len(ym), dtype=np.uint8); mm[2] = 0
+    res = []
+    for junk in (False, True):
+        x2, y2, xm2, ym2 = x.copy(), y.copy(), xm.copy(), ym.copy()
+        if junk:
+            x2[[1, 7, 8]] = 99.0; y2[[1, 7, 8]] = 0; xm2[2] = -50.0; ym2[2] = (ym2[2] + 1) % 3
+        o = SamaOracle(model, th, lam, base_lr=1e-2)
+        for _ in range(3):
+            o.base_step(x2, y2, mask)
+        res.append((o.meta_step(x2, y2, xm2, ym2, mask, mm), o))
+    assert np.array_equal(res[0][0]["h"], res[1][0]["h"]) and np.array_equal(res[0][1].theta, res[1][1].theta)
+    assert np.array_equal(res[0][1].lam, res[1][1].lam)
+
+
+def test_workload1_trajectory_runs():
+    """Workload 1 end to end, 20 meta steps at unroll 1: finite, the nudge has norm alpha, lambda moves."""
+    wl = make_workload(1)
+    model = models.make_model(wl.kind, wl.dims)
+    o = SamaOracle(model, init_theta(wl), init_lambda(wl), base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha)
+    lam0 = o.lam.copy()
+    o.base_step(wl.x_train, wl.y_train)           # a step of history so that the adaptation is non-zero
+    for s in range(wl.steps):
+        o.base_step(wl.x_train, wl.y_train)
+        r = o.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta)
+        assert np.all(np.isfinite(r["h"])) and abs(r["eps"] * np.linalg.norm(r["v"]) - wl.alpha) < 1e-12
+    assert o.meta_t == wl.steps and np.linalg.norm(o.lam - lam0) > 0
