@@ -1,0 +1,155 @@
+/*
+ * sama.h -- C ABI of the MI355X (gfx950) implementation of SAMA's per-iteration meta-gradient step
+ * ("Making Scalable Meta Learning Practical", Sec. 2-3) on the data-reweighting bilevel problem of Sec. 4.1:
+ *
+ *     base:  theta*(lambda) = argmin_theta (1/B_eff) sum_i mask_i w(l_i; lambda) l_i(theta)      (noisy batch)
+ *     meta:  lambda*        = argmin_lambda mean_j l_j(theta*(lambda))                           (clean batch)
+ *
+ * l_i is the per-sample cross-entropy of the base learner f(x_i; theta); w(.; lambda) is a 1 -> H -> 1
+ * weighting net (ReLU hidden layer, sigmoid output) applied to l_i.
+ *
+ * Conventions
+ *  - Every pointer marked DEVICE is memory of the GPU that was current at sama_init; HOST is ordinary memory.
+ *  - The library allocates no device memory: the caller hands sama_init one workspace of
+ *    sama_workspace_bytes() bytes (256-byte aligned) and keeps it alive until sama_destroy.
+ *  - All work is enqueued on the hipStream_t given to sama_init and returns without waiting for it, except
+ *    where a function says it synchronises.  Batches and outputs must stay valid until the stream has passed
+ *    the call.  Calls on one context must not overlap from several threads.
+ *  - Return value: SAMA_OK or an error detected on the host (nothing is enqueued after an error).  Conditions
+ *    only the device can see (a zero or non-finite ||v||) set a status word readable through
+ *    sama_get_state(SAMA_STATE_COUNTERS) and turn that meta step into a no-op with a zero hypergradient.
+ *
+ * Parameter layout (theta, and every theta-sized state vector), flat fp32, n = sama_param_count():
+ *    all GEMM weight matrices, each [out x in] row-major, in layer order; then every other tensor in layer order.
+ *    MLP  dims = {d0, d1, ..., dL}:    W_0[d1 x d0] ... W_{L-1}[dL x d_{L-1}],  b_0[d1] ... b_{L-1}[dL]
+ *         (two dims = multinomial logistic regression; hidden layers use ReLU)
+ *    ENCODER dims = {L, d, heads, ffn, S, V, C}  (post-LN, learned positions, erf-GELU, LN eps 1e-5,
+ *         softmax(q k^T / sqrt(d/heads)), classifier on the position-0 hidden state):
+ *         per layer l: Wqkv[3d x d] (rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V; head h owns rows h*d/heads..),
+ *                      Wo[d x d], W1[ffn x d], W2[d x ffn];
+ *         then per layer l: bqkv[3d], bo[d], ln1_g[d], ln1_b[d], b1[ffn], b2[d], ln2_g[d], ln2_b[d];
+ *         then tok_emb[V x d], pos_emb[S x d], emb_ln_g[d], emb_ln_b[d], Wc[C x d], bc[C].
+ *    sama_param_tensor() enumerates the same table.
+ * lambda layout, flat fp32, n_lambda = 3H + 1:  W1[H], b1[H], W2[H], b2[1].
+ */
+#ifndef SAMA_H
+#define SAMA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sama_ctx sama_ctx; /* opaque; owned by the library, freed by sama_destroy */
+
+typedef enum {
+  SAMA_OK = 0,
+  SAMA_EINVAL = 1,     /* bad argument or unsupported shape */
+  SAMA_ESTATE = 2,     /* call order: sama_meta_grad / sama_meta_step before any sama_base_step */
+  SAMA_EWORKSPACE = 3, /* workspace missing, misaligned or too small */
+  SAMA_EHIP = 4,       /* a HIP runtime call failed; see sama_last_error */
+  SAMA_ENONFINITE = 5  /* reserved for callers that read the device status word */
+} sama_status;
+
+enum { SAMA_MODEL_MLP = 0, SAMA_MODEL_ENCODER = 1 };
+enum { SAMA_DTYPE_FP32 = 0, SAMA_DTYPE_BF16 = 1 }; /* BF16: bf16 GEMM operands, fp32 master weights / moments / gradients */
+enum { SAMA_OPT_SGD = 0, SAMA_OPT_ADAM = 1 };
+enum { SAMA_ADAPT_OPTIMIZER = 0, SAMA_ADAPT_NONE = 1 };
+
+/* Plain data, copied by sama_init. */
+typedef struct {
+  int32_t model_kind;  /* SAMA_MODEL_* */
+  int32_t n_dims;      /* number of entries used in dims */
+  int32_t dims[8];     /* see "Parameter layout" */
+  int32_t param_dtype; /* SAMA_DTYPE_*; the encoder requires BF16, the MLP requires FP32 */
+  int32_t wnet_hidden; /* H, 1..256 */
+  int32_t base_opt;    /* SAMA_OPT_*: the base-level solver u of Sec. 2 */
+  float base_lr, beta1, beta2, adam_eps; /* gamma, beta_1, beta_2, epsilon of App. C */
+  float weight_decay;  /* L2 coefficient added to the base gradient before the solver (0 in every paper run with Adam) */
+  float meta_lr, meta_beta1, meta_beta2, meta_eps; /* Adam on lambda (Table 4) */
+  float alpha;         /* eps = alpha / ||v||_2, Sec. 3.2 below Eq. 5 */
+  int32_t adapt_mode;  /* SAMA_ADAPT_OPTIMIZER: du/dg of base_opt (App. C for Adam, gamma for SGD);
+                          SAMA_ADAPT_NONE: identity, the SAMA-NA ablation of Sec. 4.1 */
+  int32_t max_batch;      /* largest train batch that will be passed, 1..2048 */
+  int32_t max_meta_batch; /* largest meta batch, 1..2048 */
+} sama_config;
+
+/* One batch.  x: DEVICE, fp32 [n x d0] row-major (MLP) or int32 token ids [n x S] (ENCODER), ids in [0, V).
+ * y: DEVICE int32 [n], labels in [0, C).  sample_mask: DEVICE uint8 [n], 1 = use, 0 = ignore, or NULL = use all.
+ * Read-only; owned by the caller. */
+typedef struct {
+  const void* x;
+  const int32_t* y;
+  const uint8_t* sample_mask;
+  int32_t n;
+} sama_batch;
+
+/* Selectors of sama_get_state / sama_set_state.  Sizes in elements:
+ * THETA, M, V, G, GMETA, VDIR: n fp32 (M, V = Adam moments m, v of App. C; G = g_base of the last base step,
+ * Eq. 4; GMETA = dL_meta/dtheta, Eq. 1; VDIR = the perturbation vector v of Eq. 5);
+ * LAMBDA, META_M, META_V, HYPERGRAD, GLAM_PLUS, GLAM_MINUS: n_lambda fp32;
+ * COUNTERS: 4 int64 = {base step count t, meta step count, status word (0 ok, 1 = last meta step skipped), 0};
+ * SCALARS: 4 fp32 = {eps of the last meta gradient, ||v||_2, L_base of the last base step, L_meta of the last meta pass};
+ * LOSSES: max(max_batch, max_meta_batch) fp32, per-sample losses of the most recent forward pass. */
+enum {
+  SAMA_STATE_THETA = 0, SAMA_STATE_LAMBDA = 1, SAMA_STATE_M = 2, SAMA_STATE_V = 3, SAMA_STATE_G = 4,
+  SAMA_STATE_GMETA = 5, SAMA_STATE_VDIR = 6, SAMA_STATE_META_M = 7, SAMA_STATE_META_V = 8,
+  SAMA_STATE_COUNTERS = 9, SAMA_STATE_HYPERGRAD = 10, SAMA_STATE_GLAM_PLUS = 11, SAMA_STATE_GLAM_MINUS = 12,
+  SAMA_STATE_SCALARS = 13, SAMA_STATE_LOSSES = 14
+};
+
+/* Shape queries (host only, no GPU needed).  Return -1 / 0 on an invalid config. */
+int64_t sama_param_count(const sama_config* cfg);      /* n = dim theta */
+int64_t sama_gemm_param_count(const sama_config* cfg); /* leading part of theta held by GEMM weight matrices */
+int32_t sama_lambda_count(const sama_config* cfg);     /* 3H + 1 */
+int32_t sama_param_tensor_count(const sama_config* cfg);
+/* idx-th tensor of the layout table: name (<= 31 chars + NUL) copied to name_out[32], flat offset, rows, cols
+ * (cols = 1 for vectors).  SAMA_EINVAL when idx is out of range. */
+sama_status sama_param_tensor(const sama_config* cfg, int32_t idx, char* name_out, int64_t* offset,
+                              int64_t* rows, int64_t* cols);
+size_t sama_workspace_bytes(const sama_config* cfg);
+
+/* Create a context (the bilevel problem statement of Sec. 2 with the solver of Eq. 2): copies theta0 (DEVICE
+ * fp32 [n]) and lambda0 (DEVICE fp32 [n_lambda]) into the workspace, zeroes moments and counters.
+ * hip_stream: a hipStream_t (NULL = the default stream).  *out is set only on SAMA_OK. */
+sama_status sama_init(const sama_config* cfg, void* workspace /*DEVICE*/, size_t workspace_bytes,
+                      const float* theta0 /*DEVICE*/, const float* lambda0 /*DEVICE*/, void* hip_stream,
+                      sama_ctx** out);
+
+/* One step of the base solver u on L_base (Sec. 2; Sec. 4.1 objective): forward, w_i = w(l_i; lambda) held
+ * constant in the backward pass, g = dL_base/dtheta, Adam (bias-corrected) or SGD update; keeps g and the
+ * post-update moments for the adaptation of Eq. 4.  loss_out: DEVICE fp32 scalar receiving L_base, or NULL. */
+sama_status sama_base_step(sama_ctx* ctx, const sama_batch* train, float* loss_out /*DEVICE*/);
+
+/* The meta gradient of Eq. 5 at the current state:
+ *   g_meta = dL_meta/dtheta on `meta` (Eq. 1);  v = (du/dg_base) . g_meta (Eq. 4, App. C);  eps = alpha/||v||_2;
+ *   h = -(dL_base(theta + eps v, lambda)/dlambda - dL_base(theta - eps v, lambda)/dlambda) / (2 eps)
+ * with both lambda-gradients taken on `train` (the batch of the last base step).  Leaves theta, lambda and all
+ * moments unchanged.  hypergrad_out: DEVICE fp32 [n_lambda] or NULL; eps_out: DEVICE fp32 scalar or NULL.
+ * SAMA_ESTATE before the first sama_base_step. */
+sama_status sama_meta_grad(sama_ctx* ctx, const sama_batch* train, const sama_batch* meta,
+                           float* hypergrad_out /*DEVICE*/, float* eps_out /*DEVICE*/);
+
+/* sama_meta_grad, then one Adam step on lambda with h (Table 4), then theta <- theta - eps v (end of
+ * Sec. 3.2).  The base moments and step count are not touched. */
+sama_status sama_meta_step(sama_ctx* ctx, const sama_batch* train, const sama_batch* meta);
+
+/* Copy a state vector out of / into the context (DEVICE pointers; sizes above).  Enqueued on the context's
+ * stream.  sama_set_state(COUNTERS) synchronises the stream (the base step count lives on the host);
+ * setting THETA also refreshes the bf16 working copy.  SCALARS, LOSSES, HYPERGRAD, GLAM_* are read-only. */
+sama_status sama_get_state(sama_ctx* ctx, int32_t which, void* dst /*DEVICE*/);
+sama_status sama_set_state(sama_ctx* ctx, int32_t which, const void* src /*DEVICE*/);
+
+/* Text of the last error on this context (HOST string owned by the context; "" if none).  ctx may be NULL,
+ * which returns the text of the last failed sama_init on this thread. */
+const char* sama_last_error(const sama_ctx* ctx);
+
+/* Free the host-side context.  The workspace stays with the caller.  Does not synchronise. */
+void sama_destroy(sama_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMA_H */

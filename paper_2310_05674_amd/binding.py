@@ -1,0 +1,201 @@
+"""Argument marshalling for the C ABI of include/sama.h.  No arithmetic of the method happens here: torch
+supplies device memory and the current HIP stream, every step runs in the library's kernels.  There is no CPU
+fallback: without libsama.so (or without a GPU) construction fails."""
+import ctypes as C
+import os
+
+MODEL_MLP, MODEL_ENCODER = 0, 1
+DTYPE_FP32, DTYPE_BF16 = 0, 1
+OPT_SGD, OPT_ADAM = 0, 1
+ADAPT_OPTIMIZER, ADAPT_NONE = 0, 1
+STATE = dict(THETA=0, LAMBDA=1, M=2, V=3, G=4, GMETA=5, VDIR=6, META_M=7, META_V=8, COUNTERS=9, HYPERGRAD=10,
+             GLAM_PLUS=11, GLAM_MINUS=12, SCALARS=13, LOSSES=14)
+
+
+class SamaConfig(C.Structure):
+    _fields_ = [("model_kind", C.c_int32), ("n_dims", C.c_int32), ("dims", C.c_int32 * 8),
+                ("param_dtype", C.c_int32), ("wnet_hidden", C.c_int32), ("base_opt", C.c_int32),
+                ("base_lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
+                ("weight_decay", C.c_float), ("meta_lr", C.c_float), ("meta_beta1", C.c_float),
+                ("meta_beta2", C.c_float), ("meta_eps", C.c_float), ("alpha", C.c_float),
+                ("adapt_mode", C.c_int32), ("max_batch", C.c_int32), ("max_meta_batch", C.c_int32)]
+
+    @classmethod
+    def make(cls, kind, dims, *, H, max_batch, max_meta_batch, base_opt=OPT_ADAM, base_lr=1e-3, beta1=0.9,
+             beta2=0.999, adam_eps=1e-8, weight_decay=0.0, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999,
+             meta_eps=1e-8, alpha=1.0, adapt_mode=ADAPT_OPTIMIZER, bf16=None):
+        c = cls()
+        c.model_kind = MODEL_MLP if kind == "mlp" else MODEL_ENCODER
+        c.n_dims = len(dims)
+        for i, d in enumerate(dims):
+            c.dims[i] = int(d)
+        if bf16 is None:
+            bf16 = kind == "encoder"
+        c.param_dtype = DTYPE_BF16 if bf16 else DTYPE_FP32
+        c.wnet_hidden = H
+        c.base_opt, c.base_lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay = base_opt, base_lr, beta1, beta2, adam_eps, weight_decay
+        c.meta_lr, c.meta_beta1, c.meta_beta2, c.meta_eps = meta_lr, meta_beta1, meta_beta2, meta_eps
+        c.alpha, c.adapt_mode, c.max_batch, c.max_meta_batch = alpha, adapt_mode, max_batch, max_meta_batch
+        return c
+
+
+class SamaBatch(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("y", C.c_void_p), ("sample_mask", C.c_void_p), ("n", C.c_int32)]
+
+
+class SamaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libsama error {code}: {msg}")
+        self.code = code
+
+
+def lib_path():
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsama.so")
+
+
+_lib = None
+
+
+def load_library():
+    """dlopen the in-tree libsama.so and declare the prototypes of include/sama.h.  Raises if it is not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    p = lib_path()
+    if not os.path.exists(p):
+        raise FileNotFoundError(f"{p} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    L = C.CDLL(p)
+    cfgp = C.POINTER(SamaConfig)
+    L.sama_param_count.restype = C.c_int64; L.sama_param_count.argtypes = [cfgp]
+    L.sama_gemm_param_count.restype = C.c_int64; L.sama_gemm_param_count.argtypes = [cfgp]
+    L.sama_lambda_count.restype = C.c_int32; L.sama_lambda_count.argtypes = [cfgp]
+    L.sama_param_tensor_count.restype = C.c_int32; L.sama_param_tensor_count.argtypes = [cfgp]
+    L.sama_param_tensor.restype = C.c_int; L.sama_param_tensor.argtypes = [cfgp, C.c_int32, C.c_char_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.sama_workspace_bytes.restype = C.c_size_t; L.sama_workspace_bytes.argtypes = [cfgp]
+    L.sama_init.restype = C.c_int; L.sama_init.argtypes = [cfgp, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]
+    bp = C.POINTER(SamaBatch)
+    L.sama_base_step.restype = C.c_int; L.sama_base_step.argtypes = [C.c_void_p, bp, C.c_void_p]
+    L.sama_meta_grad.restype = C.c_int; L.sama_meta_grad.argtypes = [C.c_void_p, bp, bp, C.c_void_p, C.c_void_p]
+    L.sama_meta_step.restype = C.c_int; L.sama_meta_step.argtypes = [C.c_void_p, bp, bp]
+    L.sama_get_state.restype = C.c_int; L.sama_get_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    L.sama_set_state.restype = C.c_int; L.sama_set_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    L.sama_last_error.restype = C.c_char_p; L.sama_last_error.argtypes = [C.c_void_p]
+    L.sama_destroy.restype = None; L.sama_destroy.argtypes = [C.c_void_p]
+    _lib = L
+    return L
+
+
+def param_tensors(cfg):
+    """[(name, offset, rows, cols)] as the library lays theta out."""
+    L = load_library()
+    out = []
+    for i in range(L.sama_param_tensor_count(C.byref(cfg))):
+        name = C.create_string_buffer(32)
+        off, r, c = C.c_int64(), C.c_int64(), C.c_int64()
+        rc = L.sama_param_tensor(C.byref(cfg), i, name, C.byref(off), C.byref(r), C.byref(c))
+        if rc != 0:
+            raise SamaError(rc, L.sama_last_error(None).decode())
+        out.append((name.value.decode(), off.value, r.value, c.value))
+    return out
+
+
+class Sama:
+    """One SAMA context on the current CUDA(HIP) device and torch's current stream."""
+
+    def __init__(self, cfg, theta0, lambda0):
+        import torch
+        self.torch = torch
+        self.lib = load_library()
+        if not torch.cuda.is_available():
+            raise RuntimeError("libsama needs a GPU: there is no CPU path")
+        self.cfg = cfg
+        self.n = self.lib.sama_param_count(C.byref(cfg))
+        self.nl = self.lib.sama_lambda_count(C.byref(cfg))
+        nbytes = self.lib.sama_workspace_bytes(C.byref(cfg))
+        if self.n < 0 or nbytes == 0:
+            raise SamaError(1, self.lib.sama_last_error(None).decode())
+        self.dev = torch.device("cuda", torch.cuda.current_device())
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.dev)
+        base = (self.workspace.data_ptr() + 255) & ~255
+        th = self._dev_f32(theta0, self.n)
+        lam = self._dev_f32(lambda0, self.nl)
+        self.stream = torch.cuda.current_stream(self.dev)
+        h = C.c_void_p()
+        rc = self.lib.sama_init(C.byref(cfg), base, nbytes, th.data_ptr(), lam.data_ptr(), self.stream.cuda_stream, C.byref(h))
+        if rc != 0:
+            raise SamaError(rc, self.lib.sama_last_error(None).decode())
+        self.h = h
+        self._keep = [th, lam]
+        self.max_b = max(cfg.max_batch, cfg.max_meta_batch)
+
+    def _dev_f32(self, a, count):
+        torch = self.torch
+        t = a if isinstance(a, torch.Tensor) else torch.as_tensor(a)
+        t = t.to(device=self.dev, dtype=torch.float32).contiguous()
+        if t.numel() != count:
+            raise ValueError(f"expected {count} elements, got {t.numel()}")
+        return t
+
+    def _check(self, rc):
+        if rc != 0:
+            raise SamaError(rc, self.lib.sama_last_error(self.h).decode())
+
+    def batch(self, x, y, mask=None):
+        """Device tensors (x fp32 [n, d0] or int32 [n, S]; y int32 [n]; mask uint8 [n] or None) -> sama_batch."""
+        torch = self.torch
+        assert x.is_cuda and y.is_cuda and x.is_contiguous() and y.dtype == torch.int32
+        assert x.dtype in (torch.float32, torch.int32)
+        b = SamaBatch(x.data_ptr(), y.data_ptr(), None if mask is None else mask.data_ptr(), int(y.numel()))
+        b._keep = (x, y, mask)
+        if mask is not None:
+            assert mask.dtype == torch.uint8 and mask.is_cuda and mask.numel() == y.numel()
+        return b
+
+    def base_step(self, train, loss_out=None):
+        self._check(self.lib.sama_base_step(self.h, C.byref(train), None if loss_out is None else loss_out.data_ptr()))
+
+    def meta_grad(self, train, meta, hypergrad_out=None, eps_out=None):
+        self._check(self.lib.sama_meta_grad(self.h, C.byref(train), C.byref(meta),
+                                            None if hypergrad_out is None else hypergrad_out.data_ptr(),
+                                            None if eps_out is None else eps_out.data_ptr()))
+
+    def meta_step(self, train, meta):
+        self._check(self.lib.sama_meta_step(self.h, C.byref(train), C.byref(meta)))
+
+    def get_state(self, name):
+        torch = self.torch
+        which = STATE[name]
+        if name == "COUNTERS":
+            out = torch.empty(4, dtype=torch.int64, device=self.dev)
+        elif name == "SCALARS":
+            out = torch.empty(4, dtype=torch.float32, device=self.dev)
+        elif name == "LOSSES":
+            out = torch.empty(self.max_b, dtype=torch.float32, device=self.dev)
+        elif name in ("LAMBDA", "META_M", "META_V", "HYPERGRAD", "GLAM_PLUS", "GLAM_MINUS"):
+            out = torch.empty(self.nl, dtype=torch.float32, device=self.dev)
+        else:
+            out = torch.empty(self.n, dtype=torch.float32, device=self.dev)
+        self._check(self.lib.sama_get_state(self.h, which, out.data_ptr()))
+        return out
+
+    def set_state(self, name, value):
+        torch = self.torch
+        if name == "COUNTERS":
+            t = torch.as_tensor(value).to(device=self.dev, dtype=torch.int64).contiguous()
+            assert t.numel() == 4
+        else:
+            t = self._dev_f32(value, self.nl if name in ("LAMBDA", "META_M", "META_V") else self.n)
+        self._check(self.lib.sama_set_state(self.h, STATE[name], t.data_ptr()))
+        self.stream.synchronize()      # `t` may be freed once we return
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.torch.cuda.synchronize(self.dev)
+            self.lib.sama_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

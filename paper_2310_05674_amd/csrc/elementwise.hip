@@ -1,0 +1,298 @@
+// The HBM-bound elementwise chain of one SAMA iteration over the n base parameters:
+//   base solver update (Adam / SGD)                                  -- Sec. 2, Kingma & Ba Alg. 1
+//   adaptation v = (du/dg) . dL_meta/dtheta fused with ||v||^2       -- Eq. 4-5, App. C
+//   eps = alpha / ||v||_2                                            -- below Eq. 5
+//   low-order halves of theta +- eps v for the two extra passes      -- Eq. 5
+//   nudge theta <- theta - eps v                                     -- end of Sec. 3.2
+// Each kernel streams every array exactly once with 16-byte accesses; nothing is re-read.
+#include "common.h"
+#include "kernels.h"
+
+namespace sama {
+
+namespace {
+constexpr int EW_THREADS = 256;
+constexpr int EW_VEC = 4;
+
+inline int ew_grid(int64_t n) {
+  int64_t b = (n + (int64_t)EW_THREADS * EW_VEC - 1) / ((int64_t)EW_THREADS * EW_VEC);
+  if (b < 1) b = 1;
+  if (b > EW_MAX_BLOCKS) b = EW_MAX_BLOCKS;
+  return (int)b;
+}
+
+__device__ __forceinline__ void store_bf16x4(bf16_t* p, float a, float b, float c, float d) {
+  uint2 pk;
+  pk.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  pk.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+  *reinterpret_cast<uint2*>(p) = pk;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Adam: m' = b1 m + (1-b1) g ; v' = b2 v + (1-b2) g^2 ; theta' = theta - lr c1 m' / (c2 sqrt(v') + eps)
+// with c1 = 1/(1-b1^t), c2 = 1/sqrt(1-b2^t) computed on the host in double.  Optionally refreshes the bf16
+// working copy of the first n16 elements (the GEMM weight matrices).
+__device__ __forceinline__ void adam_one(float g, float& m, float& v, float& th, const AdamArgs& a) {
+  g = fmaf(a.weight_decay, th, g);
+  m = fmaf(a.beta1, m, a.one_m_beta1 * g);
+  v = fmaf(a.beta2, v, a.one_m_beta2 * g * g);
+  th = th - a.lr_c1 * m / (fmaf(a.c2, sqrtf(v), a.eps));
+}
+
+__global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g, float* __restrict__ m,
+                                                     float* __restrict__ v, float* __restrict__ theta,
+                                                     bf16_t* __restrict__ theta16, int64_t n, int64_t n16,
+                                                     AdamArgs a) {
+  const int64_t nv = n / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) {
+    float4 g4 = reinterpret_cast<const float4*>(g)[i];
+    float4 m4 = reinterpret_cast<float4*>(m)[i];
+    float4 v4 = reinterpret_cast<float4*>(v)[i];
+    float4 t4 = reinterpret_cast<float4*>(theta)[i];
+    adam_one(g4.x, m4.x, v4.x, t4.x, a);
+    adam_one(g4.y, m4.y, v4.y, t4.y, a);
+    adam_one(g4.z, m4.z, v4.z, t4.z, a);
+    adam_one(g4.w, m4.w, v4.w, t4.w, a);
+    reinterpret_cast<float4*>(m)[i] = m4;
+    reinterpret_cast<float4*>(v)[i] = v4;
+    reinterpret_cast<float4*>(theta)[i] = t4;
+    if (theta16 != nullptr && i * EW_VEC + EW_VEC <= n16) store_bf16x4(theta16 + i * EW_VEC, t4.x, t4.y, t4.z, t4.w);
+    else if (theta16 != nullptr && i * EW_VEC < n16) {
+      const float t[4] = {t4.x, t4.y, t4.z, t4.w};
+      for (int e = 0; e < EW_VEC; ++e)
+        if (i * EW_VEC + e < n16) theta16[i * EW_VEC + e] = f32_to_bf16(t[e]);
+    }
+  }
+  // ragged tail (n not a multiple of 4)
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n) {
+    float mm = m[k], vv = v[k], tt = theta[k];
+    adam_one(g[k], mm, vv, tt, a);
+    m[k] = mm; v[k] = vv; theta[k] = tt;
+    if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(tt);
+  }
+}
+
+// SGD: theta' = theta - lr (g + wd theta)
+__global__ __launch_bounds__(EW_THREADS) void k_sgd(const float* __restrict__ g, float* __restrict__ theta,
+                                                    bf16_t* __restrict__ theta16, int64_t n, int64_t n16, float lr,
+                                                    float wd) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride) {
+    float t = theta[k];
+    t = t - lr * fmaf(wd, t, g[k]);
+    theta[k] = t;
+    if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(t);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Adaptation fused with the squared norm.  mode 0: Adam, D = lr c1 c2 [(1-b1) v' - (1-b2) m' g] / [s (c2 s + eps)^2],
+// s = sqrt(v'), D = 0 where s = 0 (m', v' are the moments after the step that consumed g; the eps term of the
+// numerator is dropped as in App. C).  mode 1: D = scalar (lr for SGD, 1 for SAMA-NA).
+__device__ __forceinline__ float adapt_one(float g, float m, float v, float gm, const AdaptArgs& a) {
+  if (a.mode != 0) return a.scalar * gm;
+  const float s = sqrtf(v);
+  const float num = a.one_m_beta1 * v - a.one_m_beta2 * m * g;
+  const float q = fmaf(a.c2, s, a.eps);
+  const float D = s > 0.f ? a.lr_c1_c2 * num / (s * q * q) : 0.f;
+  return D * gm;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void k_adapt_norm(const float* __restrict__ g, const float* __restrict__ m,
+                                                           const float* __restrict__ v, const float* __restrict__ gmeta,
+                                                           float* __restrict__ vdir, double* __restrict__ partial,
+                                                           int64_t n, AdaptArgs a) {
+  __shared__ float red[16];
+  const int64_t nv = n / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  float acc = 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) {
+    float4 gm4 = reinterpret_cast<const float4*>(gmeta)[i];
+    float4 o;
+    if (a.mode == 0) {
+      float4 g4 = reinterpret_cast<const float4*>(g)[i];
+      float4 m4 = reinterpret_cast<const float4*>(m)[i];
+      float4 v4 = reinterpret_cast<const float4*>(v)[i];
+      o.x = adapt_one(g4.x, m4.x, v4.x, gm4.x, a);
+      o.y = adapt_one(g4.y, m4.y, v4.y, gm4.y, a);
+      o.z = adapt_one(g4.z, m4.z, v4.z, gm4.z, a);
+      o.w = adapt_one(g4.w, m4.w, v4.w, gm4.w, a);
+    } else {
+      o.x = a.scalar * gm4.x; o.y = a.scalar * gm4.y; o.z = a.scalar * gm4.z; o.w = a.scalar * gm4.w;
+    }
+    reinterpret_cast<float4*>(vdir)[i] = o;
+    acc = fmaf(o.x, o.x, acc); acc = fmaf(o.y, o.y, acc); acc = fmaf(o.z, o.z, acc); acc = fmaf(o.w, o.w, acc);
+  }
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n) {
+    const float o = a.mode == 0 ? adapt_one(g[k], m[k], v[k], gmeta[k], a) : a.scalar * gmeta[k];
+    vdir[k] = o;
+    acc = fmaf(o, o, acc);
+  }
+  const float s = block_sum(acc, red);
+  if (threadIdx.x == 0) partial[blockIdx.x] = (double)s;
+}
+
+// Second stage: fixed-order sum of the per-block partials in double, eps = alpha / ||v||.
+// scalars[0] = eps, scalars[1] = ||v||.  A zero or non-finite norm gives eps = 0 and raises status[0] = 1
+// (status is cleared to 0 otherwise), which turns the rest of the meta step into a no-op.
+__global__ __launch_bounds__(256) void k_eps_from_partials(const double* __restrict__ partial, int nparts, float alpha,
+                                                           float* __restrict__ scalars, int64_t* __restrict__ status) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < nparts; i += 256) s += partial[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double nrm = sqrt(red[0]);
+    const bool ok = (nrm > 0.0) && (nrm < 1e300) && (nrm == nrm);
+    const float eps = ok ? (float)((double)alpha / nrm) : 0.f;
+    const bool ok2 = ok && eps > 0.f && eps < 3.0e38f;
+    scalars[0] = ok2 ? eps : 0.f;
+    scalars[1] = (float)nrm;
+    status[0] = ok2 ? 0 : 1;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Low-order halves for the +-eps v passes: lo+-[k] = bf16((theta[k] +- eps v[k]) - float(bf16(theta[k]))).
+// The GEMMs of those passes contract with hi + lo, hi = the bf16 working copy, so the perturbation survives
+// even where eps |v| is far below one bf16 ulp of theta.
+__global__ __launch_bounds__(EW_THREADS) void k_perturb_lo(const float* __restrict__ theta, const float* __restrict__ vdir,
+                                                           const float* __restrict__ eps_ptr, bf16_t* __restrict__ lo_p,
+                                                           bf16_t* __restrict__ lo_m, int64_t n16) {
+  const float eps = *eps_ptr;
+  const int64_t nv = n16 / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) {
+    const float4 t4 = reinterpret_cast<const float4*>(theta)[i];
+    const float4 v4 = reinterpret_cast<const float4*>(vdir)[i];
+    const float t[4] = {t4.x, t4.y, t4.z, t4.w}, vv[4] = {v4.x, v4.y, v4.z, v4.w};
+    float p[4], q[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float hi = bf16_to_f32(f32_to_bf16(t[e]));
+      p[e] = fmaf(eps, vv[e], t[e]) - hi;
+      q[e] = fmaf(-eps, vv[e], t[e]) - hi;
+    }
+    store_bf16x4(lo_p + i * EW_VEC, p[0], p[1], p[2], p[3]);
+    store_bf16x4(lo_m + i * EW_VEC, q[0], q[1], q[2], q[3]);
+  }
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n16) {
+    const float hi = bf16_to_f32(f32_to_bf16(theta[k]));
+    lo_p[k] = f32_to_bf16(fmaf(eps, vdir[k], theta[k]) - hi);
+    lo_m[k] = f32_to_bf16(fmaf(-eps, vdir[k], theta[k]) - hi);
+  }
+}
+
+// theta <- theta - eps v (and the bf16 working copy).  eps = 0 (a skipped step) leaves everything as it is.
+__global__ __launch_bounds__(EW_THREADS) void k_nudge(float* __restrict__ theta, const float* __restrict__ vdir,
+                                                      const float* __restrict__ eps_ptr, bf16_t* __restrict__ theta16,
+                                                      int64_t n, int64_t n16) {
+  const float eps = *eps_ptr;
+  if (eps == 0.f) return;
+  const int64_t nv = n / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) {
+    float4 t4 = reinterpret_cast<float4*>(theta)[i];
+    const float4 v4 = reinterpret_cast<const float4*>(vdir)[i];
+    t4.x = fmaf(-eps, v4.x, t4.x); t4.y = fmaf(-eps, v4.y, t4.y);
+    t4.z = fmaf(-eps, v4.z, t4.z); t4.w = fmaf(-eps, v4.w, t4.w);
+    reinterpret_cast<float4*>(theta)[i] = t4;
+    if (theta16 != nullptr && i * EW_VEC + EW_VEC <= n16) store_bf16x4(theta16 + i * EW_VEC, t4.x, t4.y, t4.z, t4.w);
+    else if (theta16 != nullptr && i * EW_VEC < n16) {
+      const float t[4] = {t4.x, t4.y, t4.z, t4.w};
+      for (int e = 0; e < EW_VEC; ++e)
+        if (i * EW_VEC + e < n16) theta16[i * EW_VEC + e] = f32_to_bf16(t[e]);
+    }
+  }
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n) {
+    const float t = fmaf(-eps, vdir[k], theta[k]);
+    theta[k] = t;
+    if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(t);
+  }
+}
+
+__global__ __launch_bounds__(EW_THREADS) void k_fill_f32(float* __restrict__ p, float val, int64_t n) {
+  const int64_t nv = n / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const float4 v4 = make_float4(val, val, val, val);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) reinterpret_cast<float4*>(p)[i] = v4;
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n) p[k] = val;
+}
+
+__global__ __launch_bounds__(EW_THREADS) void k_copy_f32(float* __restrict__ dst, const float* __restrict__ src, int64_t n) {
+  const int64_t nv = n / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride)
+    reinterpret_cast<float4*>(dst)[i] = reinterpret_cast<const float4*>(src)[i];
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n) dst[k] = src[k];
+}
+
+__global__ __launch_bounds__(EW_THREADS) void k_to_bf16(bf16_t* __restrict__ dst, const float* __restrict__ src, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride) dst[k] = f32_to_bf16(src[k]);
+}
+
+__global__ void k_fill_i64(int64_t* p, int64_t a, int64_t b, int64_t c, int64_t d, int mask) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    if (mask & 1) p[0] = a;
+    if (mask & 2) p[1] = b;
+    if (mask & 4) p[2] = c;
+    if (mask & 8) p[3] = d;
+  }
+}
+}  // namespace
+
+void launch_adam(hipStream_t st, const float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n,
+                 int64_t n16, const AdamArgs& a) {
+  if (n <= 0) return;
+  k_adam<<<ew_grid(n), EW_THREADS, 0, st>>>(g, m, v, theta, theta16, n, n16, a);
+}
+void launch_sgd(hipStream_t st, const float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd) {
+  if (n <= 0) return;
+  k_sgd<<<ew_grid(n), EW_THREADS, 0, st>>>(g, theta, theta16, n, n16, lr, wd);
+}
+void launch_adapt_norm(hipStream_t st, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
+                       double* partial, int64_t n, const AdaptArgs& a, float alpha, float* scalars, int64_t* status) {
+  const int grid = ew_grid(n);
+  k_adapt_norm<<<grid, EW_THREADS, 0, st>>>(g, m, v, gmeta, vdir, partial, n, a);
+  k_eps_from_partials<<<1, 256, 0, st>>>(partial, grid, alpha, scalars, status);
+}
+void launch_perturb_lo(hipStream_t st, const float* theta, const float* vdir, const float* eps_ptr, bf16_t* lo_p,
+                       bf16_t* lo_m, int64_t n16) {
+  if (n16 <= 0) return;
+  k_perturb_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, lo_p, lo_m, n16);
+}
+void launch_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, int64_t n,
+                  int64_t n16) {
+  if (n <= 0) return;
+  k_nudge<<<ew_grid(n), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, theta16, n, n16);
+}
+void launch_fill_f32(hipStream_t st, float* p, float val, int64_t n) {
+  if (n <= 0) return;
+  k_fill_f32<<<ew_grid(n), EW_THREADS, 0, st>>>(p, val, n);
+}
+void launch_copy_f32(hipStream_t st, float* dst, const float* src, int64_t n) {
+  if (n <= 0) return;
+  k_copy_f32<<<ew_grid(n), EW_THREADS, 0, st>>>(dst, src, n);
+}
+void launch_to_bf16(hipStream_t st, bf16_t* dst, const float* src, int64_t n) {
+  if (n <= 0) return;
+  k_to_bf16<<<ew_grid(n * EW_VEC), EW_THREADS, 0, st>>>(dst, src, n);
+}
+void launch_fill_i64x4(hipStream_t st, int64_t* p, int64_t a, int64_t b, int64_t c, int64_t d, int mask) {
+  k_fill_i64<<<1, 64, 0, st>>>(p, a, b, c, d, mask);
+}
+
+}  // namespace sama

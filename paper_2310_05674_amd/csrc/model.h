@@ -1,0 +1,64 @@
+// Base-learner interface used by the SAMA driver: explicit forward / backward kernel sequences, no autograd.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+#include "../../include/sama.h"
+#include "common.h"
+
+namespace sama {
+
+struct TensorInfo {
+  std::string name;
+  int64_t offset, rows, cols;
+  bool is_matrix;  // a GEMM weight (leading part of theta)
+};
+
+// Builds the flat layout table documented in include/sama.h.  Returns false on an invalid config.
+bool build_layout(const sama_config& cfg, std::vector<TensorInfo>& out, int64_t& n, int64_t& n_gemm, std::string& err);
+
+// How one pass sees theta.  Non-GEMM tensors: theta[k] + sign * eps * vdir[k].  GEMM weights: fp32 models read
+// theta + sign*eps*vdir inside the GEMM loader; bf16 models contract with hi (+ lo when perturbed).
+struct PassWeights {
+  const float* theta;
+  const float* vdir;
+  const float* eps_ptr;
+  float sign;  // 0 = unperturbed
+  const bf16_t* hi;
+  const bf16_t* lo;  // null when unperturbed
+};
+
+class BumpAlloc {  // carves 256-byte aligned pieces out of the caller's workspace (base may be null to measure)
+ public:
+  explicit BumpAlloc(void* base) : base_((char*)base), off_(0) {}
+  template <typename T>
+  T* take(size_t count) {
+    size_t bytes = (count * sizeof(T) + 255) & ~(size_t)255;
+    T* p = base_ ? (T*)(base_ + off_) : nullptr;
+    off_ += bytes;
+    return p;
+  }
+  size_t used() const { return off_; }
+
+ private:
+  char* base_;
+  size_t off_;
+};
+
+class Model {
+ public:
+  virtual ~Model() {}
+  // carve activation buffers for batches up to max_b
+  virtual void plan(BumpAlloc& ws, int max_b) = 0;
+  // logits[B x C] (fp32, row stride C) for batch `b`; keep = retain what backward needs
+  virtual void forward(hipStream_t st, const PassWeights& w, const sama_batch& b, bool keep, float* logits) = 0;
+  // grad[n] = d/dtheta sum_i sum_c dlogits[i][c] z_ic, at the unperturbed theta of the last keep=true forward
+  virtual void backward(hipStream_t st, const PassWeights& w, const sama_batch& b, const float* dlogits, float* grad) = 0;
+  virtual int n_classes() const = 0;
+};
+
+Model* make_mlp(const sama_config& cfg, const std::vector<TensorInfo>& layout);
+Model* make_encoder(const sama_config& cfg, const std::vector<TensorInfo>& layout, std::string& err);
+
+}  // namespace sama

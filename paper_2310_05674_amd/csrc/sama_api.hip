@@ -1,0 +1,378 @@
+// C ABI of libsama (include/sama.h): context, workspace carving, and the kernel sequence of one SAMA
+// iteration (Sec. 3.2, Eq. 5; workflow of Fig. 2) on one HIP stream.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+#include <memory>
+#include "kernels.h"
+#include "model.h"
+
+using namespace sama;
+
+namespace sama {
+
+bool build_layout(const sama_config& c, std::vector<TensorInfo>& out, int64_t& n, int64_t& n_gemm, std::string& err) {
+  out.clear();
+  std::vector<TensorInfo> mats, vecs;
+  auto M = [&](const std::string& nm, int64_t r, int64_t cc) { mats.push_back({nm, 0, r, cc, true}); };
+  auto V = [&](const std::string& nm, int64_t r, int64_t cc) { vecs.push_back({nm, 0, r, cc, false}); };
+  if (c.model_kind == SAMA_MODEL_MLP) {
+    if (c.n_dims < 2 || c.n_dims > 8) { err = "MLP needs 2..8 dims"; return false; }
+    for (int i = 0; i < c.n_dims; ++i)
+      if (c.dims[i] < 1) { err = "MLP widths must be positive"; return false; }
+    if (c.dims[c.n_dims - 1] < 2 || c.dims[c.n_dims - 1] > 64) { err = "class count must be 2..64"; return false; }
+    for (int l = 0; l + 1 < c.n_dims; ++l) {
+      M("W" + std::to_string(l), c.dims[l + 1], c.dims[l]);
+      V("b" + std::to_string(l), c.dims[l + 1], 1);
+    }
+  } else if (c.model_kind == SAMA_MODEL_ENCODER) {
+    if (c.n_dims != 7) { err = "ENCODER needs dims = {L, d, heads, ffn, S, V, C}"; return false; }
+    const int64_t L = c.dims[0], d = c.dims[1], heads = c.dims[2], ffn = c.dims[3], S = c.dims[4], Vv = c.dims[5], C = c.dims[6];
+    if (L < 1 || d < 1 || heads < 1 || ffn < 1 || S < 1 || Vv < 1 || C < 2 || C > 64 || d % heads != 0) {
+      err = "bad ENCODER dims"; return false;
+    }
+    for (int64_t l = 0; l < L; ++l) {
+      const std::string p = "l" + std::to_string(l) + ".";
+      M(p + "Wqkv", 3 * d, d); M(p + "Wo", d, d); M(p + "W1", ffn, d); M(p + "W2", d, ffn);
+      V(p + "bqkv", 3 * d, 1); V(p + "bo", d, 1); V(p + "ln1_g", d, 1); V(p + "ln1_b", d, 1);
+      V(p + "b1", ffn, 1); V(p + "b2", d, 1); V(p + "ln2_g", d, 1); V(p + "ln2_b", d, 1);
+    }
+    V("tok_emb", Vv, d); V("pos_emb", S, d); V("emb_ln_g", d, 1); V("emb_ln_b", d, 1); V("Wc", C, d); V("bc", C, 1);
+  } else {
+    err = "unknown model_kind"; return false;
+  }
+  int64_t off = 0;
+  for (auto& t : mats) { t.offset = off; off += t.rows * t.cols; out.push_back(t); }
+  n_gemm = off;
+  for (auto& t : vecs) { t.offset = off; off += t.rows * t.cols; out.push_back(t); }
+  n = off;
+  return true;
+}
+
+}  // namespace sama
+
+struct sama_ctx {
+  sama_config cfg;
+  hipStream_t stream;
+  std::vector<TensorInfo> layout;
+  int64_t n, n_gemm;
+  int nl;
+  bool bf16;
+  std::unique_ptr<Model> model;
+  // device state (inside the caller's workspace)
+  float *theta, *m, *v, *g, *gmeta, *vdir;
+  bf16_t *theta16, *lo_p, *lo_m;
+  float *lambda, *meta_m, *meta_v, *hyper, *glam_p32, *glam_m32;
+  double *glam_p, *glam_m, *partial;
+  float* scalars;     // {eps, ||v||, L_base, L_meta}
+  int64_t* counters;  // {t (mirror), meta_t, status, 0}
+  float *logits, *dlogits, *losses;
+  int64_t t;  // base step count (host)
+  std::string err;
+};
+
+static thread_local std::string g_init_err;
+
+static bool validate(const sama_config* c, std::string& err) {
+  if (!c) { err = "null config"; return false; }
+  std::vector<TensorInfo> lay; int64_t n, ng;
+  if (!build_layout(*c, lay, n, ng, err)) return false;
+  if (c->wnet_hidden < 1 || c->wnet_hidden > MAX_WNET_HIDDEN) { err = "wnet_hidden must be 1..256"; return false; }
+  if (c->max_batch < 1 || c->max_batch > MAX_BATCH || c->max_meta_batch < 1 || c->max_meta_batch > MAX_BATCH) {
+    err = "max_batch / max_meta_batch must be 1..2048"; return false;
+  }
+  if (c->model_kind == SAMA_MODEL_MLP && c->param_dtype != SAMA_DTYPE_FP32) { err = "the MLP runs in fp32"; return false; }
+  if (c->model_kind == SAMA_MODEL_ENCODER && c->param_dtype != SAMA_DTYPE_BF16) { err = "the encoder runs in bf16"; return false; }
+  if (c->base_opt != SAMA_OPT_SGD && c->base_opt != SAMA_OPT_ADAM) { err = "unknown base_opt"; return false; }
+  if (c->adapt_mode != SAMA_ADAPT_OPTIMIZER && c->adapt_mode != SAMA_ADAPT_NONE) { err = "unknown adapt_mode"; return false; }
+  if (!(c->base_lr > 0.f) || !(c->meta_lr > 0.f) || !(c->alpha > 0.f)) { err = "base_lr, meta_lr, alpha must be > 0"; return false; }
+  if (!(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f && c->meta_beta1 >= 0.f &&
+        c->meta_beta1 < 1.f && c->meta_beta2 >= 0.f && c->meta_beta2 < 1.f)) { err = "betas must be in [0, 1)"; return false; }
+  if (c->adam_eps < 0.f || c->meta_eps < 0.f || c->weight_decay < 0.f) { err = "negative eps / weight_decay"; return false; }
+  return true;
+}
+
+// Carves the workspace; with ctx->* pointers null-based when base == nullptr (size query).
+static size_t carve(sama_ctx* c, void* base) {
+  BumpAlloc ws(base);
+  const int64_t n = c->n, ng = c->n_gemm;
+  const int nl = c->nl;
+  c->theta = ws.take<float>(n); c->m = ws.take<float>(n); c->v = ws.take<float>(n);
+  c->g = ws.take<float>(n); c->gmeta = ws.take<float>(n); c->vdir = ws.take<float>(n);
+  if (c->bf16) { c->theta16 = ws.take<bf16_t>(ng); c->lo_p = ws.take<bf16_t>(ng); c->lo_m = ws.take<bf16_t>(ng); }
+  else { c->theta16 = c->lo_p = c->lo_m = nullptr; }
+  c->lambda = ws.take<float>(nl); c->meta_m = ws.take<float>(nl); c->meta_v = ws.take<float>(nl);
+  c->hyper = ws.take<float>(nl); c->glam_p32 = ws.take<float>(nl); c->glam_m32 = ws.take<float>(nl);
+  c->glam_p = ws.take<double>(nl); c->glam_m = ws.take<double>(nl);
+  c->partial = ws.take<double>(EW_MAX_BLOCKS);
+  c->scalars = ws.take<float>(4);
+  c->counters = ws.take<int64_t>(4);
+  const int mb = c->cfg.max_batch > c->cfg.max_meta_batch ? c->cfg.max_batch : c->cfg.max_meta_batch;
+  const int C = c->cfg.dims[c->cfg.n_dims - 1];
+  c->logits = ws.take<float>((size_t)mb * C); c->dlogits = ws.take<float>((size_t)mb * C);
+  c->losses = ws.take<float>(mb);
+  if (c->model) c->model->plan(ws, mb);
+  return ws.used();
+}
+
+static sama_ctx* make_host_ctx(const sama_config* cfg, std::string& err) {
+  if (!validate(cfg, err)) return nullptr;
+  std::unique_ptr<sama_ctx> c(new sama_ctx());
+  c->cfg = *cfg;
+  build_layout(*cfg, c->layout, c->n, c->n_gemm, err);
+  c->nl = 3 * cfg->wnet_hidden + 1;
+  c->bf16 = cfg->param_dtype == SAMA_DTYPE_BF16;
+  if (cfg->model_kind == SAMA_MODEL_MLP) c->model.reset(make_mlp(*cfg, c->layout));
+  else c->model.reset(make_encoder(*cfg, c->layout, err));
+  if (!c->model) return nullptr;
+  c->t = 0;
+  c->stream = nullptr;
+  return c.release();
+}
+
+static sama_status fail(sama_ctx* c, sama_status s, const std::string& msg) {
+  if (c) c->err = msg; else g_init_err = msg;
+  return s;
+}
+static sama_status check_hip(sama_ctx* c, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, SAMA_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+  return SAMA_OK;
+}
+static sama_status check_batch(sama_ctx* c, const sama_batch* b, int maxb, const char* nm) {
+  if (!b || !b->x || !b->y) return fail(c, SAMA_EINVAL, std::string(nm) + ": null batch / x / y");
+  if (b->n < 1 || b->n > maxb) return fail(c, SAMA_EINVAL, std::string(nm) + ": batch size outside 1..max_batch");
+  return SAMA_OK;
+}
+
+extern "C" {
+
+int64_t sama_param_count(const sama_config* cfg) {
+  std::string e; std::vector<TensorInfo> l; int64_t n, ng;
+  if (!cfg || !build_layout(*cfg, l, n, ng, e)) return -1;
+  return n;
+}
+int64_t sama_gemm_param_count(const sama_config* cfg) {
+  std::string e; std::vector<TensorInfo> l; int64_t n, ng;
+  if (!cfg || !build_layout(*cfg, l, n, ng, e)) return -1;
+  return ng;
+}
+int32_t sama_lambda_count(const sama_config* cfg) {
+  if (!cfg || cfg->wnet_hidden < 1 || cfg->wnet_hidden > MAX_WNET_HIDDEN) return 0;
+  return 3 * cfg->wnet_hidden + 1;
+}
+int32_t sama_param_tensor_count(const sama_config* cfg) {
+  std::string e; std::vector<TensorInfo> l; int64_t n, ng;
+  if (!cfg || !build_layout(*cfg, l, n, ng, e)) return 0;
+  return (int32_t)l.size();
+}
+sama_status sama_param_tensor(const sama_config* cfg, int32_t idx, char* name_out, int64_t* offset, int64_t* rows,
+                              int64_t* cols) {
+  std::string e; std::vector<TensorInfo> l; int64_t n, ng;
+  if (!cfg || !build_layout(*cfg, l, n, ng, e)) return fail(nullptr, SAMA_EINVAL, e);
+  if (idx < 0 || idx >= (int32_t)l.size()) return fail(nullptr, SAMA_EINVAL, "tensor index out of range");
+  if (name_out) { strncpy(name_out, l[idx].name.c_str(), 31); name_out[31] = 0; }
+  if (offset) *offset = l[idx].offset;
+  if (rows) *rows = l[idx].rows;
+  if (cols) *cols = l[idx].cols;
+  return SAMA_OK;
+}
+
+size_t sama_workspace_bytes(const sama_config* cfg) {
+  std::string err;
+  std::unique_ptr<sama_ctx> c(make_host_ctx(cfg, err));
+  if (!c) { g_init_err = err; return 0; }
+  return carve(c.get(), nullptr);
+}
+
+sama_status sama_init(const sama_config* cfg, void* workspace, size_t workspace_bytes, const float* theta0,
+                      const float* lambda0, void* hip_stream, sama_ctx** out) {
+  if (!out) return fail(nullptr, SAMA_EINVAL, "null out");
+  std::string err;
+  std::unique_ptr<sama_ctx> c(make_host_ctx(cfg, err));
+  if (!c) return fail(nullptr, SAMA_EINVAL, err);
+  if (!theta0 || !lambda0) return fail(nullptr, SAMA_EINVAL, "null theta0 / lambda0");
+  if (!workspace || ((uintptr_t)workspace & 255) != 0) return fail(nullptr, SAMA_EWORKSPACE, "workspace null or not 256-byte aligned");
+  const size_t need = carve(c.get(), nullptr);
+  if (workspace_bytes < need) return fail(nullptr, SAMA_EWORKSPACE, "workspace smaller than sama_workspace_bytes()");
+  carve(c.get(), workspace);
+  c->stream = (hipStream_t)hip_stream;
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  launch_copy_f32(st, c->theta, theta0, c->n);
+  launch_copy_f32(st, c->lambda, lambda0, c->nl);
+  launch_fill_f32(st, c->m, 0.f, c->n); launch_fill_f32(st, c->v, 0.f, c->n);
+  launch_fill_f32(st, c->g, 0.f, c->n); launch_fill_f32(st, c->gmeta, 0.f, c->n); launch_fill_f32(st, c->vdir, 0.f, c->n);
+  launch_fill_f32(st, c->meta_m, 0.f, c->nl); launch_fill_f32(st, c->meta_v, 0.f, c->nl);
+  launch_fill_f32(st, c->hyper, 0.f, c->nl); launch_fill_f32(st, c->glam_p32, 0.f, c->nl); launch_fill_f32(st, c->glam_m32, 0.f, c->nl);
+  launch_fill_f32(st, c->scalars, 0.f, 4);
+  launch_fill_i64x4(st, c->counters, 0, 0, 0, 0, 15);
+  if (c->bf16) launch_to_bf16(st, c->theta16, c->theta, c->n_gemm);
+  sama_status s = check_hip(nullptr, "sama_init");
+  if (s != SAMA_OK) return s;
+  *out = c.release();
+  return SAMA_OK;
+}
+
+static PassWeights pass_weights(sama_ctx* c, float sign) {
+  PassWeights w{};
+  w.theta = c->theta; w.vdir = c->vdir; w.eps_ptr = c->scalars; w.sign = sign;
+  w.hi = c->theta16;
+  w.lo = sign > 0.f ? c->lo_p : (sign < 0.f ? c->lo_m : nullptr);
+  return w;
+}
+
+sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out) {
+  if (!c) return SAMA_EINVAL;
+  sama_status s = check_batch(c, train, c->cfg.max_batch, "train");
+  if (s != SAMA_OK) return s;
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  const PassWeights w = pass_weights(c, 0.f);
+  c->model->forward(st, w, *train, true, c->logits);
+  SampleStageArgs sa{};
+  sa.logits = c->logits; sa.ld = c->model->n_classes(); sa.C = sa.ld; sa.B = train->n; sa.H = c->cfg.wnet_hidden;
+  sa.mode = STAGE_BASE; sa.y = train->y; sa.mask = train->sample_mask; sa.lambda = c->lambda;
+  sa.losses = c->losses; sa.dlogits = c->dlogits; sa.loss_scalar = c->scalars + 2; sa.loss_user = loss_out;
+  launch_sample_stage(st, sa);
+  c->model->backward(st, w, *train, c->dlogits, c->g);
+  c->t += 1;
+  const sama_config& f = c->cfg;
+  if (f.base_opt == SAMA_OPT_ADAM) {
+    AdamArgs a{};
+    a.beta1 = f.beta1; a.one_m_beta1 = (float)(1.0 - (double)f.beta1);
+    a.beta2 = f.beta2; a.one_m_beta2 = (float)(1.0 - (double)f.beta2);
+    a.lr_c1 = (float)((double)f.base_lr / (1.0 - pow((double)f.beta1, (double)c->t)));
+    a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t)));
+    a.eps = f.adam_eps; a.weight_decay = f.weight_decay;
+    launch_adam(st, c->g, c->m, c->v, c->theta, c->theta16, c->n, c->n_gemm, a);
+  } else {
+    launch_sgd(st, c->g, c->theta, c->theta16, c->n, c->n_gemm, f.base_lr, f.weight_decay);
+  }
+  launch_fill_i64x4(st, c->counters, c->t, 0, 0, 0, 1);
+  return check_hip(c, "sama_base_step");
+}
+
+static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_batch* meta, float* hyper_out,
+                               float* eps_out, bool update) {
+  if (!c) return SAMA_EINVAL;
+  sama_status s = check_batch(c, train, c->cfg.max_batch, "train");
+  if (s != SAMA_OK) return s;
+  s = check_batch(c, meta, c->cfg.max_meta_batch, "meta");
+  if (s != SAMA_OK) return s;
+  if (c->t < 1) return fail(c, SAMA_ESTATE, "meta gradient requested before any sama_base_step");
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  const sama_config& f = c->cfg;
+  const int C = c->model->n_classes();
+  // pass 1: direct gradient dL_meta/dtheta on the clean batch (Eq. 1)
+  const PassWeights w0 = pass_weights(c, 0.f);
+  c->model->forward(st, w0, *meta, true, c->logits);
+  SampleStageArgs sa{};
+  sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = meta->n; sa.H = f.wnet_hidden; sa.mode = STAGE_META;
+  sa.y = meta->y; sa.mask = meta->sample_mask; sa.lambda = c->lambda; sa.losses = c->losses; sa.dlogits = c->dlogits;
+  sa.loss_scalar = c->scalars + 3;
+  launch_sample_stage(st, sa);
+  c->model->backward(st, w0, *meta, c->dlogits, c->gmeta);
+  // analytic pass: v = (du/dg) . g_meta, eps = alpha / ||v|| (Eq. 4-5, App. C)
+  AdaptArgs ad{};
+  if (f.adapt_mode == SAMA_ADAPT_NONE) { ad.mode = 1; ad.scalar = 1.f; }
+  else if (f.base_opt == SAMA_OPT_SGD) { ad.mode = 1; ad.scalar = f.base_lr; }
+  else {
+    const double c1 = 1.0 / (1.0 - pow((double)f.beta1, (double)c->t));
+    const double c2 = 1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t));
+    ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)f.beta1); ad.one_m_beta2 = (float)(1.0 - (double)f.beta2);
+    ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
+  }
+  launch_adapt_norm(st, c->g, c->m, c->v, c->gmeta, c->vdir, c->partial, c->n, ad, f.alpha, c->scalars, c->counters + 2);
+  if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
+  // passes 2 and 3: dL_base/dlambda at theta +- eps v; forward only, then the weight net's backward
+  for (int pass = 0; pass < 2; ++pass) {
+    const PassWeights wp = pass_weights(c, pass == 0 ? 1.f : -1.f);
+    c->model->forward(st, wp, *train, false, c->logits);
+    SampleStageArgs sg{};
+    sg.logits = c->logits; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM;
+    sg.y = train->y; sg.mask = train->sample_mask; sg.lambda = c->lambda; sg.losses = c->losses;
+    sg.glam = pass == 0 ? c->glam_p : c->glam_m;
+    launch_sample_stage(st, sg);
+  }
+  MetaUpdateArgs mu{};
+  mu.glam_p = c->glam_p; mu.glam_m = c->glam_m; mu.scalars = c->scalars; mu.counters = c->counters;
+  mu.hypergrad = c->hyper; mu.hypergrad_user = hyper_out; mu.eps_user = eps_out;
+  mu.glam_p_f32 = c->glam_p32; mu.glam_m_f32 = c->glam_m32;
+  mu.lambda = c->lambda; mu.meta_m = c->meta_m; mu.meta_v = c->meta_v; mu.nl = c->nl; mu.do_update = update ? 1 : 0;
+  mu.lr = f.meta_lr; mu.beta1 = f.meta_beta1; mu.beta2 = f.meta_beta2; mu.eps = f.meta_eps;
+  launch_meta_update(st, mu);
+  if (update) launch_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->n, c->n_gemm);
+  return check_hip(c, update ? "sama_meta_step" : "sama_meta_grad");
+}
+
+sama_status sama_meta_grad(sama_ctx* c, const sama_batch* train, const sama_batch* meta, float* hypergrad_out,
+                           float* eps_out) {
+  return meta_common(c, train, meta, hypergrad_out, eps_out, false);
+}
+sama_status sama_meta_step(sama_ctx* c, const sama_batch* train, const sama_batch* meta) {
+  return meta_common(c, train, meta, nullptr, nullptr, true);
+}
+
+static bool state_ptr(sama_ctx* c, int32_t which, void** p, size_t* bytes, bool* writable) {
+  const size_t nb = (size_t)c->n * 4, lb = (size_t)c->nl * 4;
+  *writable = true;
+  switch (which) {
+    case SAMA_STATE_THETA: *p = c->theta; *bytes = nb; return true;
+    case SAMA_STATE_M: *p = c->m; *bytes = nb; return true;
+    case SAMA_STATE_V: *p = c->v; *bytes = nb; return true;
+    case SAMA_STATE_G: *p = c->g; *bytes = nb; return true;
+    case SAMA_STATE_GMETA: *p = c->gmeta; *bytes = nb; return true;
+    case SAMA_STATE_VDIR: *p = c->vdir; *bytes = nb; return true;
+    case SAMA_STATE_LAMBDA: *p = c->lambda; *bytes = lb; return true;
+    case SAMA_STATE_META_M: *p = c->meta_m; *bytes = lb; return true;
+    case SAMA_STATE_META_V: *p = c->meta_v; *bytes = lb; return true;
+    case SAMA_STATE_COUNTERS: *p = c->counters; *bytes = 32; return true;
+    case SAMA_STATE_HYPERGRAD: *p = c->hyper; *bytes = lb; *writable = false; return true;
+    case SAMA_STATE_GLAM_PLUS: *p = c->glam_p32; *bytes = lb; *writable = false; return true;
+    case SAMA_STATE_GLAM_MINUS: *p = c->glam_m32; *bytes = lb; *writable = false; return true;
+    case SAMA_STATE_SCALARS: *p = c->scalars; *bytes = 16; *writable = false; return true;
+    case SAMA_STATE_LOSSES: {
+      const int mb = c->cfg.max_batch > c->cfg.max_meta_batch ? c->cfg.max_batch : c->cfg.max_meta_batch;
+      *p = c->losses; *bytes = (size_t)mb * 4; *writable = false; return true;
+    }
+  }
+  return false;
+}
+
+sama_status sama_get_state(sama_ctx* c, int32_t which, void* dst) {
+  if (!c) return SAMA_EINVAL;
+  if (!dst) return fail(c, SAMA_EINVAL, "null dst");
+  void* p; size_t bytes; bool wr;
+  if (!state_ptr(c, which, &p, &bytes, &wr)) return fail(c, SAMA_EINVAL, "unknown state selector");
+  if (hipMemcpyAsync(dst, p, bytes, hipMemcpyDeviceToDevice, c->stream) != hipSuccess)
+    return fail(c, SAMA_EHIP, "sama_get_state: copy failed");
+  return SAMA_OK;
+}
+
+sama_status sama_set_state(sama_ctx* c, int32_t which, const void* src) {
+  if (!c) return SAMA_EINVAL;
+  if (!src) return fail(c, SAMA_EINVAL, "null src");
+  void* p; size_t bytes; bool wr;
+  if (!state_ptr(c, which, &p, &bytes, &wr)) return fail(c, SAMA_EINVAL, "unknown state selector");
+  if (!wr) return fail(c, SAMA_EINVAL, "state selector is read-only");
+  if (hipMemcpyAsync(p, src, bytes, hipMemcpyDeviceToDevice, c->stream) != hipSuccess)
+    return fail(c, SAMA_EHIP, "sama_set_state: copy failed");
+  if (which == SAMA_STATE_THETA && c->bf16) launch_to_bf16(c->stream, c->theta16, c->theta, c->n_gemm);
+  if (which == SAMA_STATE_COUNTERS) {
+    int64_t host[4];
+    if (hipMemcpyAsync(host, c->counters, 32, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess)
+      return fail(c, SAMA_EHIP, "sama_set_state: counter read-back failed");
+    if (host[0] < 0 || host[1] < 0) return fail(c, SAMA_EINVAL, "negative counters");
+    c->t = host[0];
+  }
+  return check_hip(c, "sama_set_state");
+}
+
+const char* sama_last_error(const sama_ctx* c) { return c ? c->err.c_str() : g_init_err.c_str(); }
+
+void sama_destroy(sama_ctx* c) { delete c; }
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+"""Shared plumbing of the GPU parity tests: build the oracle and the HIP context from one workload, move
+oracle state INTO the GPU context (never the other way), compare with relative L2 error."""
+import numpy as np
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a))
+
+
+def make_pair(wl, theta0, lambda0, **over):
+    """(oracle, gpu context) with identical hyper-parameters."""
+    import torch
+    import paper_2310_05674_amd as pkg
+    from oracle import models
+    from oracle.reweight import SamaOracle, ADAM, SGD
+    kw = dict(base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
+              adam_eps=wl.adam_eps)
+    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps")})
+    base_opt = over.get("base_opt", "adam")
+    adapt = over.get("adapt_mode", 0)
+    orc = SamaOracle(models.make_model(wl.kind, wl.dims), theta0, lambda0, base_opt=ADAM if base_opt == "adam" else SGD,
+                     adapt_mode=adapt, **kw)
+    cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=over.get("max_batch", wl.batch),
+                              max_meta_batch=over.get("max_meta_batch", wl.meta_batch),
+                              base_opt=pkg.OPT_ADAM if base_opt == "adam" else pkg.OPT_SGD, adapt_mode=adapt, **kw)
+    gpu = pkg.Sama(cfg, theta0, lambda0)
+    return orc, gpu
+
+
+def dev_batch(gpu, x, y, mask=None):
+    import torch
+    xt = torch.as_tensor(np.ascontiguousarray(x), device=gpu.dev)
+    yt = torch.as_tensor(np.ascontiguousarray(y).astype(np.int32), device=gpu.dev)
+    mt = None if mask is None else torch.as_tensor(np.ascontiguousarray(mask).astype(np.uint8), device=gpu.dev)
+    return gpu.batch(xt, yt, mt)
+
+
+def push_state(orc, gpu):
+    """Teacher forcing: the oracle's state, rounded to fp32, becomes the GPU context's state."""
+    for name, arr in (("THETA", orc.theta), ("M", orc.m), ("V", orc.v), ("G", orc.g), ("LAMBDA", orc.lam),
+                      ("META_M", orc.meta_m), ("META_V", orc.meta_v)):
+        gpu.set_state(name, arr.astype(np.float32))
+    gpu.set_state("COUNTERS", np.array([orc.t, orc.meta_t, 0, 0], dtype=np.int64))
+
+
+def pull(gpu, name):
+    return gpu.get_state(name).cpu().numpy()

@@ -1,0 +1,66 @@
+"""CPU-side checks of the boundary: the library loads, exports every function include/*.h declares, answers
+the host-only shape queries consistently with the other two statements of the layout, and rejects bad configs."""
+import ctypes as C
+import glob
+import os
+import re
+import pytest
+from datagen import param_layout, param_count
+from datagen.workloads import WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    names = []
+    for h in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        src = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names += re.findall(r"\b(sama_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2310_05674_amd as pkg
+    if not os.path.exists(pkg.lib_path()):
+        from paper_2310_05674_amd.build import build
+        build()
+    return pkg.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    decl = _declared()
+    assert {"sama_init", "sama_base_step", "sama_meta_grad", "sama_meta_step"} <= set(decl)
+    for name in decl:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_layout_matches_datagen(lib, cfg):
+    import paper_2310_05674_amd as pkg
+    from paper_2310_05674_amd.binding import param_tensors
+    w = WORKLOADS[cfg]
+    c = pkg.SamaConfig.make(w["kind"], w["dims"], H=w["H"], max_batch=w["batch"], max_meta_batch=w["meta_batch"])
+    assert lib.sama_param_count(C.byref(c)) == param_count(w["kind"], w["dims"])
+    assert lib.sama_lambda_count(C.byref(c)) == 3 * w["H"] + 1
+    want = [(n, o, s[0], s[1] if len(s) > 1 else 1) for n, s, o in param_layout(w["kind"], w["dims"])]
+    assert param_tensors(c) == want
+    ng = lib.sama_gemm_param_count(C.byref(c))
+    assert ng == sum(r * cc for n, o, r, cc in want if n.split(".")[-1] in ("Wqkv", "Wo", "W1", "W2") or (w["kind"] == "mlp" and n.startswith("W")))
+
+
+def test_bad_configs_rejected(lib):
+    import paper_2310_05674_amd as pkg
+    good = dict(H=16, max_batch=8, max_meta_batch=8)
+    c = pkg.SamaConfig.make("mlp", (4, 3), **good)
+    assert lib.sama_workspace_bytes(C.byref(c)) > 0
+    for bad in (pkg.SamaConfig.make("mlp", (4,), **good), pkg.SamaConfig.make("mlp", (4, 1), **good),
+                pkg.SamaConfig.make("mlp", (4, 3), H=0, max_batch=8, max_meta_batch=8),
+                pkg.SamaConfig.make("mlp", (4, 3), H=16, max_batch=0, max_meta_batch=8),
+                pkg.SamaConfig.make("mlp", (4, 3), H=16, max_batch=8, max_meta_batch=8, alpha=0.0),
+                pkg.SamaConfig.make("mlp", (4, 3), H=16, max_batch=8, max_meta_batch=8, bf16=True),
+                pkg.SamaConfig.make("encoder", (2, 30, 4, 64, 128, 100, 3), **good)):
+        assert lib.sama_workspace_bytes(C.byref(bad)) == 0
+        assert lib.sama_last_error(None) != b""
+    h = C.c_void_p()
+    assert lib.sama_init(C.byref(c), None, 0, None, None, None, C.byref(h)) != 0

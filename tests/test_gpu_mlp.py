@@ -1,0 +1,162 @@
+"""GPU parity, fp32 workloads (1: logistic regression, 2: MLP 784-256-256-10): the HIP path through the C ABI
+against the float64 oracle on the same seeded inputs.  Bar: relative L2 <= 1e-4 on the hypergradient and the
+updated theta / lambda; integer artefacts bit-exact."""
+import numpy as np
+import pytest
+from datagen import make_workload, init_theta, init_lambda, CounterRNG
+from harness import rel_l2, make_pair, dev_batch, push_state, pull
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+def _batches(wl, step):
+    it, im = wl.train_batch(step), wl.meta_batch_idx(step)
+    return (wl.x_train[it], wl.y_train[it]), (wl.x_meta[im], wl.y_meta[im])
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_base_step_parity(cfg):
+    wl = make_workload(cfg)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    for s in range(3):
+        (x, y), _ = _batches(wl, s)
+        push_state(orc, gpu)
+        lo = orc.base_step(x, y)
+        gpu.base_step(dev_batch(gpu, x, y))
+        assert rel_l2(pull(gpu, "G"), orc.g) < TOL
+        assert rel_l2(pull(gpu, "THETA"), orc.theta) < 1e-6
+        assert rel_l2(pull(gpu, "M"), orc.m) < TOL and rel_l2(pull(gpu, "V"), orc.v) < TOL
+        assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 1e-5 * abs(lo)
+        assert int(pull(gpu, "COUNTERS")[0]) == orc.t
+    gpu.close()
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_meta_step_parity_teacher_forced(cfg):
+    wl = make_workload(cfg)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    for s in range(3):                      # history, so that the adaptation is not the degenerate first step
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(x, y)
+    for s in range(3, 6):
+        (x, y), (xm, ym) = _batches(wl, s)
+        orc.base_step(x, y)
+        push_state(orc, gpu)
+        tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+        # meta_grad is pure
+        gpu.meta_grad(tb, mb)
+        assert np.array_equal(pull(gpu, "THETA"), orc.theta.astype(np.float32))
+        assert np.array_equal(pull(gpu, "LAMBDA"), orc.lam.astype(np.float32))
+        h_pure = pull(gpu, "HYPERGRAD")
+        r = orc.meta_step(x, y, xm, ym)
+        gpu.meta_step(tb, mb)
+        assert rel_l2(pull(gpu, "GMETA"), r["g_meta"]) < TOL
+        assert rel_l2(pull(gpu, "VDIR"), r["v"]) < TOL
+        sc = pull(gpu, "SCALARS")
+        assert abs(sc[0] - r["eps"]) < TOL * r["eps"]
+        h = pull(gpu, "HYPERGRAD")
+        assert np.array_equal(h, h_pure)
+        assert rel_l2(h, r["h"]) < TOL, rel_l2(h, r["h"])
+        assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+        assert rel_l2(pull(gpu, "LAMBDA"), orc.lam) < TOL
+        cnt = pull(gpu, "COUNTERS")
+        assert int(cnt[1]) == orc.meta_t and int(cnt[2]) == 0
+    gpu.close()
+
+
+def test_free_running_trajectory_workload1():
+    """20 meta steps at unroll 1, no teacher forcing (plus one warm-up base step of history)."""
+    wl = make_workload(1)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
+    orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+    lam0 = orc.lam.copy()
+    for s in range(wl.steps):
+        orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+        r = orc.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta); gpu.meta_step(tb, mb)
+        assert rel_l2(pull(gpu, "HYPERGRAD"), r["h"]) < 1e-3, (s, rel_l2(pull(gpu, "HYPERGRAD"), r["h"]))
+    assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    assert rel_l2(pull(gpu, "LAMBDA") - lam0, orc.lam - lam0) < 1e-3
+    assert int(pull(gpu, "COUNTERS")[1]) == wl.steps
+    gpu.close()
+
+
+def test_masking_is_bit_exact_and_call_order():
+    import paper_2310_05674_amd as pkg
+    wl = make_workload(1)
+    th0, lam0 = init_theta(wl), init_lambda(wl)
+    mask = np.ones(wl.n_train, dtype=np.uint8); mask[::7] = 0
+    mmask = np.ones(wl.n_meta, dtype=np.uint8); mmask[3] = 0
+    outs = []
+    for junk in (False, True):
+        x, y, xm, ym = wl.x_train.copy(), wl.y_train.copy(), wl.x_meta.copy(), wl.y_meta.copy()
+        if junk:
+            x[::7] = 1e3; y[::7] = 1 - y[::7]; xm[3] = -77.0
+        orc, gpu = make_pair(wl, th0, lam0)
+        tb, mb = dev_batch(gpu, x, y, mask), dev_batch(gpu, xm, ym, mmask)
+        with pytest.raises(pkg.SamaError) as e:
+            gpu.meta_step(tb, mb)
+        assert e.value.code == 2
+        for _ in range(3):
+            gpu.base_step(tb)
+            if not junk:
+                orc.base_step(x, y, mask)
+        gpu.meta_step(tb, mb)
+        outs.append((pull(gpu, "HYPERGRAD"), pull(gpu, "THETA"), pull(gpu, "LAMBDA")))
+        if not junk:
+            r = orc.meta_step(x, y, xm, ym, mask, mmask)
+            assert rel_l2(outs[0][0], r["h"]) < TOL and rel_l2(outs[0][1], orc.theta) < TOL
+        gpu.close()
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+
+
+def test_degenerate_direction_is_skipped():
+    """Zero history (g = m = v = 0) gives v = 0: hypergradient 0, lambda and theta untouched, status raised."""
+    wl = make_workload(1)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
+    gpu.base_step(tb)
+    z = np.zeros(gpu.n, dtype=np.float32)
+    for nm in ("G", "M", "V"):
+        gpu.set_state(nm, z)
+    th, lam = pull(gpu, "THETA"), pull(gpu, "LAMBDA")
+    gpu.meta_step(tb, mb)
+    assert np.all(pull(gpu, "HYPERGRAD") == 0) and np.array_equal(pull(gpu, "THETA"), th) and np.array_equal(pull(gpu, "LAMBDA"), lam)
+    cnt = pull(gpu, "COUNTERS")
+    assert int(cnt[1]) == 0 and int(cnt[2]) == 1
+    gpu.close()
+
+
+@pytest.mark.parametrize("variant", ["sgd", "sama_na"])
+def test_sgd_and_no_adaptation_variants(variant):
+    wl = make_workload(1)
+    kw = dict(base_opt="sgd", base_lr=0.05) if variant == "sgd" else dict(adapt_mode=1)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl), **kw)
+    tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
+    for _ in range(2):
+        orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+    r = orc.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta); gpu.meta_step(tb, mb)
+    assert rel_l2(pull(gpu, "HYPERGRAD"), r["h"]) < TOL and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    gpu.close()
+
+
+def test_ragged_shapes():
+    """Widths and batch sizes that are not multiples of any tile (67-33-5, batches 37 / 19)."""
+    from datagen.workloads import Workload
+    r = CounterRNG(99)
+    wl = Workload(cfg=0, kind="mlp", dims=(67, 33, 5), bf16=False, H=9, batch=37, meta_batch=19, base_lr=1e-2,
+                  meta_lr=1e-3, alpha=0.5, noise=0.0, n_train=37, n_meta=19, steps=1)
+    x = r.normal(1, 37 * 67).reshape(37, 67).astype(np.float32); y = r.integers(2, 37, 5).astype(np.int32)
+    xm = r.normal(3, 19 * 67).reshape(19, 67).astype(np.float32); ym = r.integers(4, 19, 5).astype(np.int32)
+    th0 = (0.2 * r.normal(5, 67 * 33 + 33 * 5 + 33 + 5)).astype(np.float32).astype(np.float64)
+    lam0 = r.normal(6, 28).astype(np.float32).astype(np.float64)
+    orc, gpu = make_pair(wl, th0, lam0)
+    tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+    for _ in range(3):
+        orc.base_step(x, y); gpu.base_step(tb)
+    assert rel_l2(pull(gpu, "G"), orc.g) < TOL
+    rr = orc.meta_step(x, y, xm, ym); gpu.meta_step(tb, mb)
+    assert rel_l2(pull(gpu, "HYPERGRAD"), rr["h"]) < TOL and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    gpu.close()
