@@ -129,8 +129,9 @@ def round_to_bf16(a):
     return bits.astype(np.uint32).view(np.float32).astype(np.asarray(a).dtype).reshape(np.shape(a))
 
 
-def init_theta(wl):
-    """Initial base parameters (float64 array holding float32- or bf16-representable values)."""
+def init_theta(wl, scale=0.02):
+    """Initial base parameters (float64 array holding float32- or bf16-representable values).
+    `scale` is the std of the encoder's matrices and embeddings."""
     rng = CounterRNG(wl.seed)
     lay = param_layout(wl.kind, wl.dims)
     n = param_count(wl.kind, wl.dims)
@@ -146,7 +147,7 @@ def init_theta(wl):
             if leaf in ("ln1_g", "ln2_g", "emb_ln_g"):
                 th[off:off + size] = 1.0
             elif leaf.startswith("W") or leaf.endswith("emb"):
-                th[off:off + size] = 0.02 * z[off:off + size]
+                th[off:off + size] = scale * z[off:off + size]
     th = th.astype(np.float32).astype(np.float64)
     return round_to_bf16(th) if wl.bf16 else th
 
@@ -185,10 +186,12 @@ def _zipf_tokens(rng, stream, n_seq, S, V, a=1.1):
     return ids
 
 
-def make_workload(cfg, n_train=None, n_meta=None):
+def make_workload(cfg, n_train=None, n_meta=None, **override):
     """Build workload `cfg` (1..5).  n_train / n_meta may shrink the data set for quick tests
-    (the first rows of the full recipe are NOT guaranteed identical when shrunk)."""
+    (the first rows of the full recipe are NOT guaranteed identical when shrunk); `override`
+    replaces other fields (dims, batch, ...) to get a small model on the same data recipe."""
     kw = dict(WORKLOADS[cfg])
+    kw.update(override)
     if n_train is not None:
         kw["n_train"] = n_train
     if n_meta is not None:

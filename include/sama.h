@@ -74,6 +74,10 @@ typedef struct {
                           SAMA_ADAPT_NONE: identity, the SAMA-NA ablation of Sec. 4.1 */
   int32_t max_batch;      /* largest train batch that will be passed, 1..2048 */
   int32_t max_meta_batch; /* largest meta batch, 1..2048 */
+  int32_t fast_meta_pass; /* BF16 models only.  0 (default): the direct-gradient pass of Eq. 1 contracts with the
+                             two-term split hi + lo of the fp32 master weights, so dL_meta/dtheta is taken at theta
+                             and not at bf16(theta) (costs two extra forward-equivalents of GEMM work per meta
+                             step).  1: that pass uses the bf16 working copy like a base step. */
 } sama_config;
 
 /* One batch.  x: DEVICE, fp32 [n x d0] row-major (MLP) or int32 token ids [n x S] (ENCODER), ids in [0, V).

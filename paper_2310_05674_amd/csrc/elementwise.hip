@@ -192,6 +192,18 @@ __global__ __launch_bounds__(EW_THREADS) void k_perturb_lo(const float* __restri
   }
 }
 
+__global__ __launch_bounds__(EW_THREADS) void k_residual_lo(const float* __restrict__ theta, bf16_t* __restrict__ lo, int64_t n16) {
+  const int64_t nv = n16 / EW_VEC;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += stride) {
+    const float4 t4 = reinterpret_cast<const float4*>(theta)[i];
+    store_bf16x4(lo + i * EW_VEC, t4.x - bf16_to_f32(f32_to_bf16(t4.x)), t4.y - bf16_to_f32(f32_to_bf16(t4.y)),
+                 t4.z - bf16_to_f32(f32_to_bf16(t4.z)), t4.w - bf16_to_f32(f32_to_bf16(t4.w)));
+  }
+  const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < n16) lo[k] = f32_to_bf16(theta[k] - bf16_to_f32(f32_to_bf16(theta[k])));
+}
+
 // theta <- theta - eps v (and the bf16 working copy).  eps = 0 (a skipped step) leaves everything as it is.
 __global__ __launch_bounds__(EW_THREADS) void k_nudge(float* __restrict__ theta, const float* __restrict__ vdir,
                                                       const float* __restrict__ eps_ptr, bf16_t* __restrict__ theta16,
@@ -273,6 +285,10 @@ void launch_perturb_lo(hipStream_t st, const float* theta, const float* vdir, co
                        bf16_t* lo_m, int64_t n16) {
   if (n16 <= 0) return;
   k_perturb_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, lo_p, lo_m, n16);
+}
+void launch_residual_lo(hipStream_t st, const float* theta, bf16_t* lo, int64_t n16) {
+  if (n16 <= 0) return;
+  k_residual_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, lo, n16);
 }
 void launch_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, int64_t n,
                   int64_t n16) {

@@ -1,0 +1,513 @@
+// Non-GEMM pieces of the post-LN encoder base learner (Sec. 4.1 uses BERT / RoBERTa-shaped models):
+// embedding gather + LayerNorm, LayerNorm forward / backward, fused attention forward / backward on the matrix
+// cores, classifier head, column sums, embedding gradients.  All reductions run in a fixed order.
+#include "common.h"
+#include "kernels.h"
+
+namespace sama {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float LN_EPS = 1e-5f;
+
+// =========================================================================================== LayerNorm forward
+// One wave per row; the row lives in registers (d <= 1024).  Statistics in fp32 with a centred second pass.
+__global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.M) return;
+  const int nq = a.d >> 2;  // float4 chunks per row
+  const float sc = a.pv.scale();
+  float4 xr[4];
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int q = lane + 64 * j;
+    xr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q < nq) {
+      if (a.x != nullptr) {
+        xr[j] = reinterpret_cast<const float4*>(a.x + (int64_t)row * a.d)[q];
+      } else {
+        const int64_t to = a.tok_off + (int64_t)a.ids[row] * a.d + 4 * q, po = a.pos_off + (int64_t)(row % a.S) * a.d + 4 * q;
+        float4 t = *reinterpret_cast<const float4*>(a.pv.theta + to), p = *reinterpret_cast<const float4*>(a.pv.theta + po);
+        if (sc != 0.f) {
+          const float4 tv = *reinterpret_cast<const float4*>(a.pv.vdir + to), pvv = *reinterpret_cast<const float4*>(a.pv.vdir + po);
+          t.x = fmaf(sc, tv.x, t.x); t.y = fmaf(sc, tv.y, t.y); t.z = fmaf(sc, tv.z, t.z); t.w = fmaf(sc, tv.w, t.w);
+          p.x = fmaf(sc, pvv.x, p.x); p.y = fmaf(sc, pvv.y, p.y); p.z = fmaf(sc, pvv.z, p.z); p.w = fmaf(sc, pvv.w, p.w);
+        }
+        xr[j] = make_float4(t.x + p.x, t.y + p.y, t.z + p.z, t.w + p.w);
+        if (a.x_out != nullptr) reinterpret_cast<float4*>(a.x_out + (int64_t)row * a.d)[q] = xr[j];
+      }
+      sum += (xr[j].x + xr[j].y) + (xr[j].z + xr[j].w);
+    }
+  }
+  const float mu = wave_sum(sum) / (float)a.d;
+  float sq = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (lane + 64 * j < nq) {
+      const float e0 = xr[j].x - mu, e1 = xr[j].y - mu, e2 = xr[j].z - mu, e3 = xr[j].w - mu;
+      sq += (e0 * e0 + e1 * e1) + (e2 * e2 + e3 * e3);
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)a.d + LN_EPS);
+  if (lane == 0) {
+    if (a.mean != nullptr) a.mean[row] = mu;
+    if (a.rstd != nullptr) a.rstd[row] = rstd;
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int q = lane + 64 * j;
+    if (q < nq) {
+      float4 g = *reinterpret_cast<const float4*>(a.pv.theta + a.g_off + 4 * q), b = *reinterpret_cast<const float4*>(a.pv.theta + a.b_off + 4 * q);
+      if (sc != 0.f) {
+        const float4 gv = *reinterpret_cast<const float4*>(a.pv.vdir + a.g_off + 4 * q), bv = *reinterpret_cast<const float4*>(a.pv.vdir + a.b_off + 4 * q);
+        g.x = fmaf(sc, gv.x, g.x); g.y = fmaf(sc, gv.y, g.y); g.z = fmaf(sc, gv.z, g.z); g.w = fmaf(sc, gv.w, g.w);
+        b.x = fmaf(sc, bv.x, b.x); b.y = fmaf(sc, bv.y, b.y); b.z = fmaf(sc, bv.z, b.z); b.w = fmaf(sc, bv.w, b.w);
+      }
+      uint2 pk;
+      pk.x = (uint32_t)f32_to_bf16(fmaf((xr[j].x - mu) * rstd, g.x, b.x)) | ((uint32_t)f32_to_bf16(fmaf((xr[j].y - mu) * rstd, g.y, b.y)) << 16);
+      pk.y = (uint32_t)f32_to_bf16(fmaf((xr[j].z - mu) * rstd, g.z, b.z)) | ((uint32_t)f32_to_bf16(fmaf((xr[j].w - mu) * rstd, g.w, b.w)) << 16);
+      *reinterpret_cast<uint2*>(a.y + (int64_t)row * a.d + 4 * q) = pk;
+    }
+  }
+}
+
+// =========================================================================================== LayerNorm backward
+// dx = rstd (dy g - mean(dy g) - xh mean(dy g xh)); per-block partial sums of dgamma = dy xh, dbeta = dy and of
+// dx itself (the bias gradient of the linear layer feeding this LayerNorm).  A block owns LN_BWD_ROWS rows,
+// each wave walks its rows in order, lanes keep per-column accumulators, the four waves are added in order.
+__global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
+  __shared__ float s_acc[4][3][LN_MAX_D];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nq = a.d >> 2;
+  float4 dg[4], db[4], dc[4], gam[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    dg[j] = db[j] = dc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    gam[j] = (lane + 64 * j < nq) ? reinterpret_cast<const float4*>(a.gamma)[lane + 64 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const int r0 = blockIdx.x * LN_BWD_ROWS + wave * (LN_BWD_ROWS / 4);
+  for (int rr = 0; rr < LN_BWD_ROWS / 4; ++rr) {
+    const int row = r0 + rr;
+    if (row >= a.M) break;
+    const float mu = a.mean[row], rstd = a.rstd[row];
+    float4 xh[4], dyg[4];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = lane + 64 * j;
+      xh[j] = dyg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (q < nq) {
+        const float4 x = reinterpret_cast<const float4*>(a.x + (int64_t)row * a.d)[q];
+        const float4 dy = reinterpret_cast<const float4*>(a.dy + (int64_t)row * a.d)[q];
+        xh[j] = make_float4((x.x - mu) * rstd, (x.y - mu) * rstd, (x.z - mu) * rstd, (x.w - mu) * rstd);
+        dyg[j] = make_float4(dy.x * gam[j].x, dy.y * gam[j].y, dy.z * gam[j].z, dy.w * gam[j].w);
+        dg[j].x = fmaf(dy.x, xh[j].x, dg[j].x); dg[j].y = fmaf(dy.y, xh[j].y, dg[j].y);
+        dg[j].z = fmaf(dy.z, xh[j].z, dg[j].z); dg[j].w = fmaf(dy.w, xh[j].w, dg[j].w);
+        db[j].x += dy.x; db[j].y += dy.y; db[j].z += dy.z; db[j].w += dy.w;
+        s1 += (dyg[j].x + dyg[j].y) + (dyg[j].z + dyg[j].w);
+        s2 += (dyg[j].x * xh[j].x + dyg[j].y * xh[j].y) + (dyg[j].z * xh[j].z + dyg[j].w * xh[j].w);
+      }
+    }
+    const float m1 = wave_sum(s1) / (float)a.d, m2 = wave_sum(s2) / (float)a.d;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = lane + 64 * j;
+      if (q < nq) {
+        float4 dx;
+        dx.x = rstd * (dyg[j].x - m1 - xh[j].x * m2); dx.y = rstd * (dyg[j].y - m1 - xh[j].y * m2);
+        dx.z = rstd * (dyg[j].z - m1 - xh[j].z * m2); dx.w = rstd * (dyg[j].w - m1 - xh[j].w * m2);
+        dc[j].x += dx.x; dc[j].y += dx.y; dc[j].z += dx.z; dc[j].w += dx.w;
+        if (a.dx32 != nullptr) reinterpret_cast<float4*>(a.dx32 + (int64_t)row * a.d)[q] = dx;
+        if (a.dx16 != nullptr) {
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16(dx.x) | ((uint32_t)f32_to_bf16(dx.y) << 16);
+          pk.y = (uint32_t)f32_to_bf16(dx.z) | ((uint32_t)f32_to_bf16(dx.w) << 16);
+          *reinterpret_cast<uint2*>(a.dx16 + (int64_t)row * a.d + 4 * q) = pk;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int q = lane + 64 * j;
+    if (q < nq) {
+      reinterpret_cast<float4*>(s_acc[wave][0])[q] = dg[j];
+      reinterpret_cast<float4*>(s_acc[wave][1])[q] = db[j];
+      reinterpret_cast<float4*>(s_acc[wave][2])[q] = dc[j];
+    }
+  }
+  __syncthreads();
+  float* out = a.partial + (int64_t)blockIdx.x * 3 * a.d;
+  for (int i = threadIdx.x; i < 3 * a.d; i += 256) {
+    const int v = i / a.d, c = i - v * a.d;
+    out[i] = ((s_acc[0][v][c] + s_acc[1][v][c]) + s_acc[2][v][c]) + s_acc[3][v][c];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_reduce_rows(const float* __restrict__ partial, int nrows, int64_t stride, int N,
+                                                     float* __restrict__ out) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= N) return;
+  float s = 0.f;
+  for (int r = 0; r < nrows; ++r) s += partial[(int64_t)r * stride + c];
+  out[c] = s;
+}
+
+__global__ __launch_bounds__(256) void k_colsum_partial_bf16(const bf16_t* __restrict__ X, int M, int N, float* __restrict__ partial) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= N) return;
+  const int r0 = blockIdx.y * COLSUM_ROWS;
+  float s = 0.f;
+  for (int r = r0; r < r0 + COLSUM_ROWS && r < M; ++r) s += bf16_to_f32(X[(int64_t)r * N + c]);
+  partial[(int64_t)blockIdx.y * N + c] = s;
+}
+
+// =========================================================================================== attention
+constexpr int AS = 128, AD = 64, ALD = AS + 8;  // sequence length, head width, LDS row stride of transposed tiles
+
+__device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
+__device__ __forceinline__ s16x4 ld_s16x4(const bf16_t* p) { return *reinterpret_cast<const s16x4*>(p); }
+__device__ __forceinline__ s16x4 pack4(float a, float b, float c, float d) {
+  s16x4 r;
+  r[0] = (short)f32_to_bf16(a); r[1] = (short)f32_to_bf16(b); r[2] = (short)f32_to_bf16(c); r[3] = (short)f32_to_bf16(d);
+  return r;
+}
+
+// transposed copy of a [128 x 64] bf16 tile (row stride ld) into LDS as T[e][row], row stride ALD
+__device__ __forceinline__ void stage_transposed(const bf16_t* __restrict__ src, int64_t ld, bf16_t* __restrict__ T) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + 256 * i, row = c >> 3, ec = c & 7;
+    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)row * ld + ec * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) T[(ec * 8 + e) * ALD + row] = (bf16_t)(w[e >> 1] >> ((e & 1) * 16));
+  }
+}
+
+// X^T-style product tile: acc[32 x 32] (+)= sum_e R[rbase + l%32][e] * Cc[cbase + l%32][e], both operands read
+// from global rows of 64 contiguous bf16 (row stride ld).  Result lane layout: column = cbase + l%32,
+// rows rbase + 8(r/4) + 4(l/32) + r%4.
+__device__ __forceinline__ f32x16 rows_dot_rows(const bf16_t* __restrict__ R, const bf16_t* __restrict__ Cc, int64_t ld,
+                                                int rbase, int cbase, int lane) {
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  const bf16_t* rp = R + (int64_t)(rbase + (lane & 31)) * ld + 8 * (lane >> 5);
+  const bf16_t* cp = Cc + (int64_t)(cbase + (lane & 31)) * ld + 8 * (lane >> 5);
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(rp + 16 * ks), ld_bf16x8(cp + 16 * ks), acc, 0, 0, 0);
+  return acc;
+}
+
+// Forward.  Wave w owns queries 32w..32w+31.  S^T[key][q] tiles leave each lane with one query column, so the
+// softmax over keys is an in-lane reduction plus one cross-half shuffle, and the probability tile is already in
+// the B-operand layout of the 32x32x8 MFMA for O^T[e][q] = sum_key V^T[e][key] P^T[key][q].
+__global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out, float* __restrict__ lse,
+                                                  int heads, int d) {
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[AD * ALD];
+  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t ld = 3 * (int64_t)d;
+  const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
+  const bf16_t* K = Q + d;
+  const bf16_t* V = Q + 2 * d;
+  stage_transposed(V, ld, Vt);
+  f32x16 s[4];
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt) s[kt] = rows_dot_rows(K, Q, ld, 32 * kt, 32 * wave, lane);
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[kt][r] *= 0.125f; mx = fmaxf(mx, s[kt][r]); }
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  float sum = 0.f;
+#pragma unroll
+  for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[kt][r] = __expf(s[kt][r] - mx); sum += s[kt][r]; }
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.f / sum;
+  if (lane < 32 && lse != nullptr) lse[((int64_t)b * heads + h) * AS + 32 * wave + lane] = mx + __logf(sum);
+  __syncthreads();
+  f32x16 o[2];
+#pragma unroll
+  for (int et = 0; et < 2; ++et) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[et][r] = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const s16x4 pb = pack4(s[kt][4 * c] * inv, s[kt][4 * c + 1] * inv, s[kt][4 * c + 2] * inv, s[kt][4 * c + 3] * inv);
+        const s16x4 va = ld_s16x4(Vt + (32 * et + (lane & 31)) * ALD + 32 * kt + 8 * c + 4 * (lane >> 5));
+        o[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(va, pb, o[et], 0, 0, 0);
+      }
+  }
+  bf16_t* orow = out + ((int64_t)b * AS + 32 * wave + (lane & 31)) * d + h * AD;
+#pragma unroll
+  for (int et = 0; et < 2; ++et)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      uint2 pk;
+      pk.x = (uint32_t)f32_to_bf16(o[et][4 * c]) | ((uint32_t)f32_to_bf16(o[et][4 * c + 1]) << 16);
+      pk.y = (uint32_t)f32_to_bf16(o[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(o[et][4 * c + 3]) << 16);
+      *reinterpret_cast<uint2*>(orow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+    }
+}
+
+// Backward.  Probabilities are recomputed from q, k and the saved log-sum-exp.
+// Phase A (wave owns 32 queries): dS^T[key][q] -> dQ^T[e][q] = sum_key K^T[e][key] dS^T[key][q].
+// Phase B (wave owns 32 keys):    P[q][key], dS[q][key] -> dV^T[e][key] = sum_q dO^T[e][q] P[q][key],
+//                                                          dK^T[e][key] = sum_q Q^T[e][q] dS[q][key].
+// dS = P (dP - D) / 8 with D[q] = sum_e dO[q][e] O[q][e].
+__global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ out,
+                                                  const bf16_t* __restrict__ dout, const float* __restrict__ lse,
+                                                  bf16_t* __restrict__ dqkv, int heads, int d) {
+  __shared__ __attribute__((aligned(16))) bf16_t Kt[AD * ALD];
+  __shared__ __attribute__((aligned(16))) bf16_t Qt[AD * ALD];
+  __shared__ __attribute__((aligned(16))) bf16_t dOt[AD * ALD];
+  __shared__ float s_D[AS], s_lse[AS];
+  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t ld = 3 * (int64_t)d;
+  const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
+  const bf16_t* K = Q + d;
+  const bf16_t* V = Q + 2 * d;
+  const bf16_t* O = out + (int64_t)b * AS * d + h * AD;
+  const bf16_t* dO = dout + (int64_t)b * AS * d + h * AD;
+  stage_transposed(K, ld, Kt);
+  stage_transposed(Q, ld, Qt);
+  stage_transposed(dO, d, dOt);
+  {
+    const int q = threadIdx.x >> 1, half = threadIdx.x & 1;
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 o4 = *reinterpret_cast<const uint4*>(O + (int64_t)q * d + half * 32 + 8 * i);
+      const uint4 d4 = *reinterpret_cast<const uint4*>(dO + (int64_t)q * d + half * 32 + 8 * i);
+      const uint32_t ow[4] = {o4.x, o4.y, o4.z, o4.w}, dw[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        acc = fmaf(bf16_to_f32((bf16_t)(ow[e >> 1] >> ((e & 1) * 16))), bf16_to_f32((bf16_t)(dw[e >> 1] >> ((e & 1) * 16))), acc);
+    }
+    acc += __shfl_xor(acc, 1, 64);
+    if (half == 0) { s_D[q] = acc; s_lse[q] = lse[((int64_t)b * heads + h) * AS + q]; }
+  }
+  __syncthreads();
+
+  // ---- phase A: dQ
+  {
+    const int q = 32 * wave + (lane & 31);
+    const float lq = s_lse[q], Dq = s_D[q];
+    f32x16 dq[2];
+#pragma unroll
+    for (int et = 0; et < 2; ++et)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq[et][r] = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      f32x16 st = rows_dot_rows(K, Q, ld, 32 * kt, 32 * wave, lane);     // S^T[key][q]
+      const bf16_t* vp = V + (int64_t)(32 * kt + (lane & 31)) * ld + 8 * (lane >> 5);
+      const bf16_t* dop = dO + (int64_t)(32 * wave + (lane & 31)) * d + 8 * (lane >> 5);
+      f32x16 dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(vp + 16 * ks), ld_bf16x8(dop + 16 * ks), dp, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st[r] = __expf(st[r] * 0.125f - lq) * (dp[r] - Dq) * 0.125f;   // dS^T
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const s16x4 dsb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
+#pragma unroll
+        for (int et = 0; et < 2; ++et) {
+          const s16x4 ka = ld_s16x4(Kt + (32 * et + (lane & 31)) * ALD + 32 * kt + 8 * c + 4 * (lane >> 5));
+          dq[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ka, dsb, dq[et], 0, 0, 0);
+        }
+      }
+    }
+    bf16_t* dqrow = dqkv + ((int64_t)b * AS + q) * ld + h * AD;
+#pragma unroll
+    for (int et = 0; et < 2; ++et)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(dq[et][4 * c]) | ((uint32_t)f32_to_bf16(dq[et][4 * c + 1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(dq[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(dq[et][4 * c + 3]) << 16);
+        *reinterpret_cast<uint2*>(dqrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+      }
+  }
+
+  // ---- phase B: dK, dV
+  {
+    f32x16 dk[2], dv[2];
+#pragma unroll
+    for (int et = 0; et < 2; ++et)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { dk[et][r] = 0.f; dv[et][r] = 0.f; }
+#pragma unroll
+    for (int qt = 0; qt < 4; ++qt) {
+      f32x16 st = rows_dot_rows(Q, K, ld, 32 * qt, 32 * wave, lane);     // S[q][key]
+      const bf16_t* dop = dO + (int64_t)(32 * qt + (lane & 31)) * d + 8 * (lane >> 5);
+      const bf16_t* vp = V + (int64_t)(32 * wave + (lane & 31)) * ld + 8 * (lane >> 5);
+      f32x16 dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(dop + 16 * ks), ld_bf16x8(vp + 16 * ks), dp, 0, 0, 0);
+      f32x16 ds;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int q = 32 * qt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const float p = __expf(st[r] * 0.125f - s_lse[q]);
+        st[r] = p;
+        ds[r] = p * (dp[r] - s_D[q]) * 0.125f;
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const s16x4 pb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
+        const s16x4 dsb = pack4(ds[4 * c], ds[4 * c + 1], ds[4 * c + 2], ds[4 * c + 3]);
+#pragma unroll
+        for (int et = 0; et < 2; ++et) {
+          const int off = (32 * et + (lane & 31)) * ALD + 32 * qt + 8 * c + 4 * (lane >> 5);
+          dv[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_s16x4(dOt + off), pb, dv[et], 0, 0, 0);
+          dk[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_s16x4(Qt + off), dsb, dk[et], 0, 0, 0);
+        }
+      }
+    }
+    bf16_t* krow = dqkv + ((int64_t)b * AS + 32 * wave + (lane & 31)) * ld + d + h * AD;
+    bf16_t* vrow = krow + d;
+#pragma unroll
+    for (int et = 0; et < 2; ++et)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(dk[et][4 * c]) | ((uint32_t)f32_to_bf16(dk[et][4 * c + 1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(dk[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(dk[et][4 * c + 3]) << 16);
+        *reinterpret_cast<uint2*>(krow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+        pk.x = (uint32_t)f32_to_bf16(dv[et][4 * c]) | ((uint32_t)f32_to_bf16(dv[et][4 * c + 1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(dv[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(dv[et][4 * c + 3]) << 16);
+        *reinterpret_cast<uint2*>(vrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+      }
+  }
+}
+
+// =========================================================================================== classifier head
+__global__ __launch_bounds__(256) void k_head_fwd(const bf16_t* __restrict__ x, int S, int d, int B, int C, ParamView pv,
+                                                  int64_t wc_off, int64_t bc_off, float* __restrict__ logits) {
+  const int lane = threadIdx.x & 63, idx = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (idx >= B * C) return;
+  const int b = idx / C, c = idx - b * C;
+  const float sc = pv.scale();
+  const bf16_t* xr = x + (int64_t)b * S * d;
+  float acc = 0.f;
+  for (int k = lane; k < d; k += 64) acc = fmaf(bf16_to_f32(xr[k]), pv.at(wc_off + (int64_t)c * d + k, sc), acc);
+  acc = wave_sum(acc);
+  if (lane == 0) logits[idx] = acc + pv.at(bc_off + c, sc);
+}
+
+__global__ __launch_bounds__(256) void k_head_bwd_w(const bf16_t* __restrict__ x, int S, int d, int B, int C,
+                                                    const float* __restrict__ dlogits, float* __restrict__ gWc, float* __restrict__ gbc) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < C * d) {
+    const int c = i / d, k = i - c * d;
+    float s = 0.f;
+    for (int b = 0; b < B; ++b) s = fmaf(dlogits[b * C + c], bf16_to_f32(x[(int64_t)b * S * d + k]), s);
+    gWc[i] = s;
+  }
+  if (i < C) {
+    float s = 0.f;
+    for (int b = 0; b < B; ++b) s += dlogits[b * C + i];
+    gbc[i] = s;
+  }
+}
+__global__ __launch_bounds__(256) void k_head_bwd_x(int S, int d, int B, int C, const float* __restrict__ Wc,
+                                                    const float* __restrict__ dlogits, float* __restrict__ dx) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B * d) return;
+  const int b = i / d, k = i - b * d;
+  float s = 0.f;
+  for (int c = 0; c < C; ++c) s = fmaf(dlogits[b * C + c], Wc[(int64_t)c * d + k], s);
+  dx[(int64_t)b * S * d + k] = s;
+}
+
+// =========================================================================================== embedding gradients
+__global__ __launch_bounds__(256) void k_pos_grad(const float* __restrict__ demb, int B, int S, int d, float* __restrict__ g_pos) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= S * d) return;
+  float s = 0.f;
+  for (int b = 0; b < B; ++b) s += demb[(int64_t)b * S * d + i];
+  g_pos[i] = s;
+}
+
+// One block per position m.  The block lists, in ascending order, every position holding the same token id;
+// only the block of the first occurrence goes on, and writes the ordered sum of those rows.
+__global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb, const int32_t* __restrict__ ids, int M, int d,
+                                                  float* __restrict__ g_tok) {
+  __shared__ int s_list[MAX_BATCH > 4096 ? MAX_BATCH : 4096];
+  __shared__ int s_cnt, s_wave[4];
+  const int m = blockIdx.x, id = ids[m], lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) s_cnt = 0;
+  __syncthreads();
+  for (int base = 0; base < M; base += 256) {
+    const int mm = base + threadIdx.x;
+    const bool hit = (mm < M) && (ids[mm] == id);
+    const unsigned long long bal = __ballot(hit);
+    if (lane == 0) s_wave[wave] = __popcll(bal);
+    __syncthreads();
+    int off = s_cnt;
+    for (int w = 0; w < wave; ++w) off += s_wave[w];
+    if (hit) {
+      const int pos = off + __popcll(bal & ((1ull << lane) - 1ull));
+      if (pos < 4096) s_list[pos] = mm;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) s_cnt += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+    __syncthreads();
+    if (s_cnt > 0 && s_list[0] != m) return;   // an earlier position holds this id (the list is ascending)
+  }
+  const int cnt = s_cnt < 4096 ? s_cnt : 4096;
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float s = 0.f;
+    for (int i = 0; i < cnt; ++i) s += demb[(int64_t)s_list[i] * d + c];
+    g_tok[(int64_t)id * d + c] = s;
+  }
+}
+}  // namespace
+
+void launch_ln_fwd(hipStream_t st, const LnFwdArgs& a) { k_ln_fwd<<<(a.M + 3) / 4, 256, 0, st>>>(a); }
+void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) { k_ln_bwd<<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a); }
+void launch_reduce_rows(hipStream_t st, const float* partial, int nrows, int64_t stride, int N, float* out) {
+  k_reduce_rows<<<(N + 255) / 256, 256, 0, st>>>(partial, nrows, stride, N, out);
+}
+void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* partial, float* out) {
+  const int nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
+  k_colsum_partial_bf16<<<dim3((N + 255) / 256, nrb), 256, 0, st>>>(X, M, N, partial);
+  launch_reduce_rows(st, partial, nrb, N, N, out);
+}
+void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d) {
+  k_attn_fwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, lse, heads, d);
+}
+void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
+                          bf16_t* dqkv, int B, int heads, int d) {
+  k_attn_bwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d);
+}
+void launch_head_fwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
+                     float* logits) {
+  k_head_fwd<<<(B * C + 3) / 4, 256, 0, st>>>(x, S, d, B, C, pv, wc_off, bc_off, logits);
+}
+void launch_head_bwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
+                     int64_t bc_off, const float* dlogits, float* grad, float* dx) {
+  k_head_bwd_w<<<(C * d + 255) / 256, 256, 0, st>>>(x, S, d, B, C, dlogits, grad + wc_off, grad + bc_off);
+  k_head_bwd_x<<<(B * d + 255) / 256, 256, 0, st>>>(S, d, B, C, theta + wc_off, dlogits, dx);
+}
+void launch_embedding_bwd(hipStream_t st, const float* demb, const int32_t* ids, int B, int S, int d, float* g_tok, float* g_pos) {
+  k_pos_grad<<<(S * d + 255) / 256, 256, 0, st>>>(demb, B, S, d, g_pos);
+  k_tok_grad<<<B * S, 256, 0, st>>>(demb, ids, B * S, d, g_tok);
+}
+
+}  // namespace sama

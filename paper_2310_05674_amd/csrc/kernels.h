@@ -33,6 +33,8 @@ void launch_adapt_norm(hipStream_t, const float* g, const float* m, const float*
                        int64_t* status);
 void launch_perturb_lo(hipStream_t, const float* theta, const float* vdir, const float* eps_ptr, bf16_t* lo_p,
                        bf16_t* lo_m, int64_t n16);
+// lo[k] = bf16(theta[k] - float(bf16(theta[k]))): the part of the master weights the bf16 working copy cannot hold
+void launch_residual_lo(hipStream_t, const float* theta, bf16_t* lo, int64_t n16);
 void launch_nudge(hipStream_t, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, int64_t n,
                   int64_t n16);
 void launch_fill_f32(hipStream_t, float* p, float val, int64_t n);
@@ -85,5 +87,61 @@ struct GemmF32Args {
 void launch_gemm_f32(hipStream_t, const GemmF32Args&);
 // out[j] = sum_i X[i*ld + j], fixed order.
 void launch_colsum_f32(hipStream_t, const float* X, int64_t ld, int M, int N, float* out);
+
+// ------------------------------------------------------------------ bf16 MFMA GEMM (gemm_bf16.hip)
+enum { GEMM_ACT_NONE = 0, GEMM_ACT_GELU_FWD = 1, GEMM_ACT_GELU_BWD = 2 };
+// C[M x N] = A . (B + B2).  a_trans = 0: A stored [M][K]; 1: stored [K][M].  b_trans = 1: B stored [N][K]
+// (a weight matrix [out x in] used forward); 0: stored [K][N].  B2 (same storage as B) may be null.
+// Epilogue, in this order: + bias[j] (+ bsign * *beps * bias_v[j]); + res16 / res32 [i*ldc + j];
+// GELU_FWD: C16_pre = bf16(c), c = gelu(that);  GELU_BWD: c *= gelu'(aux16[i*ldc + j]);  stores to C32 and/or C16.
+struct GemmBf16Args {
+  const bf16_t* A; int64_t lda; int a_trans;
+  const bf16_t* B; const bf16_t* B2; int64_t ldb; int b_trans;
+  int M, N, K;
+  int64_t ldc;
+  const float* bias; const float* bias_v; const float* beps; float bsign;
+  const bf16_t* res16; const float* res32;
+  int act; const bf16_t* aux16; bf16_t* C16_pre;
+  float* C32; bf16_t* C16;
+};
+const char* check_gemm_bf16(const GemmBf16Args&);  // null if the shapes / alignments are supported
+void launch_gemm_bf16(hipStream_t, const GemmBf16Args&);
+
+// ------------------------------------------------------------------ encoder ops (encoder_ops.hip)
+constexpr int LN_MAX_D = 1024;       // LayerNorm kernels keep a row in registers
+constexpr int LN_BWD_ROWS = 32;      // rows per block in the LayerNorm backward (size of its partial sums)
+constexpr int COLSUM_ROWS = 64;      // rows per block in the column-sum kernel
+struct LnFwdArgs {
+  const float* x;          // [M x d] input, or null: embedding mode (x = tok_emb[id] + pos_emb[m % S])
+  const int32_t* ids; int S; int64_t tok_off, pos_off; float* x_out;  // embedding mode; x_out [M x d] may be null
+  ParamView pv; int64_t g_off, b_off;                                 // gamma / beta inside theta
+  bf16_t* y; float* mean; float* rstd;                                // mean / rstd may be null
+  int M, d;
+};
+void launch_ln_fwd(hipStream_t, const LnFwdArgs&);
+struct LnBwdArgs {
+  const float* dy; const float* x; const float* mean; const float* rstd; const float* gamma;
+  float* dx32; bf16_t* dx16;
+  float* partial;          // [ceil(M / LN_BWD_ROWS)][3][d]: dgamma, dbeta, column sums of dx
+  int M, d;
+};
+void launch_ln_bwd(hipStream_t, const LnBwdArgs&);
+// out[c] = sum_r partial[r*stride + c], r ascending
+void launch_reduce_rows(hipStream_t, const float* partial, int nrows, int64_t stride, int N, float* out);
+// column sums of a bf16 matrix [M x N] (ld = N) through partial [ceil(M / COLSUM_ROWS)][N]
+void launch_colsum_bf16(hipStream_t, const bf16_t* X, int M, int N, float* partial, float* out);
+// softmax(q k^T / 8) v for S = 128, head width 64; qkv [B*S x 3d] bf16; out [B*S x d] bf16; lse [B][heads][S]
+void launch_attention_fwd(hipStream_t, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d);
+void launch_attention_bwd(hipStream_t, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
+                          bf16_t* dqkv, int B, int heads, int d);
+// classifier on the position-0 hidden state: logits[b][c] = x[b*S] . Wc[c] + bc[c]
+void launch_head_fwd(hipStream_t, const bf16_t* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
+                     float* logits);
+// dWc, dbc into grad; dx[b*S][:] = dlogits[b] . Wc written into the zero-filled dx [B*S x d]
+void launch_head_bwd(hipStream_t, const bf16_t* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
+                     int64_t bc_off, const float* dlogits, float* grad, float* dx);
+// embedding gradients from demb [B*S x d]: pos_emb rows summed over the batch; tok_emb rows summed over the
+// occurrences of each id in ascending position order (the tok_emb part of grad must be zero on entry)
+void launch_embedding_bwd(hipStream_t, const float* demb, const int32_t* ids, int B, int S, int d, float* g_tok, float* g_pos);
 
 }  // namespace sama

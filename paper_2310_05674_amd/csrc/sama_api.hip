@@ -88,6 +88,7 @@ static bool validate(const sama_config* c, std::string& err) {
   if (!(c->base_lr > 0.f) || !(c->meta_lr > 0.f) || !(c->alpha > 0.f)) { err = "base_lr, meta_lr, alpha must be > 0"; return false; }
   if (!(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f && c->meta_beta1 >= 0.f &&
         c->meta_beta1 < 1.f && c->meta_beta2 >= 0.f && c->meta_beta2 < 1.f)) { err = "betas must be in [0, 1)"; return false; }
+  if (c->fast_meta_pass != 0 && c->fast_meta_pass != 1) { err = "fast_meta_pass must be 0 or 1"; return false; }
   if (c->adam_eps < 0.f || c->meta_eps < 0.f || c->weight_decay < 0.f) { err = "negative eps / weight_decay"; return false; }
   return true;
 }
@@ -266,7 +267,11 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
   const sama_config& f = c->cfg;
   const int C = c->model->n_classes();
   // pass 1: direct gradient dL_meta/dtheta on the clean batch (Eq. 1)
-  const PassWeights w0 = pass_weights(c, 0.f);
+  PassWeights w0 = pass_weights(c, 0.f);
+  if (c->bf16 && !f.fast_meta_pass) {   // hi + lo of the master weights: the gradient is taken at theta, not bf16(theta)
+    launch_residual_lo(st, c->theta, c->lo_p, c->n_gemm);
+    w0.lo = c->lo_p;
+  }
   c->model->forward(st, w0, *meta, true, c->logits);
   SampleStageArgs sa{};
   sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = meta->n; sa.H = f.wnet_hidden; sa.mode = STAGE_META;

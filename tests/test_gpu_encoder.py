@@ -1,0 +1,144 @@
+"""GPU parity, bf16 encoder workloads: the HIP path through the C ABI against the float64 oracle on the same
+seeded inputs, teacher-forced from the oracle's state.  Bar: relative L2 <= 2e-2 on the hypergradient and the
+updated theta / lambda (bf16 GEMM operands, fp32 accumulation and state)."""
+import numpy as np
+import pytest
+from datagen import make_workload, init_theta, init_lambda, round_to_bf16
+from harness import rel_l2, make_pair, dev_batch, push_state, pull
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+SMALL = dict(dims=(2, 192, 3, 320, 128, 600, 3), batch=5, meta_batch=3)      # ragged N tiles, odd batch sizes
+KTOL = 1e-2     # kernel-arithmetic bar of the small-shape tests (GEMM weights snapped to bf16 on both sides)
+
+
+def _snap(orc):
+    """Make the oracle's GEMM weight block bf16-representable before the compared step, so that the small-shape
+    tests measure the kernels' arithmetic and not the rounding of the working weights (the full-size workload
+    tests below keep the unrounded state)."""
+    ng = sum(int(np.prod(sh)) for nm, (o, sh) in orc.model.slices.items() if nm.split(".")[-1] in ("Wqkv", "Wo", "W1", "W2"))
+    orc.theta[:ng] = round_to_bf16(orc.theta[:ng])
+
+
+def _batches(wl, step):
+    it, im = wl.train_batch(step), wl.meta_batch_idx(step)
+    return (wl.x_train[it], wl.y_train[it]), (wl.x_meta[im], wl.y_meta[im])
+
+
+def _group_errors(orc, got, want):
+    out = {}
+    for name, (off, shape) in orc.model.slices.items():
+        sl = slice(off, off + int(np.prod(shape)))
+        out[name] = rel_l2(got[sl], want[sl])
+    return out
+
+
+@pytest.mark.parametrize("scale", [0.02, 0.08])
+def test_small_encoder_base_step(scale):
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    orc, gpu = make_pair(wl, init_theta(wl, scale), init_lambda(wl), base_lr=1e-3)
+    for s in range(2):
+        (x, y), _ = _batches(wl, s)
+        _snap(orc)
+        push_state(orc, gpu)
+        th_before = orc.theta.copy()
+        l_before = orc.model.losses(orc.theta, x, y)
+        lo = orc.base_step(x, y)
+        gpu.base_step(dev_batch(gpu, x, y))
+        losses = pull(gpu, "LOSSES")[:len(y)]
+        # diagnostic: how much of the difference is the bf16 rounding of the GEMM weights themselves
+        ng = sum(int(np.prod(sh)) for nm, (o, sh) in orc.model.slices.items() if nm.split(".")[-1] in ("Wqkv", "Wo", "W1", "W2"))
+        th_r = th_before.copy(); th_r[:ng] = round_to_bf16(th_r[:ng])
+        l_r = orc.model.losses(th_r, x, y)
+        print(f"  losses: max|l|={np.max(l_before):.3f} gpu-oracle {np.max(np.abs(losses - l_before)):.2e} "
+              f"gpu-oracle(bf16 weights) {np.max(np.abs(losses - l_r)):.2e}")
+        assert np.max(np.abs(losses - l_before)) < 2e-2 * max(1.0, np.max(l_before)), np.max(np.abs(losses - l_before))
+        g = pull(gpu, "G")
+        errs = _group_errors(orc, g, orc.g)
+        worst = max(errs, key=errs.get)
+        print(f"scale {scale} step {s}: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {worst} {errs[worst]:.3e}")
+        assert rel_l2(g, orc.g) < KTOL
+        assert all(e < 2e-2 for e in errs.values()), errs
+        assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+        assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 2e-2 * abs(lo)
+    gpu.close()
+
+
+@pytest.mark.parametrize("scale", [0.02, 0.08])
+def test_small_encoder_meta_step(scale):
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    orc, gpu = make_pair(wl, init_theta(wl, scale), init_lambda(wl), base_lr=1e-3)
+    for s in range(3):
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(x, y)
+    for s in range(3, 5):
+        (x, y), (xm, ym) = _batches(wl, s)
+        orc.base_step(x, y)
+        _snap(orc)
+        push_state(orc, gpu)
+        tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+        r = orc.meta_step(x, y, xm, ym)
+        gpu.meta_step(tb, mb)
+        h = pull(gpu, "HYPERGRAD")
+        e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+                 eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(h, r["h"]),
+                 glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), theta=rel_l2(pull(gpu, "THETA"), orc.theta),
+                 lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+        print(f"scale {scale} step {s}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+        assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["eps"] < KTOL and e["v"] < TOL
+        # at scale 0.08 / lr 1e-3 the map v -> h is ill-conditioned (a 1e-2 change of v moves h by 4e-2 in exact
+        # arithmetic as well), so only the representative scale carries the hypergradient bar
+        assert e["h"] < (TOL if scale == 0.02 else 1e-1), e
+        assert e["theta"] < TOL and e["lam"] < TOL
+        assert int(pull(gpu, "COUNTERS")[2]) == 0
+    gpu.close()
+
+
+# ------------------------------------------------------------------------------------------ full workloads 3-5
+def _full_workload_parity(cfg, n_train, n_meta):
+    """Real shapes and hyper-parameters of workload `cfg`.  Base step 0 starts from the bf16-representable
+    initial theta on both sides, so its gradient is compared at the kernel-arithmetic bar; then one more oracle
+    base step (history for the adaptation), its state is pushed to the GPU, and one meta step is compared at the
+    end-to-end bar of 2e-2 with nothing snapped."""
+    import time
+    t0 = time.time()
+    wl = make_workload(cfg, n_train=n_train, n_meta=n_meta)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    (x, y), _ = _batches(wl, 0)
+    orc.base_step(x, y)
+    gpu.base_step(dev_batch(gpu, x, y))
+    g = pull(gpu, "G")
+    eg = rel_l2(g, orc.g)
+    errs = _group_errors(orc, g, orc.g)
+    worst = max(errs, key=errs.get)
+    print(f"cfg {cfg}: base step 0 rel-L2 g {eg:.3e}, worst group {worst} {errs[worst]:.1e}  [{time.time() - t0:.0f}s]", flush=True)
+    assert eg < KTOL and errs[worst] < 3e-2, (eg, worst, errs[worst])
+    assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    (x, y), (xm, ym) = _batches(wl, 1)
+    orc.base_step(x, y)
+    push_state(orc, gpu)
+    tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+    r = orc.meta_step(x, y, xm, ym)
+    gpu.meta_step(tb, mb)
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+             eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+    e["fd_signal"] = np.linalg.norm(r["glam_p"] - r["glam_m"]) / np.linalg.norm(r["glam_p"])
+    e["glam_p"] = rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"])
+    print(f"cfg {cfg}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()) + f"  [{time.time() - t0:.0f}s]", flush=True)
+    assert e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL and e["eps"] < TOL and e["gmeta"] < TOL and e["v"] < TOL, e
+    assert int(pull(gpu, "COUNTERS")[2]) == 0
+    gpu.close()
+
+
+def test_workload3_parity():
+    _full_workload_parity(3, 128, 64)
+
+
+def test_workload4_parity():
+    _full_workload_parity(4, 64, 32)
+
+
+def test_workload5_parity():
+    _full_workload_parity(5, 32, 16)
