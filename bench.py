@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Throughput of SAMA's per-iteration hot path on one MI355X: meta-steps/sec.
+
+One "step" = one pass of the whole hot path at unroll U (default 1): U x sama_base_step + one sama_meta_step
+(direct-gradient pass, adaptation + norm, two +-eps passes, finite-difference combine, meta-Adam, nudge) on
+synthetic batches that are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (measured in a separate instrumented replay of the
+same steps with HIP events on the launch stream, so that the event records do not slow the timed region);
+`roofline.kernels` lists every kernel family.  `cpu_baseline` is the float64 oracle on the host cores on a
+bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
+PEAK_FP32_MATRIX_TFLOPS = 157.3
+
+
+def fwd_flops(wl, batch):
+    """Algorithmic flops of one forward pass of the base learner on `batch` samples (2 flops per MAC)."""
+    if wl.kind == "mlp":
+        return sum(2.0 * batch * wl.dims[i] * wl.dims[i + 1] for i in range(len(wl.dims) - 1))
+    L, d, heads, ffn, S, V, C = wl.dims
+    M = batch * S
+    per_layer = 2.0 * M * d * 3 * d + 2.0 * M * d * d + 2 * 2.0 * M * d * ffn + 2 * 2.0 * batch * heads * S * S * (d // heads)
+    return L * per_layer + 2.0 * batch * d * C
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=5, help="BASELINE.json config number 1..5")
+    ap.add_argument("--unroll", type=int, default=1)
+    ap.add_argument("--fast-meta-pass", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from datagen import make_workload, init_theta, init_lambda
+    import paper_2310_05674_amd as pkg
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg_id = args.workload
+    nb = 4                                                  # distinct synthetic batches cycled through
+    wl0 = make_workload(cfg_id, n_train=8, n_meta=8)        # shapes only
+    wl = make_workload(cfg_id, n_train=min(wl0.batch * nb, 12800) if cfg_id != 1 else None,
+                       n_meta=min(wl0.meta_batch * nb, 1280) if cfg_id != 1 else None)
+    th0, lam0 = init_theta(wl), init_lambda(wl)
+    cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch,
+                              base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
+                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass)
+    s = pkg.Sama(cfg, th0, lam0)
+    n, n16 = s.n, s.lib.sama_gemm_param_count(__import__("ctypes").byref(cfg))
+    batches = []
+    for k in range(nb):
+        it, im = wl.train_batch(k), wl.meta_batch_idx(k)
+        batches.append((s.batch(torch.as_tensor(np.ascontiguousarray(wl.x_train[it]), device=dev),
+                                torch.as_tensor(wl.y_train[it].astype(np.int32), device=dev)),
+                        s.batch(torch.as_tensor(np.ascontiguousarray(wl.x_meta[im]), device=dev),
+                                torch.as_tensor(wl.y_meta[im].astype(np.int32), device=dev))))
+
+    def step(k):
+        tb, mb = batches[k % nb]
+        for _ in range(args.unroll):
+            s.base_step(tb)
+        s.meta_step(tb, mb)
+
+    s.base_step(batches[0][0])                              # one step of Adam history before anything is timed
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k)
+    torch.cuda.synchronize(dev)
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    status = s.get_state("COUNTERS").cpu().numpy()
+    skipped = int(status[2])
+
+    out = {
+        "metric": "SAMA meta-steps/sec on 1 MI355X", "value": args.steps / elapsed, "unit": "meta-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"BASELINE.json configs[{cfg_id - 1}]: " +
+                   ("MLP " + "-".join(map(str, wl.dims)) if wl.kind == "mlp" else
+                    "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
+                   "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
+                   "wnet_hidden": wl.H, "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
+                   "last_step_skipped": bool(skipped)},
+    }
+
+    # ---------------------------------------------------------------- per-kernel roofline (instrumented replay)
+    if not args.no_roofline:
+        prof_steps = min(args.steps, 5)
+        s.profile(True)
+        for k in range(prof_steps):
+            step(k)
+        torch.cuda.synchronize(dev)
+        fam = s.profile_read()
+        s.profile(False)
+        kernels = {}
+        for name, (cnt, ms, units) in fam.items():
+            avg_us = 1e3 * ms / cnt
+            ent = {"launches_per_step": cnt / prof_steps, "avg_us": avg_us, "ms_per_step": ms / prof_steps}
+            if name.startswith("gemm_bf16") or name.startswith("attention"):
+                ent.update(bound="mfma", achieved=units / (ms * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
+            elif name == "gemm_f32":
+                ent.update(bound="mfma", achieved=units / (ms * 1e-3) / 1e12, peak=PEAK_FP32_MATRIX_TFLOPS, unit="TFLOP/s")
+            elif units > 0:
+                ent.update(bound="hbm", achieved=units / (ms * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s")
+            if "achieved" in ent:
+                ent["frac"] = ent["achieved"] / ent["peak"]
+            kernels[name] = ent
+        dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+        d = kernels[dom]
+        U = args.unroll
+        paper_flops = (3 * U + 5) * fwd_flops(wl, wl.batch)   # three-pass count of Sec. 3.3 (train and meta batches are equal here)
+        ew = [kernels[k] for k in ("adam", "adapt_norm", "perturb_lo", "residual_lo", "nudge") if k in kernels]
+        ew_bytes = sum(k["achieved"] * 1e9 * k["ms_per_step"] * 1e-3 for k in ew)
+        ew_ms = sum(k["ms_per_step"] for k in ew)
+        out["roofline"] = {
+            "kernel": dom, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
+            "unit": d.get("unit"), "frac": d.get("frac"), "traffic": None, "avg_us": d["avg_us"],
+            "elementwise_chain": {"bound": "hbm", "achieved": ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None,
+                                  "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                  "frac": ew_bytes / (ew_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if ew_ms > 0 else None,
+                                  "ms_per_step": ew_ms, "bytes_per_param": ew_bytes / n},
+            "step_algorithmic": {"flops_per_step": paper_flops, "achieved": paper_flops / (ms_per_step * 1e-3) / 1e12,
+                                 "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS if wl.bf16 else PEAK_FP32_MATRIX_TFLOPS},
+            "kernels": kernels,
+        }
+
+    # ---------------------------------------------------------------- oracle on the host cores (bounded sample)
+    if not args.no_cpu_baseline:
+        from oracle import models
+        from oracle.reweight import SamaOracle
+        cb = {1: wl.batch, 2: wl.batch, 3: 8, 4: 2, 5: 1}[cfg_id]       # samples per batch in the CPU sample
+        cm = min(cb, wl.meta_batch)
+        orc = SamaOracle(models.make_model(wl.kind, wl.dims), th0, lam0, base_lr=wl.base_lr, meta_lr=wl.meta_lr,
+                         alpha=wl.alpha)
+        it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
+        x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
+        orc.base_step(x, y)                                               # history (untimed)
+        reps = {1: 20, 2: 10}.get(cfg_id, 1)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for _ in range(args.unroll):
+                orc.base_step(x, y)
+            orc.meta_step(x, y, xm, ym)
+        tcpu = (time.perf_counter() - t0) / reps
+        scale = wl.batch / cb
+        try:
+            import threadpoolctl
+            threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+        except Exception:
+            threads = os.cpu_count()
+        out["cpu_baseline"] = {
+            "value": 1.0 / (tcpu * scale), "unit": "meta-steps/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{reps} meta step(s) of the float64 NumPy oracle at train/meta batch {cb}/{cm} instead of "
+                      f"{wl.batch}/{wl.meta_batch}; measured {tcpu:.2f} s per step, scaled by {scale:g} "
+                      f"(over-counts the batch-independent elementwise part)"}
+    s.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -150,6 +150,19 @@ sama_status sama_set_state(sama_ctx* ctx, int32_t which, const void* src /*DEVIC
  * which returns the text of the last failed sama_init on this thread. */
 const char* sama_last_error(const sama_ctx* ctx);
 
+/* Optional per-kernel timing, for roofline reports (not part of the method).  While enabled, every kernel launch
+ * of this library in the process is bracketed by two HIP events on its stream, which costs a few microseconds
+ * per launch: keep it off in throughput runs.  sama_profile_enable(ctx, 1) clears earlier records.
+ * sama_profile_read synchronises with the recorded events and returns, for kernel family `family`
+ * (0 .. sama_profile_family_count()-1): its name (HOST string owned by the library), the number of launches, their
+ * summed duration in milliseconds and their summed algorithmic work: flops for the GEMM and attention families,
+ * bytes for the others (Adam 28 B per parameter + 2 B per GEMM weight; adaptation 20 B; +-eps halves 12 B per
+ * GEMM weight; residual half 6 B; nudge 12 B + 2 B).  A two-term (hi + lo) GEMM launch counts 2 M N (2K). */
+int32_t sama_profile_family_count(void);
+sama_status sama_profile_enable(sama_ctx* ctx, int32_t on);
+sama_status sama_profile_read(sama_ctx* ctx, int32_t family, const char** name, int64_t* launches, double* total_ms,
+                              double* units);
+
 /* Free the host-side context.  The workspace stays with the caller.  Does not synchronise. */
 void sama_destroy(sama_ctx* ctx);
 

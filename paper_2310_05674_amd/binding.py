@@ -81,6 +81,9 @@ def load_library():
     L.sama_meta_step.restype = C.c_int; L.sama_meta_step.argtypes = [C.c_void_p, bp, bp]
     L.sama_get_state.restype = C.c_int; L.sama_get_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.sama_set_state.restype = C.c_int; L.sama_set_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    L.sama_profile_family_count.restype = C.c_int32; L.sama_profile_family_count.argtypes = []
+    L.sama_profile_enable.restype = C.c_int; L.sama_profile_enable.argtypes = [C.c_void_p, C.c_int32]
+    L.sama_profile_read.restype = C.c_int; L.sama_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.sama_last_error.restype = C.c_char_p; L.sama_last_error.argtypes = [C.c_void_p]
     L.sama_destroy.restype = None; L.sama_destroy.argtypes = [C.c_void_p]
     _lib = L
@@ -189,6 +192,19 @@ class Sama:
             t = self._dev_f32(value, self.nl if name in ("LAMBDA", "META_M", "META_V") else self.n)
         self._check(self.lib.sama_set_state(self.h, STATE[name], t.data_ptr()))
         self.stream.synchronize()      # `t` may be freed once we return
+
+    def profile(self, on):
+        self._check(self.lib.sama_profile_enable(self.h, 1 if on else 0))
+
+    def profile_read(self):
+        """{family name: (launches, total_ms, units)} for every family with at least one launch."""
+        out = {}
+        for f in range(self.lib.sama_profile_family_count()):
+            name, n, ms, u = C.c_char_p(), C.c_int64(), C.c_double(), C.c_double()
+            self._check(self.lib.sama_profile_read(self.h, f, C.byref(name), C.byref(n), C.byref(ms), C.byref(u)))
+            if n.value:
+                out[name.value.decode()] = (n.value, ms.value, u.value)
+        return out
 
     def close(self):
         if getattr(self, "h", None):

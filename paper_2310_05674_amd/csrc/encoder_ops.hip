@@ -479,8 +479,14 @@ __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb
 }
 }  // namespace
 
-void launch_ln_fwd(hipStream_t st, const LnFwdArgs& a) { k_ln_fwd<<<(a.M + 3) / 4, 256, 0, st>>>(a); }
-void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) { k_ln_bwd<<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a); }
+void launch_ln_fwd(hipStream_t st, const LnFwdArgs& a) {
+  ProfScope ps(st, F_LN_FWD, 6.0 * a.M * a.d);
+  k_ln_fwd<<<(a.M + 3) / 4, 256, 0, st>>>(a);
+}
+void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) {
+  ProfScope ps(st, F_LN_BWD, 14.0 * a.M * a.d);
+  k_ln_bwd<<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
+}
 void launch_reduce_rows(hipStream_t st, const float* partial, int nrows, int64_t stride, int N, float* out) {
   k_reduce_rows<<<(N + 255) / 256, 256, 0, st>>>(partial, nrows, stride, N, out);
 }
@@ -490,10 +496,12 @@ void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* pa
   launch_reduce_rows(st, partial, nrb, N, N, out);
 }
 void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d) {
+  ProfScope ps(st, F_ATTN_FWD, 4.0 * B * heads * 128.0 * 128.0 * 64.0);
   k_attn_fwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, lse, heads, d);
 }
 void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
                           bf16_t* dqkv, int B, int heads, int d) {
+  ProfScope ps(st, F_ATTN_BWD, 10.0 * B * heads * 128.0 * 128.0 * 64.0);
   k_attn_bwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d);
 }
 void launch_head_fwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,

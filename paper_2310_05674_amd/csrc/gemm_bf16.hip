@@ -152,6 +152,8 @@ const char* check_gemm_bf16(const GemmBf16Args& a) {
 
 void launch_gemm_bf16(hipStream_t st, const GemmBf16Args& a) {
   dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM);
+  const double flops = 2.0 * a.M * a.N * a.K * (a.B2 ? 2.0 : 1.0);   // hi + lo contracts over 2K
+  ProfScope ps(st, a.a_trans ? F_GEMM_TN : (a.b_trans ? F_GEMM_NT : F_GEMM_NN), flops);
   if (!a.a_trans && a.b_trans) k_gemm_bf16<false, true><<<grid, 256, 0, st>>>(a);
   else if (!a.a_trans && !a.b_trans) k_gemm_bf16<false, false><<<grid, 256, 0, st>>>(a);
   else if (a.a_trans && !a.b_trans) k_gemm_bf16<true, false><<<grid, 256, 0, st>>>(a);

@@ -6,6 +6,22 @@
 
 namespace sama {
 
+// ------------------------------------------------------------------ optional per-launch timing (profile.hip)
+enum Family {
+  F_GEMM_NT = 0, F_GEMM_NN, F_GEMM_TN, F_GEMM_F32, F_ATTN_FWD, F_ATTN_BWD, F_LN_FWD, F_LN_BWD, F_ADAM, F_ADAPT_NORM,
+  F_PERTURB, F_RESIDUAL, F_NUDGE, F_SAMPLE_STAGE, F_OTHER, F_COUNT
+};
+// While profiling is enabled every launcher brackets its kernel with two HIP events on the launch stream.
+// `units` = algorithmic flops (GEMM, attention) or algorithmic bytes (everything else) of that launch.
+struct ProfScope {
+  ProfScope(hipStream_t st, int family, double units);
+  ~ProfScope();
+  hipStream_t st_;
+  int idx_;
+};
+void prof_enable(bool on);
+bool prof_read(int family, const char** name, int64_t* launches, double* total_ms, double* units);
+
 constexpr int EW_MAX_BLOCKS = 4096;  // grid cap of the elementwise kernels (also the size of the norm partials)
 constexpr int MAX_BATCH = 2048;
 constexpr int MAX_WNET_HIDDEN = 256;

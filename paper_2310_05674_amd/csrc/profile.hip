@@ -1,0 +1,67 @@
+// Per-launch timing with HIP events on the launch stream, aggregated per kernel family.  Off by default: the
+// two event records per launch cost a few microseconds each, so timed throughput runs keep it disabled.
+#include <mutex>
+#include <vector>
+#include "kernels.h"
+
+namespace sama {
+namespace {
+struct Rec { int family; double units; hipEvent_t start, stop; };
+std::mutex g_mu;
+bool g_on = false;
+std::vector<Rec> g_recs;
+std::vector<hipEvent_t> g_pool;
+const char* kNames[F_COUNT] = {"gemm_bf16_nt", "gemm_bf16_nn", "gemm_bf16_tn", "gemm_f32", "attention_fwd", "attention_bwd",
+                               "layernorm_fwd", "layernorm_bwd", "adam", "adapt_norm", "perturb_lo", "residual_lo",
+                               "nudge", "sample_stage", "other"};
+hipEvent_t take_event() {
+  if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+}  // namespace
+
+ProfScope::ProfScope(hipStream_t st, int family, double units) : st_(st), idx_(-1) {
+  if (!g_on) return;
+  std::lock_guard<std::mutex> lk(g_mu);
+  Rec r{family, units, take_event(), take_event()};
+  if (r.start == nullptr || r.stop == nullptr) return;
+  (void)hipEventRecord(r.start, st);
+  g_recs.push_back(r);
+  idx_ = (int)g_recs.size() - 1;
+}
+ProfScope::~ProfScope() {
+  if (idx_ < 0) return;
+  std::lock_guard<std::mutex> lk(g_mu);
+  (void)hipEventRecord(g_recs[idx_].stop, st_);
+}
+
+void prof_enable(bool on) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (on) {
+    for (auto& r : g_recs) { g_pool.push_back(r.start); g_pool.push_back(r.stop); }
+    g_recs.clear();
+  }
+  g_on = on;
+}
+
+bool prof_read(int family, const char** name, int64_t* launches, double* total_ms, double* units) {
+  if (family < 0 || family >= F_COUNT) return false;
+  std::lock_guard<std::mutex> lk(g_mu);
+  int64_t n = 0; double ms = 0.0, u = 0.0;
+  for (auto& r : g_recs) {
+    if (r.family != family) continue;
+    if (hipEventSynchronize(r.stop) != hipSuccess) continue;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, r.start, r.stop) != hipSuccess) continue;
+    ms += t; u += r.units; ++n;
+  }
+  if (name) *name = kNames[family];
+  if (launches) *launches = n;
+  if (total_ms) *total_ms = ms;
+  if (units) *units = u;
+  return true;
+}
+
+}  // namespace sama

@@ -376,6 +376,19 @@ sama_status sama_set_state(sama_ctx* c, int32_t which, const void* src) {
   return check_hip(c, "sama_set_state");
 }
 
+int32_t sama_profile_family_count(void) { return F_COUNT; }
+sama_status sama_profile_enable(sama_ctx* c, int32_t on) {
+  if (!c) return SAMA_EINVAL;
+  prof_enable(on != 0);
+  return SAMA_OK;
+}
+sama_status sama_profile_read(sama_ctx* c, int32_t family, const char** name, int64_t* launches, double* total_ms,
+                              double* units) {
+  if (!c) return SAMA_EINVAL;
+  if (!prof_read(family, name, launches, total_ms, units)) return fail(c, SAMA_EINVAL, "unknown kernel family");
+  return SAMA_OK;
+}
+
 const char* sama_last_error(const sama_ctx* c) { return c ? c->err.c_str() : g_init_err.c_str(); }
 
 void sama_destroy(sama_ctx* c) { delete c; }
