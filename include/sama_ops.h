@@ -1,0 +1,53 @@
+/*
+ * sama_ops.h -- op-level entry points of libsama: the individual kernels of the hot path, exposed for
+ * per-kernel parity tests and roofline measurements.  Same conventions as sama.h: DEVICE pointers, work is
+ * enqueued on the given hipStream_t (NULL = default stream) and not waited for, no allocation.
+ */
+#ifndef SAMA_OPS_H
+#define SAMA_OPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+#include "sama.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M x N] = A . (B + B2) on the bf16 matrix cores with fp32 accumulation: the contraction behind every linear
+ * layer of the base learner (forward X W^T, dgrad dY W, wgrad dY^T X; Sec. 3.3 counts these passes).
+ * a_trans = 0: A stored [M][K] (lda >= K); 1: stored [K][M] (lda >= M).
+ * b_trans = 1: B stored [N][K] (ldb >= K), i.e. a weight matrix [out x in] used forward; 0: stored [K][N].
+ * B2: optional second bf16 term of the weight (the low half of a two-term split), same storage as B, or NULL.
+ * bias: optional fp32 [N] added to every row.  Outputs: C32 (fp32) and/or C16 (bf16), row stride ldc; either may
+ * be NULL.  Requirements: K % 64 == 0, M % 8 == 0, N % 8 == 0, lda/ldb % 8 == 0, ldc % 4 == 0, 16-byte aligned
+ * pointers.  Returns SAMA_EINVAL otherwise (nothing is launched). */
+sama_status sama_op_gemm_bf16(const void* A, int64_t lda, int32_t a_trans, const void* B, const void* B2, int64_t ldb,
+                              int32_t b_trans, int32_t M, int32_t N, int32_t K, const float* bias, float* C32, void* C16,
+                              int64_t ldc, void* hip_stream);
+
+/* Base solver update, Adam form (Sec. 2; Kingma & Ba Alg. 1 with bias correction at step t >= 1), over n fp32
+ * elements in place; theta16 (bf16 [n16], n16 <= n) receives the rounded leading part of theta, or NULL. */
+sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16,
+                         int64_t t, float lr, float beta1, float beta2, float eps, float weight_decay, void* hip_stream);
+
+/* Adaptation fused with the step size (Eq. 4-5, App. C): vdir = (du_adam/dg) . gmeta from the post-update moments at
+ * step t, then scalars[0] = alpha / ||vdir||_2, scalars[1] = ||vdir||_2, status[0] = 1 if the norm is zero or not
+ * finite (else 0).  partial: DEVICE scratch of 4096 doubles. */
+sama_status sama_op_adapt_norm(const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
+                               double* partial, int64_t n, int64_t t, float lr, float beta1, float beta2, float eps,
+                               float alpha, float* scalars, int64_t* status, void* hip_stream);
+
+/* Low halves of theta +- eps v against the bf16 working copy (Eq. 5): lo_p/lo_m[k] = bf16((theta[k] +- eps v[k]) -
+ * float(bf16(theta[k]))), eps read from DEVICE eps_ptr. */
+sama_status sama_op_perturb_lo(const float* theta, const float* vdir, const float* eps_ptr, void* lo_p, void* lo_m,
+                               int64_t n16, void* hip_stream);
+
+/* theta <- theta - eps v (end of Sec. 3.2), refreshing theta16 like sama_op_adam. */
+sama_status sama_op_nudge(float* theta, const float* vdir, const float* eps_ptr, void* theta16, int64_t n, int64_t n16,
+                          void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAMA_OPS_H */

@@ -86,6 +86,15 @@ def load_library():
     L.sama_profile_read.restype = C.c_int; L.sama_profile_read.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.sama_last_error.restype = C.c_char_p; L.sama_last_error.argtypes = [C.c_void_p]
     L.sama_destroy.restype = None; L.sama_destroy.argtypes = [C.c_void_p]
+    vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_float
+    L.sama_op_gemm_bf16.restype = C.c_int
+    L.sama_op_gemm_bf16.argtypes = [vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, i64, vp]
+    L.sama_op_adam.restype = C.c_int
+    L.sama_op_adam.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, f32, f32, f32, f32, vp]
+    L.sama_op_adapt_norm.restype = C.c_int
+    L.sama_op_adapt_norm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, f32, f32, vp, vp, vp]
+    L.sama_op_perturb_lo.restype = C.c_int; L.sama_op_perturb_lo.argtypes = [vp, vp, vp, vp, vp, i64, vp]
+    L.sama_op_nudge.restype = C.c_int; L.sama_op_nudge.argtypes = [vp, vp, vp, vp, i64, i64, vp]
     _lib = L
     return L
 
@@ -217,3 +226,51 @@ class Sama:
             self.close()
         except Exception:
             pass
+
+
+# ---------------------------------------------------------------------------------------------- op-level calls
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def op_gemm_bf16(A, B, *, a_trans=False, b_trans=True, B2=None, bias=None, out32=None, out16=None):
+    """C = A . (B + B2) (+ bias) through sama_op_gemm_bf16.  A, B, B2: 2-D contiguous torch.bfloat16 CUDA tensors in
+    the storage the flags describe; out32 / out16: preallocated [M, N] outputs."""
+    L = load_library()
+    K, M = (A.shape[0], A.shape[1]) if a_trans else (A.shape[1], A.shape[0])
+    N = B.shape[0] if b_trans else B.shape[1]
+    out = out32 if out32 is not None else out16
+    rc = L.sama_op_gemm_bf16(_p(A), A.stride(0), int(a_trans), _p(B), _p(B2), B.stride(0), int(b_trans), M, N, K, _p(bias),
+                             _p(out32), _p(out16), out.stride(0), _stream())
+    if rc != 0:
+        raise SamaError(rc, "sama_op_gemm_bf16 rejected the arguments")
+
+
+def op_adam(g, m, v, theta, theta16, n16, t, lr, beta1, beta2, eps, wd=0.0):
+    rc = load_library().sama_op_adam(_p(g), _p(m), _p(v), _p(theta), _p(theta16), theta.numel(), n16, t, lr, beta1, beta2, eps, wd, _stream())
+    if rc != 0:
+        raise SamaError(rc, "sama_op_adam rejected the arguments")
+
+
+def op_adapt_norm(g, m, v, gmeta, vdir, partial, t, lr, beta1, beta2, eps, alpha, scalars, status):
+    rc = load_library().sama_op_adapt_norm(_p(g), _p(m), _p(v), _p(gmeta), _p(vdir), _p(partial), g.numel(), t, lr, beta1, beta2,
+                                           eps, alpha, _p(scalars), _p(status), _stream())
+    if rc != 0:
+        raise SamaError(rc, "sama_op_adapt_norm rejected the arguments")
+
+
+def op_perturb_lo(theta, vdir, eps_t, lo_p, lo_m, n16):
+    rc = load_library().sama_op_perturb_lo(_p(theta), _p(vdir), _p(eps_t), _p(lo_p), _p(lo_m), n16, _stream())
+    if rc != 0:
+        raise SamaError(rc, "sama_op_perturb_lo rejected the arguments")
+
+
+def op_nudge(theta, vdir, eps_t, theta16, n16):
+    rc = load_library().sama_op_nudge(_p(theta), _p(vdir), _p(eps_t), _p(theta16), theta.numel(), n16, _stream())
+    if rc != 0:
+        raise SamaError(rc, "sama_op_nudge rejected the arguments")

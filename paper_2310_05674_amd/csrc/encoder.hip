@@ -122,9 +122,7 @@ class EncoderModel : public Model {
       // LN2
       LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds16_, lnpart_, M, d_};
       launch_ln_bwd(st, n2);
-      launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, grad + o.ln2g);
-      launch_reduce_rows(st, lnpart_ + d_, nblk, 3 * d_, d_, grad + o.ln2b);
-      launch_reduce_rows(st, lnpart_ + 2 * d_, nblk, 3 * d_, d_, grad + o.b2);
+      launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + o.ln2g, grad + o.ln2b, grad + o.b2);
       // FFN
       wgrad(st, ds16_, d_, fact_[l], ffn_, M, grad + o.W2);
       GemmBf16Args g = dgrad(w, ds16_, d_, o.W2, ffn_, M);
@@ -138,9 +136,7 @@ class EncoderModel : public Model {
       // LN1
       LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds16_, lnpart_, M, d_};
       launch_ln_bwd(st, n1);
-      launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, grad + o.ln1g);
-      launch_reduce_rows(st, lnpart_ + d_, nblk, 3 * d_, d_, grad + o.ln1b);
-      launch_reduce_rows(st, lnpart_ + 2 * d_, nblk, 3 * d_, d_, grad + o.bo);
+      launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + o.ln1g, grad + o.ln1b, grad + o.bo);
       // attention
       wgrad(st, ds16_, d_, ao_[l], d_, M, grad + o.Wo);
       g = dgrad(w, ds16_, d_, o.Wo, d_, M);
@@ -155,8 +151,7 @@ class EncoderModel : public Model {
     }
     LnBwdArgs n0{dx, pre0_, mean0_, rstd0_, w.theta + eg_, ds32_, nullptr, lnpart_, M, d_};
     launch_ln_bwd(st, n0);
-    launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, grad + eg_);
-    launch_reduce_rows(st, lnpart_ + d_, nblk, 3 * d_, d_, grad + eb_);
+    launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + eg_, grad + eb_, nullptr);
     launch_fill_f32(st, grad + tok_, 0.f, (int64_t)V_ * d_);
     launch_embedding_bwd(st, ds32_, (const int32_t*)b.x, B, S_, d_, grad + tok_, grad + pos_);
   }

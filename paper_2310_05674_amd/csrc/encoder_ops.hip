@@ -148,13 +148,26 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
   }
 }
 
-__global__ __launch_bounds__(256) void k_reduce_rows(const float* __restrict__ partial, int nrows, int64_t stride, int N,
-                                                     float* __restrict__ out) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= N) return;
-  float s = 0.f;
-  for (int r = 0; r < nrows; ++r) s += partial[(int64_t)r * stride + c];
-  out[c] = s;
+// out_v[c] = sum_r partial[r*stride + v*vstride + c] for up to three vectors v = blockIdx.y.  A block owns 32 columns;
+// eight row groups walk the rows with stride 8 (independent loads), then are added in a fixed order.
+struct ReduceRowsArgs { const float* partial; int nrows; int64_t stride, vstride; int N; float* out[3]; };
+__global__ __launch_bounds__(256) void k_reduce_rows(ReduceRowsArgs a) {
+  __shared__ float s_part[8][33];
+  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5, c = blockIdx.x * 32 + cl, v = blockIdx.y;
+  float acc = 0.f;
+  if (c < a.N) {
+    const float* p = a.partial + (int64_t)v * a.vstride + c;
+#pragma unroll 4
+    for (int r = rg; r < a.nrows; r += 8) acc += p[(int64_t)r * a.stride];
+  }
+  s_part[rg][cl] = acc;
+  __syncthreads();
+  if (rg == 0 && c < a.N) {
+    float t = s_part[0][cl];
+#pragma unroll
+    for (int g = 1; g < 8; ++g) t += s_part[g][cl];
+    a.out[v][c] = t;
+  }
 }
 
 __global__ __launch_bounds__(256) void k_colsum_partial_bf16(const bf16_t* __restrict__ X, int M, int N, float* __restrict__ partial) {
@@ -162,6 +175,7 @@ __global__ __launch_bounds__(256) void k_colsum_partial_bf16(const bf16_t* __res
   if (c >= N) return;
   const int r0 = blockIdx.y * COLSUM_ROWS;
   float s = 0.f;
+#pragma unroll 4
   for (int r = r0; r < r0 + COLSUM_ROWS && r < M; ++r) s += bf16_to_f32(X[(int64_t)r * N + c]);
   partial[(int64_t)blockIdx.y * N + c] = s;
 }
@@ -487,13 +501,20 @@ void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) {
   ProfScope ps(st, F_LN_BWD, 14.0 * a.M * a.d);
   k_ln_bwd<<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
 }
-void launch_reduce_rows(hipStream_t st, const float* partial, int nrows, int64_t stride, int N, float* out) {
-  k_reduce_rows<<<(N + 255) / 256, 256, 0, st>>>(partial, nrows, stride, N, out);
+void launch_reduce_rows(hipStream_t st, const float* partial, int nrows, int64_t stride, int64_t vstride, int N, float* out0,
+                        float* out1, float* out2) {
+  const int nv = out2 ? 3 : (out1 ? 2 : 1);
+  ProfScope ps(st, F_OTHER, 4.0 * nrows * N * nv);
+  ReduceRowsArgs a{partial, nrows, stride, vstride, N, {out0, out1, out2}};
+  k_reduce_rows<<<dim3((N + 31) / 32, nv), 256, 0, st>>>(a);
 }
 void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* partial, float* out) {
   const int nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
-  k_colsum_partial_bf16<<<dim3((N + 255) / 256, nrb), 256, 0, st>>>(X, M, N, partial);
-  launch_reduce_rows(st, partial, nrb, N, N, out);
+  {
+    ProfScope ps(st, F_OTHER, 2.0 * M * N);
+    k_colsum_partial_bf16<<<dim3((N + 255) / 256, nrb), 256, 0, st>>>(X, M, N, partial);
+  }
+  launch_reduce_rows(st, partial, nrb, N, 0, N, out, nullptr, nullptr);
 }
 void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d) {
   ProfScope ps(st, F_ATTN_FWD, 4.0 * B * heads * 128.0 * 128.0 * 64.0);
@@ -506,14 +527,17 @@ void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, 
 }
 void launch_head_fwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits) {
+  ProfScope ps(st, F_OTHER, 0.0);
   k_head_fwd<<<(B * C + 3) / 4, 256, 0, st>>>(x, S, d, B, C, pv, wc_off, bc_off, logits);
 }
 void launch_head_bwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
                      int64_t bc_off, const float* dlogits, float* grad, float* dx) {
+  ProfScope ps(st, F_OTHER, 0.0);
   k_head_bwd_w<<<(C * d + 255) / 256, 256, 0, st>>>(x, S, d, B, C, dlogits, grad + wc_off, grad + bc_off);
   k_head_bwd_x<<<(B * d + 255) / 256, 256, 0, st>>>(S, d, B, C, theta + wc_off, dlogits, dx);
 }
 void launch_embedding_bwd(hipStream_t st, const float* demb, const int32_t* ids, int B, int S, int d, float* g_tok, float* g_pos) {
+  ProfScope ps(st, F_OTHER, 4.0 * B * S * d);
   k_pos_grad<<<(S * d + 255) / 256, 256, 0, st>>>(demb, B, S, d, g_pos);
   k_tok_grad<<<B * S, 256, 0, st>>>(demb, ids, B * S, d, g_tok);
 }

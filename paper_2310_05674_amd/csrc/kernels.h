@@ -122,11 +122,12 @@ struct GemmBf16Args {
 };
 const char* check_gemm_bf16(const GemmBf16Args&);  // null if the shapes / alignments are supported
 void launch_gemm_bf16(hipStream_t, const GemmBf16Args&);
+void gemm_bf16_force_shape(int shape);  // tuning hook: 0 = heuristic, 1 = 128x128/4 waves, 2 = 256x128/8 waves, 3 = 256x128/4 waves
 
 // ------------------------------------------------------------------ encoder ops (encoder_ops.hip)
 constexpr int LN_MAX_D = 1024;       // LayerNorm kernels keep a row in registers
-constexpr int LN_BWD_ROWS = 32;      // rows per block in the LayerNorm backward (size of its partial sums)
-constexpr int COLSUM_ROWS = 64;      // rows per block in the column-sum kernel
+constexpr int LN_BWD_ROWS = 8;       // rows per block in the LayerNorm backward (size of its partial sums)
+constexpr int COLSUM_ROWS = 16;      // rows per block in the column-sum kernel
 struct LnFwdArgs {
   const float* x;          // [M x d] input, or null: embedding mode (x = tok_emb[id] + pos_emb[m % S])
   const int32_t* ids; int S; int64_t tok_off, pos_off; float* x_out;  // embedding mode; x_out [M x d] may be null
@@ -142,8 +143,9 @@ struct LnBwdArgs {
   int M, d;
 };
 void launch_ln_bwd(hipStream_t, const LnBwdArgs&);
-// out[c] = sum_r partial[r*stride + c], r ascending
-void launch_reduce_rows(hipStream_t, const float* partial, int nrows, int64_t stride, int N, float* out);
+// out_v[c] = sum_r partial[r*stride + v*vstride + c] for the non-null outputs v = 0, 1, 2, in a fixed order
+void launch_reduce_rows(hipStream_t, const float* partial, int nrows, int64_t stride, int64_t vstride, int N, float* out0,
+                        float* out1, float* out2);
 // column sums of a bf16 matrix [M x N] (ld = N) through partial [ceil(M / COLSUM_ROWS)][N]
 void launch_colsum_bf16(hipStream_t, const bf16_t* X, int M, int N, float* partial, float* out);
 // softmax(q k^T / 8) v for S = 128, head width 64; qkv [B*S x 3d] bf16; out [B*S x d] bf16; lse [B][heads][S]

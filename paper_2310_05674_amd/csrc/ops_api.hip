@@ -1,0 +1,73 @@
+// Op-level C entry points (include/sama_ops.h): thin argument checks around the kernel launchers.
+#include <math.h>
+#include "../../include/sama_ops.h"
+#include "kernels.h"
+
+using namespace sama;
+
+extern "C" {
+
+// Tuning hook (not declared in the public headers): block shape of the bf16 GEMM, 0 = heuristic.
+void sama_dev_gemm_shape(int32_t shape) { gemm_bf16_force_shape(shape); }
+
+sama_status sama_op_gemm_bf16(const void* A, int64_t lda, int32_t a_trans, const void* B, const void* B2, int64_t ldb,
+                              int32_t b_trans, int32_t M, int32_t N, int32_t K, const float* bias, float* C32, void* C16,
+                              int64_t ldc, void* hip_stream) {
+  if (!A || !B || (!C32 && !C16)) return SAMA_EINVAL;
+  GemmBf16Args g{};
+  g.A = (const bf16_t*)A; g.lda = lda; g.a_trans = a_trans ? 1 : 0;
+  g.B = (const bf16_t*)B; g.B2 = (const bf16_t*)B2; g.ldb = ldb; g.b_trans = b_trans ? 1 : 0;
+  g.M = M; g.N = N; g.K = K; g.ldc = ldc; g.bias = bias; g.C32 = C32; g.C16 = (bf16_t*)C16;
+  if (check_gemm_bf16(g) != nullptr) return SAMA_EINVAL;
+  (void)hipGetLastError();
+  launch_gemm_bf16((hipStream_t)hip_stream, g);
+  return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
+}
+
+sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16, int64_t t,
+                         float lr, float beta1, float beta2, float eps, float weight_decay, void* hip_stream) {
+  if (!g || !m || !v || !theta || n < 0 || n16 < 0 || n16 > n || t < 1) return SAMA_EINVAL;
+  if (((uintptr_t)g | (uintptr_t)m | (uintptr_t)v | (uintptr_t)theta) & 15 || ((uintptr_t)theta16 & 7)) return SAMA_EINVAL;
+  AdamArgs a{};
+  a.beta1 = beta1; a.one_m_beta1 = (float)(1.0 - (double)beta1); a.beta2 = beta2; a.one_m_beta2 = (float)(1.0 - (double)beta2);
+  a.lr_c1 = (float)((double)lr / (1.0 - pow((double)beta1, (double)t)));
+  a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)beta2, (double)t)));
+  a.eps = eps; a.weight_decay = weight_decay;
+  (void)hipGetLastError();
+  launch_adam((hipStream_t)hip_stream, g, m, v, theta, (bf16_t*)theta16, n, theta16 ? n16 : 0, a);
+  return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
+}
+
+sama_status sama_op_adapt_norm(const float* g, const float* m, const float* v, const float* gmeta, float* vdir, double* partial,
+                               int64_t n, int64_t t, float lr, float beta1, float beta2, float eps, float alpha, float* scalars,
+                               int64_t* status, void* hip_stream) {
+  if (!g || !m || !v || !gmeta || !vdir || !partial || !scalars || !status || n < 1 || t < 1) return SAMA_EINVAL;
+  if (((uintptr_t)g | (uintptr_t)m | (uintptr_t)v | (uintptr_t)gmeta | (uintptr_t)vdir) & 15) return SAMA_EINVAL;
+  const double c1 = 1.0 / (1.0 - pow((double)beta1, (double)t)), c2 = 1.0 / sqrt(1.0 - pow((double)beta2, (double)t));
+  AdaptArgs ad{};
+  ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)beta1); ad.one_m_beta2 = (float)(1.0 - (double)beta2);
+  ad.lr_c1_c2 = (float)((double)lr * c1 * c2); ad.c2 = (float)c2; ad.eps = eps;
+  (void)hipGetLastError();
+  launch_adapt_norm((hipStream_t)hip_stream, g, m, v, gmeta, vdir, partial, n, ad, alpha, scalars, status);
+  return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
+}
+
+sama_status sama_op_perturb_lo(const float* theta, const float* vdir, const float* eps_ptr, void* lo_p, void* lo_m, int64_t n16,
+                               void* hip_stream) {
+  if (!theta || !vdir || !eps_ptr || !lo_p || !lo_m || n16 < 0) return SAMA_EINVAL;
+  if ((((uintptr_t)theta | (uintptr_t)vdir) & 15) || (((uintptr_t)lo_p | (uintptr_t)lo_m) & 7)) return SAMA_EINVAL;
+  (void)hipGetLastError();
+  launch_perturb_lo((hipStream_t)hip_stream, theta, vdir, eps_ptr, (bf16_t*)lo_p, (bf16_t*)lo_m, n16);
+  return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
+}
+
+sama_status sama_op_nudge(float* theta, const float* vdir, const float* eps_ptr, void* theta16, int64_t n, int64_t n16,
+                          void* hip_stream) {
+  if (!theta || !vdir || !eps_ptr || n < 0 || n16 < 0 || n16 > n) return SAMA_EINVAL;
+  if ((((uintptr_t)theta | (uintptr_t)vdir) & 15) || ((uintptr_t)theta16 & 7)) return SAMA_EINVAL;
+  (void)hipGetLastError();
+  launch_nudge((hipStream_t)hip_stream, theta, vdir, eps_ptr, (bf16_t*)theta16, n, theta16 ? n16 : 0);
+  return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
+}
+
+}  // extern "C"
