@@ -36,6 +36,7 @@ class EncoderModel : public Model {
     }
     pre0_ = ws.take<float>(M * d_); mean0_ = ws.take<float>(M); rstd0_ = ws.take<float>(M);
     dX_[0] = ws.take<float>(M * d_); dX_[1] = ws.take<float>(M * d_);
+    res_[0] = ws.take<float>(M * d_); res_[1] = ws.take<float>(M * d_);
     ds32_ = ws.take<float>(M * d_); ds16_ = ws.take<bf16_t>(M * d_);
     dpre_ = ws.take<bf16_t>(M * ffn_); do_ = ws.take<bf16_t>(M * d_); dqkv_ = ws.take<bf16_t>(M * 3 * d_);
     const size_t nblk = (M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
@@ -59,7 +60,7 @@ class EncoderModel : public Model {
     const ParamView pv{w.theta, w.vdir, w.eps_ptr, w.sign};
     LnFwdArgs e{};
     e.x = nullptr; e.ids = (const int32_t*)b.x; e.S = S_; e.tok_off = tok_; e.pos_off = pos_; e.x_out = keep ? pre0_ : nullptr;
-    e.pv = pv; e.g_off = eg_; e.b_off = eb_; e.y = X_[0]; e.mean = keep ? mean0_ : nullptr; e.rstd = keep ? rstd0_ : nullptr;
+    e.pv = pv; e.g_off = eg_; e.b_off = eb_; e.y = X_[0]; e.y32 = res_[0]; e.mean = keep ? mean0_ : nullptr; e.rstd = keep ? rstd0_ : nullptr;
     e.M = M; e.d = d_;
     launch_ln_fwd(st, e);
     for (int l = 0; l < L_; ++l) {
@@ -72,25 +73,24 @@ class EncoderModel : public Model {
       launch_gemm_bf16(st, g);
       launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, B, heads_, d_);
       g = fwd_gemm(w, ao_[s], d_, o.Wo, d_, o.bo, M);
-      g.res16 = xin; g.C32 = pre1_[s];
+      g.res32 = res_[0]; g.C32 = pre1_[s];          // the residual stream stays fp32
       launch_gemm_bf16(st, g);
       LnFwdArgs n1{};
-      n1.x = pre1_[s]; n1.pv = pv; n1.g_off = o.ln1g; n1.b_off = o.ln1b; n1.y = x1_[s];
+      n1.x = pre1_[s]; n1.pv = pv; n1.g_off = o.ln1g; n1.b_off = o.ln1b; n1.y = x1_[s]; n1.y32 = res_[1];
       n1.mean = keep ? mean1_[s] : nullptr; n1.rstd = keep ? rstd1_[s] : nullptr; n1.M = M; n1.d = d_;
       launch_ln_fwd(st, n1);
       g = fwd_gemm(w, x1_[s], d_, o.W1, ffn_, o.b1, M);
       g.act = GEMM_ACT_GELU_FWD; g.C16_pre = fpre_[s]; g.C16 = fact_[s];
       launch_gemm_bf16(st, g);
       g = fwd_gemm(w, fact_[s], ffn_, o.W2, d_, o.b2, M);
-      g.res16 = x1_[s]; g.C32 = pre2_[s];
+      g.res32 = res_[1]; g.C32 = pre2_[s];
       launch_gemm_bf16(st, g);
       LnFwdArgs n2{};
-      n2.x = pre2_[s]; n2.pv = pv; n2.g_off = o.ln2g; n2.b_off = o.ln2b; n2.y = xout;
+      n2.x = pre2_[s]; n2.pv = pv; n2.g_off = o.ln2g; n2.b_off = o.ln2b; n2.y = xout; n2.y32 = res_[0];
       n2.mean = keep ? mean2_[s] : nullptr; n2.rstd = keep ? rstd2_[s] : nullptr; n2.M = M; n2.d = d_;
       launch_ln_fwd(st, n2);
     }
-    const bf16_t* xl = keep ? X_[L_] : X_[L_ & 1];
-    launch_head_fwd(st, xl, S_, d_, B, C_, pv, wc_, bc_, logits);
+    launch_head_fwd(st, res_[0], S_, d_, B, C_, pv, wc_, bc_, logits);   // res_[0] = fp32 output of the last LayerNorm
   }
 
   // dW[N x K] = dY^T . X into grad + woff
@@ -116,7 +116,7 @@ class EncoderModel : public Model {
     float* dx = dX_[0];
     float* dx_next = dX_[1];
     launch_fill_f32(st, dx, 0.f, (int64_t)M * d_);
-    launch_head_bwd(st, X_[L_], S_, d_, B, C_, w.theta, wc_, bc_, dlogits, grad, dx);
+    launch_head_bwd(st, res_[0], S_, d_, B, C_, w.theta, wc_, bc_, dlogits, grad, dx);
     for (int l = L_ - 1; l >= 0; --l) {
       const LayerOff& o = off_[l];
       // LN2
@@ -164,6 +164,7 @@ class EncoderModel : public Model {
   std::vector<float*> lse_, pre1_, mean1_, rstd1_, pre2_, mean2_, rstd2_;
   float *pre0_ = nullptr, *mean0_ = nullptr, *rstd0_ = nullptr;
   float* dX_[2] = {nullptr, nullptr};
+  float* res_[2] = {nullptr, nullptr};   // fp32 LayerNorm outputs: the residual stream of the current forward pass
   float* ds32_ = nullptr; bf16_t* ds16_ = nullptr; bf16_t* dpre_ = nullptr; bf16_t* do_ = nullptr; bf16_t* dqkv_ = nullptr;
   float* lnpart_ = nullptr; float* cspart_ = nullptr;
 };

@@ -67,10 +67,13 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
         g.x = fmaf(sc, gv.x, g.x); g.y = fmaf(sc, gv.y, g.y); g.z = fmaf(sc, gv.z, g.z); g.w = fmaf(sc, gv.w, g.w);
         b.x = fmaf(sc, bv.x, b.x); b.y = fmaf(sc, bv.y, b.y); b.z = fmaf(sc, bv.z, b.z); b.w = fmaf(sc, bv.w, b.w);
       }
+      const float4 o = make_float4(fmaf((xr[j].x - mu) * rstd, g.x, b.x), fmaf((xr[j].y - mu) * rstd, g.y, b.y),
+                                   fmaf((xr[j].z - mu) * rstd, g.z, b.z), fmaf((xr[j].w - mu) * rstd, g.w, b.w));
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(fmaf((xr[j].x - mu) * rstd, g.x, b.x)) | ((uint32_t)f32_to_bf16(fmaf((xr[j].y - mu) * rstd, g.y, b.y)) << 16);
-      pk.y = (uint32_t)f32_to_bf16(fmaf((xr[j].z - mu) * rstd, g.z, b.z)) | ((uint32_t)f32_to_bf16(fmaf((xr[j].w - mu) * rstd, g.w, b.w)) << 16);
+      pk.x = (uint32_t)f32_to_bf16(o.x) | ((uint32_t)f32_to_bf16(o.y) << 16);
+      pk.y = (uint32_t)f32_to_bf16(o.z) | ((uint32_t)f32_to_bf16(o.w) << 16);
       *reinterpret_cast<uint2*>(a.y + (int64_t)row * a.d + 4 * q) = pk;
+      if (a.y32 != nullptr) reinterpret_cast<float4*>(a.y32 + (int64_t)row * a.d)[q] = o;
     }
   }
 }
@@ -411,26 +414,26 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
 }
 
 // =========================================================================================== classifier head
-__global__ __launch_bounds__(256) void k_head_fwd(const bf16_t* __restrict__ x, int S, int d, int B, int C, ParamView pv,
+__global__ __launch_bounds__(256) void k_head_fwd(const float* __restrict__ x, int S, int d, int B, int C, ParamView pv,
                                                   int64_t wc_off, int64_t bc_off, float* __restrict__ logits) {
   const int lane = threadIdx.x & 63, idx = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (idx >= B * C) return;
   const int b = idx / C, c = idx - b * C;
   const float sc = pv.scale();
-  const bf16_t* xr = x + (int64_t)b * S * d;
+  const float* xr = x + (int64_t)b * S * d;
   float acc = 0.f;
-  for (int k = lane; k < d; k += 64) acc = fmaf(bf16_to_f32(xr[k]), pv.at(wc_off + (int64_t)c * d + k, sc), acc);
+  for (int k = lane; k < d; k += 64) acc = fmaf(xr[k], pv.at(wc_off + (int64_t)c * d + k, sc), acc);
   acc = wave_sum(acc);
   if (lane == 0) logits[idx] = acc + pv.at(bc_off + c, sc);
 }
 
-__global__ __launch_bounds__(256) void k_head_bwd_w(const bf16_t* __restrict__ x, int S, int d, int B, int C,
+__global__ __launch_bounds__(256) void k_head_bwd_w(const float* __restrict__ x, int S, int d, int B, int C,
                                                     const float* __restrict__ dlogits, float* __restrict__ gWc, float* __restrict__ gbc) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < C * d) {
     const int c = i / d, k = i - c * d;
     float s = 0.f;
-    for (int b = 0; b < B; ++b) s = fmaf(dlogits[b * C + c], bf16_to_f32(x[(int64_t)b * S * d + k]), s);
+    for (int b = 0; b < B; ++b) s = fmaf(dlogits[b * C + c], x[(int64_t)b * S * d + k], s);
     gWc[i] = s;
   }
   if (i < C) {
@@ -525,12 +528,12 @@ void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, 
   ProfScope ps(st, F_ATTN_BWD, 10.0 * B * heads * 128.0 * 128.0 * 64.0);
   k_attn_bwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d);
 }
-void launch_head_fwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
+void launch_head_fwd(hipStream_t st, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits) {
   ProfScope ps(st, F_OTHER, 0.0);
   k_head_fwd<<<(B * C + 3) / 4, 256, 0, st>>>(x, S, d, B, C, pv, wc_off, bc_off, logits);
 }
-void launch_head_bwd(hipStream_t st, const bf16_t* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
+void launch_head_bwd(hipStream_t st, const float* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
                      int64_t bc_off, const float* dlogits, float* grad, float* dx) {
   ProfScope ps(st, F_OTHER, 0.0);
   k_head_bwd_w<<<(C * d + 255) / 256, 256, 0, st>>>(x, S, d, B, C, dlogits, grad + wc_off, grad + bc_off);

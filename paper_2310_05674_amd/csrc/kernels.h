@@ -132,7 +132,7 @@ struct LnFwdArgs {
   const float* x;          // [M x d] input, or null: embedding mode (x = tok_emb[id] + pos_emb[m % S])
   const int32_t* ids; int S; int64_t tok_off, pos_off; float* x_out;  // embedding mode; x_out [M x d] may be null
   ParamView pv; int64_t g_off, b_off;                                 // gamma / beta inside theta
-  bf16_t* y; float* mean; float* rstd;                                // mean / rstd may be null
+  bf16_t* y; float* y32; float* mean; float* rstd;                    // y32 (fp32 copy for the residual path), mean, rstd may be null
   int M, d;
 };
 void launch_ln_fwd(hipStream_t, const LnFwdArgs&);
@@ -153,10 +153,10 @@ void launch_attention_fwd(hipStream_t, const bf16_t* qkv, bf16_t* out, float* ls
 void launch_attention_bwd(hipStream_t, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
                           bf16_t* dqkv, int B, int heads, int d);
 // classifier on the position-0 hidden state: logits[b][c] = x[b*S] . Wc[c] + bc[c]
-void launch_head_fwd(hipStream_t, const bf16_t* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
+void launch_head_fwd(hipStream_t, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits);
 // dWc, dbc into grad; dx[b*S][:] = dlogits[b] . Wc written into the zero-filled dx [B*S x d]
-void launch_head_bwd(hipStream_t, const bf16_t* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
+void launch_head_bwd(hipStream_t, const float* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
                      int64_t bc_off, const float* dlogits, float* grad, float* dx);
 // embedding gradients from demb [B*S x d]: pos_emb rows summed over the batch; tok_emb rows summed over the
 // occurrences of each id in ascending position order (the tok_emb part of grad must be zero on entry)
