@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
 PEAK_FP32_MATRIX_TFLOPS = 157.3
+# HBM-side bytes per launch of the dominant kernel family (forward GEMM) on workload 5, from the two rocprofv3 --pmc
+# runs summarised in profiles/bench_workload5_hbm_traffic.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, calibrated on
+# the library's own copy kernel).  Not measured for other workloads / kernels: reported as null there.
+MEASURED_TRAFFIC_BYTES = {(5, "gemm_bf16_nt"): 117.0e6}
 
 
 def fwd_flops(wl, batch):
@@ -138,7 +142,9 @@ def main():
         ew_ms = sum(k["ms_per_step"] for k in ew)
         out["roofline"] = {
             "kernel": dom, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
-            "unit": d.get("unit"), "frac": d.get("frac"), "traffic": None, "avg_us": d["avg_us"],
+            "unit": d.get("unit"), "frac": d.get("frac"),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg_id, dom)) if args.unroll == 1 and not args.fast_meta_pass else None,
+            "avg_us": d["avg_us"],
             "elementwise_chain": {"bound": "hbm", "achieved": ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None,
                                   "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                   "frac": ew_bytes / (ew_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if ew_ms > 0 else None,
