@@ -10,7 +10,7 @@ OUT = os.path.join(HERE, "libsama.so")
 OBJ = os.path.join(HERE, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument"] + os.environ.get("SAMA_EXTRA_HIPCC_FLAGS", "").split()
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-inline-asm"] + os.environ.get("SAMA_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def sources():

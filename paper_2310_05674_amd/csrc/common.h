@@ -51,7 +51,12 @@ struct ParamView {
   const float* vdir;
   const float* eps_ptr;
   float sign;
+  int flip_row;  // > 0: a kernel's rows >= flip_row see the opposite sign (the + and the - pass stacked in one launch)
   __device__ __forceinline__ float scale() const { return (eps_ptr != nullptr && sign != 0.f) ? sign * (*eps_ptr) : 0.f; }
+  __device__ __forceinline__ float scale_row(int row) const {
+    const float s = scale();
+    return (flip_row > 0 && row >= flip_row) ? -s : s;
+  }
   __device__ __forceinline__ float at(int64_t k, float s) const { return s != 0.f ? fmaf(s, vdir[k], theta[k]) : theta[k]; }
 };
 

@@ -27,17 +27,20 @@ class EncoderModel : public Model {
     const size_t M = (size_t)max_b * S_;
     X_.resize(L_ + 1); qkv_.resize(L_); lse_.resize(L_); ao_.resize(L_); pre1_.resize(L_); mean1_.resize(L_); rstd1_.resize(L_);
     x1_.resize(L_); fpre_.resize(L_); fact_.resize(L_); pre2_.resize(L_); mean2_.resize(L_); rstd2_.resize(L_);
-    for (int l = 0; l <= L_; ++l) X_[l] = ws.take<bf16_t>(M * d_);
+    // Forward-only passes run in activation slot 0 and ping-pong between X_[0] / X_[1]; the + and the - pass of
+    // Eq. 5 run stacked (2M rows), so those buffers are twice as tall.
+    for (int l = 0; l <= L_; ++l) X_[l] = ws.take<bf16_t>((l < 2 ? 2 : 1) * M * d_);
     for (int l = 0; l < L_; ++l) {
-      qkv_[l] = ws.take<bf16_t>(M * 3 * d_); lse_[l] = ws.take<float>((size_t)max_b * heads_ * S_);
-      ao_[l] = ws.take<bf16_t>(M * d_); pre1_[l] = ws.take<float>(M * d_); mean1_[l] = ws.take<float>(M); rstd1_[l] = ws.take<float>(M);
-      x1_[l] = ws.take<bf16_t>(M * d_); fpre_[l] = ws.take<bf16_t>(M * ffn_); fact_[l] = ws.take<bf16_t>(M * ffn_);
-      pre2_[l] = ws.take<float>(M * d_); mean2_[l] = ws.take<float>(M); rstd2_[l] = ws.take<float>(M);
+      const size_t R = (l == 0 ? 2 : 1) * M;
+      qkv_[l] = ws.take<bf16_t>(R * 3 * d_); lse_[l] = ws.take<float>((size_t)max_b * heads_ * S_);
+      ao_[l] = ws.take<bf16_t>(R * d_); pre1_[l] = ws.take<float>(R * d_); mean1_[l] = ws.take<float>(M); rstd1_[l] = ws.take<float>(M);
+      x1_[l] = ws.take<bf16_t>(R * d_); fpre_[l] = ws.take<bf16_t>(R * ffn_); fact_[l] = ws.take<bf16_t>(R * ffn_);
+      pre2_[l] = ws.take<float>(R * d_); mean2_[l] = ws.take<float>(M); rstd2_[l] = ws.take<float>(M);
     }
     pre0_ = ws.take<float>(M * d_); mean0_ = ws.take<float>(M); rstd0_ = ws.take<float>(M);
     dX_[0] = ws.take<float>(M * d_); dX_[1] = ws.take<float>(M * d_);
-    res_[0] = ws.take<float>(M * d_); res_[1] = ws.take<float>(M * d_);
-    ds32_ = ws.take<float>(M * d_); ds16_ = ws.take<bf16_t>(M * d_);
+    res_[0] = ws.take<float>(2 * M * d_); res_[1] = ws.take<float>(2 * M * d_);
+    ds32_ = ws.take<float>(M * d_); ds16_[0] = ws.take<bf16_t>(M * d_); ds16_[1] = ws.take<bf16_t>(M * d_);
     dpre_ = ws.take<bf16_t>(M * ffn_); do_ = ws.take<bf16_t>(M * d_); dqkv_ = ws.take<bf16_t>(M * 3 * d_);
     const size_t nblk = (M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
     const size_t wide = (size_t)(3 * d_ > ffn_ ? 3 * d_ : ffn_);
@@ -45,61 +48,84 @@ class EncoderModel : public Model {
     cspart_ = ws.take<float>(nrb * wide);
   }
 
-  GemmBf16Args fwd_gemm(const PassWeights& w, const bf16_t* A, int K, int64_t woff, int N, int64_t boff, int M) const {
-    GemmBf16Args g{};
-    g.A = A; g.lda = K; g.a_trans = 0;
-    g.B = w.hi + woff; g.B2 = w.lo ? w.lo + woff : nullptr; g.ldb = K; g.b_trans = 1;
-    g.M = M; g.N = N; g.K = K; g.ldc = N;
-    g.bias = w.theta + boff;
-    if (w.sign != 0.f) { g.bias_v = w.vdir + boff; g.beps = w.eps_ptr; g.bsign = w.sign; }
-    return g;
+  // One linear layer of `nw` stacked passes (pass k owns rows [k M, (k + 1) M) of every activation): the same
+  // epilogue `e` (its pointers are those of pass 0) for each pass, with that pass's weights.
+  void fwd_linear(hipStream_t st, const PassWeights* w, int nw, const bf16_t* A, int K, int64_t woff, int N, int64_t boff, int M,
+                  const GemmBf16Args& e) const {
+    GemmBf16Args g[2];
+    for (int k = 0; k < nw; ++k) {
+      g[k] = e;
+      const int64_t ro = (int64_t)k * M * N;
+      g[k].A = A + (int64_t)k * M * K; g[k].lda = K; g[k].a_trans = 0;
+      g[k].B = w[k].hi + woff; g[k].B2 = w[k].lo ? w[k].lo + woff : nullptr; g[k].ldb = K; g[k].b_trans = 1;
+      g[k].M = M; g[k].N = N; g[k].K = K; g[k].ldc = N;
+      g[k].bias = w[k].theta + boff;
+      if (w[k].sign != 0.f) { g[k].bias_v = w[k].vdir + boff; g[k].beps = w[k].eps_ptr; g[k].bsign = w[k].sign; }
+      if (e.res32) g[k].res32 = e.res32 + ro;
+      if (e.C32) g[k].C32 = e.C32 + ro;
+      if (e.C16) g[k].C16 = e.C16 + ro;
+      if (e.C16_pre) g[k].C16_pre = e.C16_pre + ro;
+    }
+    launch_gemm_bf16_batch(st, g, nw);
   }
 
-  void forward(hipStream_t st, const PassWeights& w, const sama_batch& b, bool keep, float* logits) override {
-    const int B = b.n, M = B * S_;
-    const ParamView pv{w.theta, w.vdir, w.eps_ptr, w.sign};
+  // nw = 1: one pass with weights w[0].  nw = 2: the theta + eps v and theta - eps v passes of Eq. 5 on the same
+  // batch, stacked along the row dimension (forward only, keep must be false); logits [nw B x C].
+  void run_forward(hipStream_t st, const PassWeights* w, int nw, const sama_batch& b, bool keep, float* logits) {
+    const int B = b.n, M = B * S_, R = nw * M;
+    ParamView pv{w[0].theta, w[0].vdir, w[0].eps_ptr, w[0].sign};
+    pv.flip_row = nw == 2 ? M : 0;
     LnFwdArgs e{};
-    e.x = nullptr; e.ids = (const int32_t*)b.x; e.S = S_; e.tok_off = tok_; e.pos_off = pos_; e.x_out = keep ? pre0_ : nullptr;
+    e.x = nullptr; e.ids = (const int32_t*)b.x; e.ids_rows = M; e.S = S_; e.tok_off = tok_; e.pos_off = pos_; e.x_out = keep ? pre0_ : nullptr;
     e.pv = pv; e.g_off = eg_; e.b_off = eb_; e.y = X_[0]; e.y32 = res_[0]; e.mean = keep ? mean0_ : nullptr; e.rstd = keep ? rstd0_ : nullptr;
-    e.M = M; e.d = d_;
+    e.M = R; e.d = d_;
     launch_ln_fwd(st, e);
     for (int l = 0; l < L_; ++l) {
       const int s = keep ? l : 0;                       // activation slot: forward-only passes reuse slot 0
       const bf16_t* xin = keep ? X_[l] : X_[l & 1];
       bf16_t* xout = keep ? X_[l + 1] : X_[(l + 1) & 1];
       const LayerOff& o = off_[l];
-      GemmBf16Args g = fwd_gemm(w, xin, d_, o.Wqkv, 3 * d_, o.bqkv, M);
+      GemmBf16Args g{};
       g.C16 = qkv_[s];
-      launch_gemm_bf16(st, g);
-      launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, B, heads_, d_);
-      g = fwd_gemm(w, ao_[s], d_, o.Wo, d_, o.bo, M);
+      fwd_linear(st, w, nw, xin, d_, o.Wqkv, 3 * d_, o.bqkv, M, g);
+      launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, nw * B, heads_, d_);
+      g = GemmBf16Args{};
       g.res32 = res_[0]; g.C32 = pre1_[s];          // the residual stream stays fp32
-      launch_gemm_bf16(st, g);
+      fwd_linear(st, w, nw, ao_[s], d_, o.Wo, d_, o.bo, M, g);
       LnFwdArgs n1{};
       n1.x = pre1_[s]; n1.pv = pv; n1.g_off = o.ln1g; n1.b_off = o.ln1b; n1.y = x1_[s]; n1.y32 = res_[1];
-      n1.mean = keep ? mean1_[s] : nullptr; n1.rstd = keep ? rstd1_[s] : nullptr; n1.M = M; n1.d = d_;
+      n1.mean = keep ? mean1_[s] : nullptr; n1.rstd = keep ? rstd1_[s] : nullptr; n1.M = R; n1.d = d_;
       launch_ln_fwd(st, n1);
-      g = fwd_gemm(w, x1_[s], d_, o.W1, ffn_, o.b1, M);
+      g = GemmBf16Args{};
       g.act = GEMM_ACT_GELU_FWD; g.C16_pre = fpre_[s]; g.C16 = fact_[s];
-      launch_gemm_bf16(st, g);
-      g = fwd_gemm(w, fact_[s], ffn_, o.W2, d_, o.b2, M);
+      fwd_linear(st, w, nw, x1_[s], d_, o.W1, ffn_, o.b1, M, g);
+      g = GemmBf16Args{};
       g.res32 = res_[1]; g.C32 = pre2_[s];
-      launch_gemm_bf16(st, g);
+      fwd_linear(st, w, nw, fact_[s], ffn_, o.W2, d_, o.b2, M, g);
       LnFwdArgs n2{};
       n2.x = pre2_[s]; n2.pv = pv; n2.g_off = o.ln2g; n2.b_off = o.ln2b; n2.y = xout; n2.y32 = res_[0];
-      n2.mean = keep ? mean2_[s] : nullptr; n2.rstd = keep ? rstd2_[s] : nullptr; n2.M = M; n2.d = d_;
+      n2.mean = keep ? mean2_[s] : nullptr; n2.rstd = keep ? rstd2_[s] : nullptr; n2.M = R; n2.d = d_;
       launch_ln_fwd(st, n2);
     }
-    launch_head_fwd(st, res_[0], S_, d_, B, C_, pv, wc_, bc_, logits);   // res_[0] = fp32 output of the last LayerNorm
+    pv.flip_row = nw == 2 ? B : 0;                  // the head's rows are samples
+    launch_head_fwd(st, res_[0], S_, d_, nw * B, C_, pv, wc_, bc_, logits);   // res_[0] = fp32 output of the last LayerNorm
   }
 
-  // dW[N x K] = dY^T . X into grad + woff
-  void wgrad(hipStream_t st, const bf16_t* dY, int N, const bf16_t* X, int K, int M, float* out) const {
+  void forward(hipStream_t st, const PassWeights& w, const sama_batch& b, bool keep, float* logits) override {
+    run_forward(st, &w, 1, b, keep, logits);
+  }
+  void forward_pair(hipStream_t st, const PassWeights& wp, const PassWeights& wm, const sama_batch& b, float* logits) override {
+    const PassWeights w[2] = {wp, wm};
+    run_forward(st, w, 2, b, false, logits);
+  }
+
+  // dW[N x K] = dY^T . X into `out`
+  GemmBf16Args wgrad(const bf16_t* dY, int N, const bf16_t* X, int K, int M, float* out) const {
     GemmBf16Args g{};
     g.A = dY; g.lda = N; g.a_trans = 1;
     g.B = X; g.ldb = K; g.b_trans = 0;
     g.M = N; g.N = K; g.K = M; g.ldc = K; g.C32 = out;
-    launch_gemm_bf16(st, g);
+    return g;
   }
   // dX[M x K] = dY[M x N] . W[N x K]
   GemmBf16Args dgrad(const PassWeights& w, const bf16_t* dY, int N, int64_t woff, int K, int M) const {
@@ -119,35 +145,37 @@ class EncoderModel : public Model {
     launch_head_bwd(st, res_[0], S_, d_, B, C_, w.theta, wc_, bc_, dlogits, grad, dx);
     for (int l = L_ - 1; l >= 0; --l) {
       const LayerOff& o = off_[l];
+      GemmBf16Args wg[4];   // the layer's four weight gradients leave in one launch at the end of the layer
       // LN2
-      LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds16_, lnpart_, M, d_};
+      LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds16_[0], lnpart_, M, d_};
       launch_ln_bwd(st, n2);
       launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + o.ln2g, grad + o.ln2b, grad + o.b2);
       // FFN
-      wgrad(st, ds16_, d_, fact_[l], ffn_, M, grad + o.W2);
-      GemmBf16Args g = dgrad(w, ds16_, d_, o.W2, ffn_, M);
+      wg[0] = wgrad(ds16_[0], d_, fact_[l], ffn_, M, grad + o.W2);
+      GemmBf16Args g = dgrad(w, ds16_[0], d_, o.W2, ffn_, M);
       g.act = GEMM_ACT_GELU_BWD; g.aux16 = fpre_[l]; g.C16 = dpre_;
       launch_gemm_bf16(st, g);
       launch_colsum_bf16(st, dpre_, M, ffn_, cspart_, grad + o.b1);
-      wgrad(st, dpre_, ffn_, x1_[l], d_, M, grad + o.W1);
+      wg[1] = wgrad(dpre_, ffn_, x1_[l], d_, M, grad + o.W1);
       g = dgrad(w, dpre_, ffn_, o.W1, d_, M);
       g.res32 = ds32_; g.C32 = dx_next;                       // + the residual branch
       launch_gemm_bf16(st, g);
       // LN1
-      LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds16_, lnpart_, M, d_};
+      LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds16_[1], lnpart_, M, d_};
       launch_ln_bwd(st, n1);
       launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + o.ln1g, grad + o.ln1b, grad + o.bo);
       // attention
-      wgrad(st, ds16_, d_, ao_[l], d_, M, grad + o.Wo);
-      g = dgrad(w, ds16_, d_, o.Wo, d_, M);
+      wg[2] = wgrad(ds16_[1], d_, ao_[l], d_, M, grad + o.Wo);
+      g = dgrad(w, ds16_[1], d_, o.Wo, d_, M);
       g.C16 = do_;
       launch_gemm_bf16(st, g);
       launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv_, B, heads_, d_);
       launch_colsum_bf16(st, dqkv_, M, 3 * d_, cspart_, grad + o.bqkv);
-      wgrad(st, dqkv_, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
+      wg[3] = wgrad(dqkv_, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
       g = dgrad(w, dqkv_, 3 * d_, o.Wqkv, d_, M);
       g.res32 = ds32_; g.C32 = dx;                            // gradient w.r.t. the layer input
       launch_gemm_bf16(st, g);
+      launch_gemm_bf16_batch(st, wg, 4);
     }
     LnBwdArgs n0{dx, pre0_, mean0_, rstd0_, w.theta + eg_, ds32_, nullptr, lnpart_, M, d_};
     launch_ln_bwd(st, n0);
@@ -165,7 +193,7 @@ class EncoderModel : public Model {
   float *pre0_ = nullptr, *mean0_ = nullptr, *rstd0_ = nullptr;
   float* dX_[2] = {nullptr, nullptr};
   float* res_[2] = {nullptr, nullptr};   // fp32 LayerNorm outputs: the residual stream of the current forward pass
-  float* ds32_ = nullptr; bf16_t* ds16_ = nullptr; bf16_t* dpre_ = nullptr; bf16_t* do_ = nullptr; bf16_t* dqkv_ = nullptr;
+  float* ds32_ = nullptr; bf16_t* ds16_[2] = {nullptr, nullptr}; bf16_t* dpre_ = nullptr; bf16_t* do_ = nullptr; bf16_t* dqkv_ = nullptr;
   float* lnpart_ = nullptr; float* cspart_ = nullptr;
 };
 }  // namespace

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= a.M) return;
   const int nq = a.d >> 2;  // float4 chunks per row
-  const float sc = a.pv.scale();
+  const float sc = a.pv.scale_row(row);
   float4 xr[4];
   float sum = 0.f;
 #pragma unroll
@@ -30,7 +30,7 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
       if (a.x != nullptr) {
         xr[j] = reinterpret_cast<const float4*>(a.x + (int64_t)row * a.d)[q];
       } else {
-        const int64_t to = a.tok_off + (int64_t)a.ids[row] * a.d + 4 * q, po = a.pos_off + (int64_t)(row % a.S) * a.d + 4 * q;
+        const int64_t to = a.tok_off + (int64_t)a.ids[a.ids_rows > 0 ? row % a.ids_rows : row] * a.d + 4 * q, po = a.pos_off + (int64_t)(row % a.S) * a.d + 4 * q;
         float4 t = *reinterpret_cast<const float4*>(a.pv.theta + to), p = *reinterpret_cast<const float4*>(a.pv.theta + po);
         if (sc != 0.f) {
           const float4 tv = *reinterpret_cast<const float4*>(a.pv.vdir + to), pvv = *reinterpret_cast<const float4*>(a.pv.vdir + po);
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(256) void k_head_fwd(const float* __restrict__ x, i
   const int lane = threadIdx.x & 63, idx = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (idx >= B * C) return;
   const int b = idx / C, c = idx - b * C;
-  const float sc = pv.scale();
+  const float sc = pv.scale_row(b);
   const float* xr = x + (int64_t)b * S * d;
   float acc = 0.f;
   for (int k = lane; k < d; k += 64) acc = fmaf(xr[k], pv.at(wc_off + (int64_t)c * d + k, sc), acc);

@@ -1,19 +1,25 @@
-// bf16 x bf16 -> fp32 contraction on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16) for the encoder's
-// linear layers: forward (X W^T), dgrad (dY W) and wgrad (dY^T X) are one kernel template over the storage of its
-// two operands.
+// bf16 x bf16 -> fp32 contraction on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16) for the encoder's linear
+// layers: forward (X W^T), dgrad (dY W) and wgrad (dY^T X) are one kernel template over the storage of its two
+// operands.
 //
-//   block tile 128 x 128 (4 waves) or 256 x 128 (8 waves), k slab 64, each wave owning a 64 x 64 accumulator
-//   LDS double buffer (one barrier per slab); three register sets keep the global loads of the next three slabs in
-//   flight behind the MFMAs of the current one
-//   an operand whose contraction index is contiguous in memory is staged as [row][k] and fetched with 16-byte reads;
-//   an operand whose contraction index is the strided one (dgrad's W, both operands of wgrad) is staged as it lies
-//   in memory, [k][row], and fetched with the transposing LDS read (ds_read_b64_tr_b16), so nothing is ever
-//   transposed through registers or scattered into LDS
-//   workgroup ids are remapped so that each XCD (own L2) works on a contiguous run of tiles
+//   operand slabs go global -> LDS directly (global_load_lds_dwordx4, 1 KB per wave instruction) into dense,
+//   XOR-swizzled stages, NSTAGE - 1 slabs in flight, one barrier per slab; no staging registers
+//   an operand whose contraction index is contiguous in memory is staged [row][k] and fetched with 16-byte reads;
+//   one whose contraction index is the strided one (dgrad's W, both operands of wgrad) is staged as it lies in
+//   memory, [k][row], and fetched with the transposing LDS read (ds_read_b64_tr_b16)
+//   the MFMA operands of k-step t + 1 are fetched while the MFMAs of step t issue, also across the slab boundary
+//   measured on MI355X: a CU ingests at most ~25-30 B/clk from L2 (about 100-128 outstanding 128-byte requests
+//   times the loaded L2 latency), so the block tile, not the MFMA rate, bounds the kernel: 256 x 256 tiles need
+//   32 B/clk per CU at the MFMA peak, 256 x 128 need 48, 128 x 128 need 64
+//   workgroup ids are remapped so that each XCD (own L2) works on a compact patch of tiles
 //   the accumulators leave through LDS so that every global access of the epilogue is a full row segment
 //
 // For the theta +- eps v passes of Eq. 5 and the direct-gradient pass the weight operand is hi + lo (two bf16
-// halves): the k loop simply runs twice, the second time over `B2`, into the same accumulators.
+// halves).  DUAL tiles stage the A slab once together with the hi and the lo slab of B and issue two MFMAs per A
+// operand, so A is neither loaded nor fetched twice.
+//
+// Several independent problems of one storage class can share a launch (the + and - pass of Eq. 5, the four weight
+// gradients of a layer): more tiles per launch for the small per-layer shapes.
 //
 // Fused epilogues: + bias (fp32, optionally perturbed), + residual (bf16 or fp32), GELU forward (writes both the
 // pre-activation and the activation), GELU backward (multiplies by gelu'(pre)), fp32 and/or bf16 stores.
@@ -27,32 +33,28 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gvoid;
+constexpr int LDS_MAX = 160 * 1024;
 
-constexpr int BN = 128, BK = 64;
-constexpr int LDK = BK + 8;        // [row][k] staging: 144-byte rows, conflict-free 16-byte reads
-constexpr int EPI_LD = 64 + 4;     // fp32 row stride of a wave's 32 x 64 epilogue tile
-
-// Block shapes: WROWS x 2 waves, each wave owning XT x 2 MFMA tiles of 32 x 32:
-//   <2,2> 128 x 128, 4 waves of 64 x 64, two blocks per CU: keeps every CU busy on small problems
-//   <4,2> 256 x 128, 8 waves of 64 x 64, one block per CU
-//   <2,4> 256 x 128, 4 waves of 128 x 64, one block per CU: fewest LDS operand reads per MFMA
-// The 256-row tiles move 25% fewer operand bytes per flop through L2 and the vector memory path.
-template <int WROWS, int XT>
-struct Shape {
-  static constexpr int THREADS = WROWS * 128;
-  static constexpr int WM = 32 * XT;         // rows of a wave tile
-  static constexpr int BM = WROWS * WM;
-  static constexpr int LDRA = BM + 32;       // [k][row] staging of A: 320 / 576-byte rows, conflict-free transposing reads
-  static constexpr int LDRB = BN + 32;
-  static constexpr int TILE_A = (BM * LDK > BK * LDRA) ? BM * LDK : BK * LDRA;
-  static constexpr int TILE_B = BK * LDRB;   // >= BN * LDK
-  static constexpr int STAGE = TILE_A + TILE_B;
-  static constexpr int LDS_BYTES = 2 * STAGE * 2;
-  static constexpr int NA = BM * 8 / THREADS;   // 16-byte pieces of the A slab per thread (4 or 8)
-  static constexpr int NB = 1024 / THREADS;     // of the B slab (4 or 2)
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_, int NSTAGE_, bool DUAL_>
+struct Tile {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_, NSTAGE = NSTAGE_;
+  static constexpr bool DUAL = DUAL_;
+  static constexpr int WAVES = WGM * WGN, THREADS = WAVES * 64;
+  static constexpr int WM = BM / WGM, WN = BN / WGN, XT = WM / 32, YT = WN / 32;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + (DUAL ? 2 : 1) * B_BYTES;
+  static constexpr int NLA = A_BYTES / 1024 / WAVES, NLB = B_BYTES / 1024 / WAVES;   // wave-level 1 KB loads per slab
+  static constexpr int NL = NLA + (DUAL ? 2 : 1) * NLB;
+  static_assert(LDS_MAX >= NSTAGE * STAGE_BYTES, "stages exceed the 160 KB of LDS");
+  static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES;
+  static constexpr int EPI_LD = WN + 4;
+  static constexpr int LDS_EPI = WAVES * 32 * EPI_LD * 4;
+  static constexpr int LDS_BYTES = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
+  static_assert(A_BYTES % (1024 * WAVES) == 0 && B_BYTES % (1024 * WAVES) == 0, "slab must split into whole wave loads");
+  static_assert(NL * (NSTAGE - 2) <= 63, "vmcnt range");
 };
 
-// erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7), sharing exp(-x^2) with the Gaussian density
 __device__ __forceinline__ void erf_and_gauss(float z, float& erfz, float& ez2) {
   const float az = fabsf(z);
   const float t = __frcp_rn(fmaf(0.3275911f, az, 1.f));
@@ -68,182 +70,239 @@ __device__ __forceinline__ float gelu_f(float x) {
 }
 __device__ __forceinline__ float dgelu_f(float x) {
   float e, g;
-  erf_and_gauss(x * 0.70710678118654752f, e, g);   // g = exp(-x^2 / 2)
+  erf_and_gauss(x * 0.70710678118654752f, e, g);
   return fmaf(x * 0.39894228040143268f, g, 0.5f * (1.f + e));
 }
 
-// One 16-byte piece (i-th of this thread) of a ROWS-row x 64-k operand slab, global -> register.  KC = true:
-// storage [rows][k]; false: storage [k][rows].  Rows past `nrows` are clamped to the last valid row (their
-// products land in output rows / columns that the epilogue never stores), so every load is unconditional and in
-// bounds.
-template <bool KC, int ROWS, int THREADS>
-__device__ __forceinline__ uint4 load_piece(const bf16_t* __restrict__ P, int64_t ld, int row0, int nrows, int k0, int i) {
-  const int c = threadIdx.x + THREADS * i;
+// Byte offset (relative to the slab's first element in global memory) of the 16-byte piece that belongs at byte
+// `ldsoff` of an operand's dense LDS stage.
+//   KC (contraction contiguous, storage [rows][k]): stage [R][BK]; the 16-byte chunk index within a row is XORed
+//     with (row / RP) % NCH so that 16 consecutive rows at one logical chunk fill all 64 banks.
+//   KS (contraction strided, storage [k][rows]): stage [BK][R]; the 64-byte chunk index within a k-row is XORed with
+//     (k-row / RP) % W (RP = k-rows per 256 bytes, W = min(chunks per k-row, 4)) so that the four k-rows one
+//     transposing read touches fill all 64 banks.
+// Rows past `nrows` are clamped (their products land in outputs the epilogue never stores).
+template <bool KC, int R, int BK>
+__device__ __forceinline__ uint32_t piece_offset(int ldsoff, int row0, int nrows, int64_t ld) {
   if (KC) {
-    const int row = min(row0 + (c >> 3), nrows - 1), kc = c & 7;
-    return *reinterpret_cast<const uint4*>(P + (int64_t)row * ld + k0 + kc * 8);
+    constexpr int RB = BK * 2, RP = 256 / RB, NCH = RB / 16;
+    const int r = ldsoff / RB, p = (ldsoff % RB) / 16;
+    const int c = p ^ ((r / RP) % NCH);
+    return (uint32_t)(((int64_t)min(row0 + r, nrows - 1) * ld + c * 8) * 2);
   } else {
-    constexpr int CPR = ROWS / 8;    // 16-byte chunks per k-row
-    const int k = c / CPR, rs = min(row0 + (c % CPR) * 8, nrows - 8);
-    return *reinterpret_cast<const uint4*>(P + (int64_t)(k0 + k) * ld + rs);
-  }
-}
-template <bool KC, int ROWS, int THREADS>
-__device__ __forceinline__ void store_piece(bf16_t* __restrict__ S, int i, const uint4& v) {
-  const int c = threadIdx.x + THREADS * i;
-  if (KC) *reinterpret_cast<uint4*>(S + (c >> 3) * LDK + (c & 7) * 8) = v;
-  else {
-    constexpr int CPR = ROWS / 8;
-    *reinterpret_cast<uint4*>(S + (c / CPR) * (ROWS + 32) + (c % CPR) * 8) = v;
+    constexpr int RBS = R * 2, RP = RBS >= 256 ? 1 : 256 / RBS, W = RBS / 64 < 4 ? RBS / 64 : 4;
+    const int kr = ldsoff / RBS, q16 = (ldsoff % RBS) / 16;
+    const int ql = (((q16 >> 2) ^ ((kr / RP) % W)) << 2) | (q16 & 3);
+    return (uint32_t)(((int64_t)kr * ld + min(row0 + ql * 8, nrows - 8)) * 2);
   }
 }
 
-// The 8 contraction values k = ks*16 + 8*(lane/32) + 0..7 of tile row (rbase + lane%32), as an MFMA operand.
-template <bool KC, int LDR>
-__device__ __forceinline__ bf16x8 fetch_operand(const bf16_t* __restrict__ S, int rbase, int ks, int lane) {
+// MFMA operand (8 contraction values k = ks*16 + 8*(lane/32) + 0..7 of tile row tb + lane%32) out of a swizzled stage.
+// `lo` is the lane-dependent part precomputed by fetch_lane_offset, `tb` the first row of the 32-row tile.
+template <bool KC, int R, int BK>
+__device__ __forceinline__ int fetch_lane_offset(int lane, int ks_or_tile) {
   if (KC) {
-    return *reinterpret_cast<const bf16x8*>(S + (rbase + (lane & 31)) * LDK + ks * 16 + 8 * (lane >> 5));
+    constexpr int RB = BK * 2, RP = 256 / RB, NCH = RB / 16;
+    const int rl = lane & 31, hi = lane >> 5;
+    const int s = (rl / RP) % NCH;
+    return rl * RB + (((2 * ks_or_tile + hi) ^ s) * 16);                  // per ks
   } else {
-    // Transposing read: in every group of 16 lanes, lane j addresses 4 consecutive elements of k-row (j/4) at
-    // column 4*(j%4); lane i of the group receives column i of those four k-rows.
+    constexpr int RBS = R * 2, RP = RBS >= 256 ? 1 : 256 / RBS, W = RBS / 64 < 4 ? RBS / 64 : 4;
     const int g = lane >> 4, j = lane & 15;
-    const bf16_t* p = S + (ks * 16 + 8 * (g >> 1) + (j >> 2)) * LDR + rbase + 16 * (g & 1) + 4 * (j & 3);
-    union { bf16x8 v; s16x4 h[2]; } u;
-    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * LDR));
-    return u.v;
+    const int cc = ks_or_tile;                                            // 64-byte chunk of the tile = tile_row0 / 32
+    const int kr = 8 * (g >> 1) + (j >> 2);                               // (kr / RP) % W is the same for kr + 4 and kr + 16
+    return kr * RBS + ((cc ^ ((kr / RP) % W)) * 64) + (16 * (g & 1) + 4 * (j & 3)) * 2;   // per tile
   }
 }
 
-template <typename SH, int XT, bool A_KC, bool B_KC>
-__device__ __forceinline__ void compute_slab(const bf16_t* __restrict__ As, const bf16_t* __restrict__ Bs, int wr, int wc, int lane,
-                                             f32x16 (&acc)[XT][2]) {
-#pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) {
-    bf16x8 av[XT], bv[2];
-#pragma unroll
-    for (int x = 0; x < XT; ++x) av[x] = fetch_operand<A_KC, SH::LDRA>(As, wr + x * 32, ks, lane);
-#pragma unroll
-    for (int y = 0; y < 2; ++y) bv[y] = fetch_operand<B_KC, SH::LDRB>(Bs, wc + y * 32, ks, lane);
-#pragma unroll
-    for (int x = 0; x < XT; ++x)
-#pragma unroll
-      for (int y = 0; y < 2; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[x], bv[y], acc[x][y], 0, 0, 0);
-  }
-}
+struct GemmBatch {
+  GemmBf16Args p[GEMM_MAX_BATCH];
+  int first_tile[GEMM_MAX_BATCH + 1];   // tile ids [first_tile[k], first_tile[k + 1]) belong to problem k
+  int count, group;
+};
 
-template <int WROWS, int XT, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(WROWS * 128) void k_gemm_bf16(GemmBf16Args a, int gx, int ntiles, int tiles_per_xcd) {
-  typedef Shape<WROWS, XT> SH;
-  constexpr int BM = SH::BM, NT = SH::THREADS;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wr = (wave >> 1) * SH::WM, wc = (wave & 1) * 64;
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous run of row-major tiles so that
-  // the A row panels and B column panels it touches stay in its own L2.
-  const int tile = (blockIdx.x & 7) * tiles_per_xcd + (blockIdx.x >> 3);
-  if (tile >= ntiles) return;
-  const int i0 = (tile / gx) * BM, j0 = (tile % gx) * BN;
+template <typename T, bool A_KC, bool B_KC>
+__global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int ntiles, int tiles_per_xcd) {
+  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, XT = T::XT, YT = T::YT, NSTAGE = T::NSTAGE, WAVES = T::WAVES;
+  constexpr bool DUAL = T::DUAL;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wr = (wave / T::WGN) * T::WM, wc = (wave % T::WGN) * T::WN;
+  // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous run of tile ids, and
+  // tile ids walk down `group` tile rows before moving one tile column to the right, so that the tiles in flight on
+  // one XCD form a compact patch (few distinct A and B panels in its L2).
+  int pid = (blockIdx.x & 7) * tiles_per_xcd + (blockIdx.x >> 3);
+  if (pid >= ntiles) return;
+  int prob = 0;
+#pragma unroll
+  for (int k = 1; k < GEMM_MAX_BATCH; ++k)
+    if (k < batch.count && pid >= batch.first_tile[k]) prob = k;
+  pid -= batch.first_tile[prob];
+  const GemmBf16Args& a = batch.p[prob];
+  const int group = batch.group;
+  const int gx = (a.N + BN - 1) / BN, gy = (a.M + BM - 1) / BM;
+  const int width = group * gx, grp = pid / width, first = grp * group;
+  const int gsz = min(gy - first, group);
+  const int ti = first + (pid % width) % gsz, tj = (pid % width) / gsz;
+  const int i0 = ti * BM, j0 = tj * BN;
 
-  f32x16 acc[XT][2];
+  f32x16 acc[XT][YT];
 #pragma unroll
   for (int x = 0; x < XT; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < YT; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   const int nk = a.K / BK;
-  const int iters = (a.B2 != nullptr) ? 2 * nk : nk;
-  // Three register sets rotate through the slabs: while slab i is multiplied out of LDS, slabs i+1 .. i+3 are in
-  // registers or still in flight, so a slab's global loads have two to three slab-times to land.  (Named scalars
-  // and branch-free steady state: the sets must stay in registers and the wait counters exact.)
-  uint4 a00, a01, a02, a03, a04, a05, a06, a07, b00, b01, b02, b03, a10, a11, a12, a13, a14, a15, a16, a17, b10, b11, b12, b13,
-      a20, a21, a22, a23, a24, a25, a26, a27, b20, b21, b22, b23;
-#define SAMA_LOAD(SL, S)                                                                          \
-  {                                                                                               \
-    const int sl_ = (SL);                                                                         \
-    const int kk_ = (sl_ >= nk ? sl_ - nk : sl_) * BK;                                            \
-    const bf16_t* bp_ = sl_ >= nk ? a.B2 : a.B;                                                   \
-    a##S##0 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 0);                              \
-    a##S##1 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 1);                              \
-    a##S##2 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 2);                              \
-    a##S##3 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 3);                              \
-    if (SH::NA > 4) {                                                                             \
-      a##S##4 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 4);                            \
-      a##S##5 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 5);                            \
-      a##S##6 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 6);                            \
-      a##S##7 = load_piece<A_KC, BM, NT>(a.A, a.lda, i0, a.M, kk_, 7);                            \
-    }                                                                                             \
-    b##S##0 = load_piece<B_KC, BN, NT>(bp_, a.ldb, j0, a.N, kk_, 0);                              \
-    b##S##1 = load_piece<B_KC, BN, NT>(bp_, a.ldb, j0, a.N, kk_, 1);                              \
-    if (SH::NB > 2) {                                                                             \
-      b##S##2 = load_piece<B_KC, BN, NT>(bp_, a.ldb, j0, a.N, kk_, 2);                            \
-      b##S##3 = load_piece<B_KC, BN, NT>(bp_, a.ldb, j0, a.N, kk_, 3);                            \
-    }                                                                                             \
-  }
-#define SAMA_STORE(STG, S)                                                                        \
-  {                                                                                               \
-    bf16_t* sa_ = smem + (STG) * SH::STAGE;                                                       \
-    bf16_t* sb_ = sa_ + SH::TILE_A;                                                               \
-    store_piece<A_KC, BM, NT>(sa_, 0, a##S##0); store_piece<A_KC, BM, NT>(sa_, 1, a##S##1);       \
-    store_piece<A_KC, BM, NT>(sa_, 2, a##S##2); store_piece<A_KC, BM, NT>(sa_, 3, a##S##3);       \
-    if (SH::NA > 4) {                                                                             \
-      store_piece<A_KC, BM, NT>(sa_, 4, a##S##4); store_piece<A_KC, BM, NT>(sa_, 5, a##S##5);     \
-      store_piece<A_KC, BM, NT>(sa_, 6, a##S##6); store_piece<A_KC, BM, NT>(sa_, 7, a##S##7);     \
-    }                                                                                             \
-    store_piece<B_KC, BN, NT>(sb_, 0, b##S##0); store_piece<B_KC, BN, NT>(sb_, 1, b##S##1);       \
-    if (SH::NB > 2) {                                                                             \
-      store_piece<B_KC, BN, NT>(sb_, 2, b##S##2); store_piece<B_KC, BN, NT>(sb_, 3, b##S##3);     \
-    }                                                                                             \
-  }
-#define SAMA_COMPUTE(I)                                                                           \
-  {                                                                                               \
-    const bf16_t* As_ = smem + ((I) & 1) * SH::STAGE;                                             \
-    compute_slab<SH, XT, A_KC, B_KC>(As_, As_ + SH::TILE_A, wr, wc, lane, acc);                   \
-  }
-  // slab I: start the loads of slab I+3 into set L (the set slab I came from); multiply slab I out of its LDS
-  // stage; move slab I+1 from set T into the other stage (last read during slab I-1, before the previous barrier)
-#define SAMA_PHASE_FULL(I, L, T)                                                                  \
-  {                                                                                               \
-    SAMA_LOAD((I) + 3, L)                                                                         \
-    SAMA_COMPUTE(I)                                                                               \
-    SAMA_STORE(((I) + 1) & 1, T)                                                                  \
-    __syncthreads();                                                                              \
-  }
-#define SAMA_PHASE(I, L, T)                                                                       \
-  {                                                                                               \
-    if ((I) + 3 < iters) SAMA_LOAD((I) + 3, L)                                                    \
-    SAMA_COMPUTE(I)                                                                               \
-    if ((I) + 1 < iters) SAMA_STORE(((I) + 1) & 1, T)                                             \
-    __syncthreads();                                                                              \
-  }
-  SAMA_LOAD(0, 0)
-  if (iters > 1) SAMA_LOAD(1, 1)
-  if (iters > 2) SAMA_LOAD(2, 2)
-  SAMA_STORE(0, 0)
-  __syncthreads();
-  int it = 0;
-  for (; it + 5 < iters; it += 3) {
-    SAMA_PHASE_FULL(it, 0, 1)
-    SAMA_PHASE_FULL(it + 1, 1, 2)
-    SAMA_PHASE_FULL(it + 2, 2, 0)
-  }
-  for (; it < iters; it += 3) {
-    SAMA_PHASE(it, 0, 1)
-    if (it + 1 < iters) SAMA_PHASE(it + 1, 1, 2)
-    if (it + 2 < iters) SAMA_PHASE(it + 2, 2, 0)
-  }
-#undef SAMA_PHASE
-#undef SAMA_PHASE_FULL
-#undef SAMA_COMPUTE
-#undef SAMA_STORE
-#undef SAMA_LOAD
+  const int iters = (!DUAL && a.B2 != nullptr) ? 2 * nk : nk;   // non-DUAL tiles contract with hi, then with lo
 
-  // ---- epilogue: accumulators -> LDS (per wave, 32 x 64 fp32 at a time) -> row-contiguous global accesses
+  // per-lane global offsets of this wave's loads
+  uint32_t offA[T::NLA], offB[T::NLB];
+#pragma unroll
+  for (int q = 0; q < T::NLA; ++q) offA[q] = piece_offset<A_KC, BM, BK>((q * WAVES + wave) * 1024 + lane * 16, i0, a.M, a.lda);
+#pragma unroll
+  for (int q = 0; q < T::NLB; ++q) offB[q] = piece_offset<B_KC, BN, BK>((q * WAVES + wave) * 1024 + lane * 16, j0, a.N, a.ldb);
+  const int64_t stepA = A_KC ? (int64_t)BK * 2 : (int64_t)BK * a.lda * 2;   // bytes per slab
+  const int64_t stepB = B_KC ? (int64_t)BK * 2 : (int64_t)BK * a.ldb * 2;
+
+  // Direct global -> LDS loads: lane l of a wave-level load lands at (m0) + 16 l.  Written as inline assembly so
+  // that the only waits on them are the explicit vmcnt waits below.
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void*)smem_raw;
+  auto issue = [&](int sl) {
+    const int stage = sl % NSTAGE;
+    const int kq = sl >= nk ? sl - nk : sl;
+    const char* ap = reinterpret_cast<const char*>(a.A) + kq * stepA;
+    const char* bp = reinterpret_cast<const char*>(sl >= nk ? a.B2 : a.B) + kq * stepB;
+    const uint32_t sa = lds0 + stage * T::STAGE_BYTES + wave * 1024;
+    const uint32_t sb = sa + T::A_BYTES;
+    const char* b2p = reinterpret_cast<const char*>(a.B2) + kq * stepB;
+#pragma unroll
+    for (int q = 0; q < T::NLA; ++q)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sa + q * WAVES * 1024), "v"(offA[q]), "s"(ap) : "memory", "m0");
+#pragma unroll
+    for (int q = 0; q < T::NLB; ++q)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sb + q * WAVES * 1024), "v"(offB[q]), "s"(bp) : "memory", "m0");
+    if (DUAL) {
+#pragma unroll
+      for (int q = 0; q < T::NLB; ++q)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sb + T::B_BYTES + q * WAVES * 1024), "v"(offB[q]), "s"(b2p) : "memory", "m0");
+    }
+  };
+
+  // lane-dependent parts of the operand fetch addresses
+  int fa[A_KC ? BK / 16 : XT], fb[B_KC ? BK / 16 : YT];
+  if (A_KC) {
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) fa[ks] = fetch_lane_offset<true, BM, BK>(lane, ks) + wr * BK * 2;
+  } else {
+#pragma unroll
+    for (int x = 0; x < XT; ++x) fa[x] = fetch_lane_offset<false, BM, BK>(lane, (wr >> 5) + x);
+  }
+  if (B_KC) {
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) fb[ks] = fetch_lane_offset<true, BN, BK>(lane, ks) + wc * BK * 2;
+  } else {
+#pragma unroll
+    for (int y = 0; y < YT; ++y) fb[y] = fetch_lane_offset<false, BN, BK>(lane, (wc >> 5) + y);
+  }
+
+  auto fetchA = [&](const unsigned char* sa, int x, int ks) -> bf16x8 {
+    if (A_KC) return *reinterpret_cast<const bf16x8*>(sa + fa[ks] + x * 32 * BK * 2);
+    const unsigned char* p = sa + fa[x] + ks * 16 * BM * 2;
+    union { bf16x8 v; s16x4 h[2]; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * BM * 2));
+    return u.v;
+  };
+  auto fetchB = [&](const unsigned char* sb, int y, int ks) -> bf16x8 {
+    if (B_KC) return *reinterpret_cast<const bf16x8*>(sb + fb[ks] + y * 32 * BK * 2);
+    const unsigned char* p = sb + fb[y] + ks * 16 * BN * 2;
+    union { bf16x8 v; s16x4 h[2]; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * BN * 2));
+    return u.v;
+  };
+
+  // ---- pipeline: NSTAGE - 1 slabs in flight; the k-steps of all slabs form one stream in which the operands of
+  // step t + 1 are fetched from LDS before the MFMAs of step t are issued (also across the slab boundary, so the
+  // LDS latency after a barrier hides behind the last MFMAs of the previous slab)
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < iters) issue(s);
+
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "operand double buffer parity");
+  bf16x8 av[2][XT], bv[2][YT], bw[2][DUAL ? YT : 1];
+  // make slab `sl` visible: own loads landed, then everyone's; afterwards the stage of slab sl - 1 is free
+  auto arrive = [&](int sl) {
+    const int younger = iters - 1 - sl;
+    if (younger >= NSTAGE - 2) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(T::NL * (NSTAGE - 2)) : "memory");
+    } else if (NSTAGE >= 4 && younger == NSTAGE - 3) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(T::NL * (NSTAGE >= 4 ? NSTAGE - 3 : 0)) : "memory");
+    } else if (NSTAGE >= 5 && younger == NSTAGE - 4) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(T::NL * (NSTAGE >= 5 ? NSTAGE - 4 : 0)) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __builtin_amdgcn_s_barrier();
+    if (sl + NSTAGE - 1 < iters) issue(sl + NSTAGE - 1);
+  };
+  auto fetch = [&](int sl, int ks, int buf) {
+    const unsigned char* sa = smem_raw + (sl % NSTAGE) * T::STAGE_BYTES;
+    const unsigned char* sb = sa + T::A_BYTES;
+#pragma unroll
+    for (int x = 0; x < XT; ++x) av[buf][x] = fetchA(sa, x, ks);
+#pragma unroll
+    for (int y = 0; y < YT; ++y) bv[buf][y] = fetchB(sb, y, ks);
+    if (DUAL) {
+#pragma unroll
+      for (int y = 0; y < YT; ++y) bw[buf][y] = fetchB(sb + T::B_BYTES, y, ks);
+    }
+  };
+  arrive(0);
+  fetch(0, 0, 0);
+  auto mfma_step = [&](int cur) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int x = 0; x < XT; ++x)
+#pragma unroll
+      for (int y = 0; y < YT; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[cur][x], bv[cur][y], acc[x][y], 0, 0, 0);
+    if (DUAL) {
+#pragma unroll
+      for (int x = 0; x < XT; ++x)
+#pragma unroll
+        for (int y = 0; y < YT; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[cur][x], bw[cur][y], acc[x][y], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  for (int i = 0; i + 1 < iters; ++i) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int cur = ks & 1;
+      if (ks + 1 < KS) {
+        fetch(i, ks + 1, cur ^ 1);
+      } else {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's reads of slab i are complete
+        arrive(i + 1);
+        fetch(i + 1, 0, cur ^ 1);
+      }
+      mfma_step(cur);
+    }
+  }
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {   // last slab
+    if (ks + 1 < KS) fetch(iters - 1, ks + 1, (ks & 1) ^ 1);
+    mfma_step(ks & 1);
+  }
+  __syncthreads();
+
+  // ---- epilogue: accumulators -> LDS (per wave, 32 x WN fp32 at a time) -> row-contiguous global accesses
+  constexpr int EPI_LD = T::EPI_LD, LPR = T::WN / 4, RPP = 64 / LPR;   // lanes per row, rows per pass
   float* epi = reinterpret_cast<float*>(smem_raw) + wave * 32 * EPI_LD;
-  const int cg = lane & 15, rq = lane >> 4;          // this lane: columns 4*cg .. 4*cg+3, rows rq, rq+4, ...
+  const int cg = lane % LPR, rq = lane / LPR;
   const int gj = j0 + wc + 4 * cg;
   const bool col_ok = gj < a.N;
   float4 bias = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -259,15 +318,15 @@ __global__ __launch_bounds__(WROWS * 128) void k_gemm_bf16(GemmBf16Args a, int g
   for (int x = 0; x < XT; ++x) {
     if (x > 0) __syncthreads();
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < YT; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         epi[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * EPI_LD + y * 32 + (lane & 31)] = acc[x][y][r];
     __syncthreads();
     if (!col_ok) continue;
 #pragma unroll 4
-    for (int itr = 0; itr < 8; ++itr) {
-      const int row = rq + 4 * itr, gi = i0 + wr + x * 32 + row;
+    for (int itr = 0; itr < 32 / RPP; ++itr) {
+      const int row = rq + RPP * itr, gi = i0 + wr + x * 32 + row;
       if (gi >= a.M) break;
       const float4 v = *reinterpret_cast<const float4*>(epi + row * EPI_LD + 4 * cg);
       const int64_t o = (int64_t)gi * a.ldc + gj;
@@ -286,7 +345,6 @@ __global__ __launch_bounds__(WROWS * 128) void k_gemm_bf16(GemmBf16Args a, int g
         pk.x = (uint32_t)f32_to_bf16(c[0]) | ((uint32_t)f32_to_bf16(c[1]) << 16);
         pk.y = (uint32_t)f32_to_bf16(c[2]) | ((uint32_t)f32_to_bf16(c[3]) << 16);
         *reinterpret_cast<uint2*>(a.C16_pre + o) = pk;
-        // the backward pass sees the rounded pre-activation, so the activation is taken from it too
         c[0] = gelu_f(bf16_to_f32((bf16_t)pk.x)); c[1] = gelu_f(bf16_to_f32((bf16_t)(pk.x >> 16)));
         c[2] = gelu_f(bf16_to_f32((bf16_t)pk.y)); c[3] = gelu_f(bf16_to_f32((bf16_t)(pk.y >> 16)));
       } else if (a.act == GEMM_ACT_GELU_BWD) {
@@ -305,52 +363,118 @@ __global__ __launch_bounds__(WROWS * 128) void k_gemm_bf16(GemmBf16Args a, int g
   }
 }
 
-template <int WROWS, int XT, bool A_KC, bool B_KC>
-void launch_shape(hipStream_t st, const GemmBf16Args& a) {
-  typedef Shape<WROWS, XT> SH;
+template <typename T, bool A_KC, bool B_KC>
+void launch_tile(hipStream_t st, const GemmBf16Args* p, int count, int group) {
   static bool configured = false;      // per instantiation: raise the dynamic LDS limit once
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<WROWS, XT, A_KC, B_KC>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, SH::LDS_BYTES);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<T, A_KC, B_KC>), hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     configured = true;
   }
-  const int gx = (a.N + BN - 1) / BN, gy = (a.M + SH::BM - 1) / SH::BM, ntiles = gx * gy, per_xcd = (ntiles + 7) / 8;
-  k_gemm_bf16<WROWS, XT, A_KC, B_KC><<<8 * per_xcd, SH::THREADS, SH::LDS_BYTES, st>>>(a, gx, ntiles, per_xcd);
+  GemmBatch b{};
+  b.count = count; b.group = group;
+  int nt = 0;
+  for (int k = 0; k < count; ++k) {
+    b.p[k] = p[k];
+    b.first_tile[k] = nt;
+    nt += ((p[k].N + T::BN - 1) / T::BN) * ((p[k].M + T::BM - 1) / T::BM);
+  }
+  for (int k = count; k <= GEMM_MAX_BATCH; ++k) b.first_tile[k] = nt;
+  const int per_xcd = (nt + 7) / 8;
+  k_gemm_bf16<T, A_KC, B_KC><<<8 * per_xcd, T::THREADS, T::LDS_BYTES, st>>>(b, nt, per_xcd);
 }
-int g_force_shape = 0;   // 0 = heuristic; 1, 2, 3 = force <2,2>, <4,2>, <2,4> (tuning hook)
+
+// Tile configurations <BM, BN, BK, waves in M, waves in N, stages, DUAL>
+typedef Tile<256, 256, 64, 2, 4, 2, false> TL;    // 8 waves of 128 x 64, 2 stages of 64 KB
+typedef Tile<256, 128, 64, 4, 2, 3, false> TM;    // 8 waves of 64 x 64, 3 stages of 48 KB
+typedef Tile<128, 128, 64, 2, 2, 2, false> TS;    // 4 waves of 64 x 64, 2 stages of 32 KB: two blocks per CU
+typedef Tile<128, 64, 64, 2, 2, 3, false> TX;     // 4 waves of 64 x 32, 3 stages of 24 KB: two blocks per CU
+typedef Tile<128, 64, 64, 2, 2, 4, false> TX4;    // 4 stages: one block per CU, deeper prefetch
+typedef Tile<256, 256, 32, 2, 4, 3, true> DL;     // DUAL: 3 stages of 48 KB
+typedef Tile<256, 128, 64, 4, 2, 2, true> DM;     // 2 stages of 64 KB
+typedef Tile<128, 128, 64, 2, 2, 3, true> DS;     // 3 stages of 48 KB
+typedef Tile<128, 64, 64, 2, 2, 2, true> DX;      // 2 stages of 32 KB: two blocks per CU
+typedef Tile<128, 64, 64, 2, 2, 4, true> DX4;     // 4 stages of 32 KB
+
+int g_force_shape = 0, g_group = 8;
+
+// Which block tile: estimated cycles per 64-deep k-slab on the busiest CU.  A CU ingests ~25 B/clk from L2 (measured),
+// i.e. 5.12 clk per 128-byte operand row, and sustains ~70% of its 4096 flop/clk MFMA rate; rounds = how many tiles
+// the busiest of the 256 CUs works through.  Near-ties go to the larger tile.
+int pick_tile(const GemmBf16Args* p, int count, bool dual) {
+  static const int dims[4][2] = {{256, 256}, {256, 128}, {128, 128}, {128, 64}};
+  const double nb = dual ? 2.0 : 1.0;
+  int best = 0;
+  double best_cost = 0.0;
+  for (int c = 0; c < 4; ++c) {
+    const int bm = dims[c][0], bn = dims[c][1];
+    int64_t tiles = 0;
+    for (int k = 0; k < count; ++k) tiles += (int64_t)((p[k].M + bm - 1) / bm) * ((p[k].N + bn - 1) / bn);
+    const double ingest = 5.12 * (bm + nb * bn), mfma = bm * bn * nb / 22.0;
+    const double cost = (double)((tiles + 255) / 256) * (ingest > mfma ? ingest : mfma) * (1.0 + 0.05 * c);
+    if (c == 0 || cost < best_cost) { best = c; best_cost = cost; }
+    if (c == 3 && best == 3 && tiles <= 256) best = 4;   // one block per CU is enough: take the deeper pipeline
+  }
+  return (dual ? 11 : 1) + best;
+}
+
 template <bool A_KC, bool B_KC>
-void launch_one(hipStream_t st, const GemmBf16Args& a) {
-  // 256 x 128 tiles when they still give (nearly) every CU a block, else 128 x 128
-  const int64_t big_tiles = (int64_t)((a.M + 255) / 256) * ((a.N + BN - 1) / BN);
-  int shape = g_force_shape ? g_force_shape : (big_tiles >= 192 ? 2 : 1);
-  if (shape == 3) launch_shape<2, 4, A_KC, B_KC>(st, a);
-  else if (shape == 2) launch_shape<4, 2, A_KC, B_KC>(st, a);
-  else launch_shape<2, 2, A_KC, B_KC>(st, a);
+void launch_class(hipStream_t st, const GemmBf16Args* p, int count) {
+  const bool dual = p[0].B2 != nullptr;
+  int shape = g_force_shape;
+  if (shape >= 11 && !dual) shape = 0;   // DUAL tiles read B2
+  if (shape == 0) shape = pick_tile(p, count, dual);
+  switch (shape) {
+    case 1: launch_tile<TL, A_KC, B_KC>(st, p, count, g_group); break;
+    case 2: launch_tile<TM, A_KC, B_KC>(st, p, count, g_group); break;
+    case 4: launch_tile<TX, A_KC, B_KC>(st, p, count, g_group); break;
+    case 5: launch_tile<TX4, A_KC, B_KC>(st, p, count, g_group); break;
+    case 11: launch_tile<DL, A_KC, B_KC>(st, p, count, g_group); break;
+    case 12: launch_tile<DM, A_KC, B_KC>(st, p, count, g_group); break;
+    case 13: launch_tile<DS, A_KC, B_KC>(st, p, count, g_group); break;
+    case 14: launch_tile<DX, A_KC, B_KC>(st, p, count, g_group); break;
+    case 15: launch_tile<DX4, A_KC, B_KC>(st, p, count, g_group); break;
+    default: launch_tile<TS, A_KC, B_KC>(st, p, count, g_group); break;
+  }
 }
 }  // namespace
 
 const char* check_gemm_bf16(const GemmBf16Args& a) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return "empty GEMM";
-  if (a.K % BK != 0) return "K must be a multiple of 64";
+  if (a.K % 64 != 0) return "K must be a multiple of 64";
   if (a.M % 8 != 0 || a.N % 8 != 0) return "M and N must be multiples of 8";
   if (a.lda % 8 != 0 || a.ldb % 8 != 0 || a.ldc % 4 != 0) return "leading dimensions must be multiples of 8 (A, B) and 4 (C)";
   if (((uintptr_t)a.A | (uintptr_t)a.B | (uintptr_t)a.B2 | (uintptr_t)a.bias | (uintptr_t)a.bias_v | (uintptr_t)a.C32 |
        (uintptr_t)a.res32) & 15) return "operands, bias, fp32 residual and fp32 output must be 16-byte aligned";
   if (((uintptr_t)a.C16 | (uintptr_t)a.C16_pre | (uintptr_t)a.aux16 | (uintptr_t)a.res16) & 7) return "bf16 epilogue tensors must be 8-byte aligned";
   if (a.lda < (a.a_trans ? a.M : a.K) || a.ldb < (a.b_trans ? a.K : a.N) || a.ldc < a.N) return "leading dimension too small";
+  const int64_t abytes = (int64_t)(a.a_trans ? a.K : a.M) * a.lda * 2, bbytes = (int64_t)(a.b_trans ? a.N : a.K) * a.ldb * 2;
+  if (abytes >= ((int64_t)1 << 31) || bbytes >= ((int64_t)1 << 31)) return "operands must be smaller than 2 GiB";
   return nullptr;
 }
 
-void gemm_bf16_force_shape(int s) { g_force_shape = s; }
+void gemm_bf16_force_shape(int s) { g_force_shape = s % 100; g_group = s >= 100 ? s / 100 : 8; }
 
-void launch_gemm_bf16(hipStream_t st, const GemmBf16Args& a) {
-  const double flops = 2.0 * a.M * a.N * a.K * (a.B2 ? 2.0 : 1.0);   // hi + lo contracts over 2K
-  ProfScope ps(st, a.a_trans ? F_GEMM_TN : (a.b_trans ? F_GEMM_NT : F_GEMM_NN), flops);
-  // a_trans = 0: A is [M][K], contraction contiguous.  b_trans = 1: B is [N][K], contraction contiguous.
-  if (!a.a_trans && a.b_trans) launch_one<true, true>(st, a);
-  else if (!a.a_trans && !a.b_trans) launch_one<true, false>(st, a);
-  else if (a.a_trans && !a.b_trans) launch_one<false, false>(st, a);
-  else launch_one<false, true>(st, a);
+const char* check_gemm_bf16_batch(const GemmBf16Args* p, int count) {
+  if (count < 1 || count > GEMM_MAX_BATCH) return "batch of 1 to 4 problems";
+  for (int k = 0; k < count; ++k) {
+    if (const char* e = check_gemm_bf16(p[k])) return e;
+    if (p[k].a_trans != p[0].a_trans || p[k].b_trans != p[0].b_trans || (p[k].B2 != nullptr) != (p[0].B2 != nullptr))
+      return "the problems of a batch must share operand storage and the hi + lo form";
+  }
+  return nullptr;
 }
+
+void launch_gemm_bf16_batch(hipStream_t st, const GemmBf16Args* p, int count) {
+  double flops = 0.0;
+  for (int k = 0; k < count; ++k) flops += 2.0 * p[k].M * p[k].N * p[k].K * (p[k].B2 ? 2.0 : 1.0);   // hi + lo contracts over 2K
+  ProfScope ps(st, p[0].a_trans ? F_GEMM_TN : (p[0].b_trans ? F_GEMM_NT : F_GEMM_NN), flops);
+  // a_trans = 0: A is [M][K], contraction contiguous.  b_trans = 1: B is [N][K], contraction contiguous.
+  if (!p[0].a_trans && p[0].b_trans) launch_class<true, true>(st, p, count);
+  else if (!p[0].a_trans && !p[0].b_trans) launch_class<true, false>(st, p, count);
+  else if (p[0].a_trans && !p[0].b_trans) launch_class<false, false>(st, p, count);
+  else launch_class<false, true>(st, p, count);
+}
+
+void launch_gemm_bf16(hipStream_t st, const GemmBf16Args& a) { launch_gemm_bf16_batch(st, &a, 1); }
 
 }  // namespace sama

@@ -122,7 +122,12 @@ struct GemmBf16Args {
 };
 const char* check_gemm_bf16(const GemmBf16Args&);  // null if the shapes / alignments are supported
 void launch_gemm_bf16(hipStream_t, const GemmBf16Args&);
-void gemm_bf16_force_shape(int shape);  // tuning hook: 0 = heuristic, 1 = 128x128/4 waves, 2 = 256x128/8 waves, 3 = 256x128/4 waves
+// Up to GEMM_MAX_BATCH independent problems in one launch; they must agree in a_trans, b_trans and in whether B2 is
+// given (shapes, K and epilogues may differ).
+constexpr int GEMM_MAX_BATCH = 4;
+const char* check_gemm_bf16_batch(const GemmBf16Args* p, int count);
+void launch_gemm_bf16_batch(hipStream_t, const GemmBf16Args* p, int count);
+void gemm_bf16_force_shape(int shape);  // tuning hook: 0 = heuristic, else 100 * tile-order group + tile configuration id
 
 // ------------------------------------------------------------------ encoder ops (encoder_ops.hip)
 constexpr int LN_MAX_D = 1024;       // LayerNorm kernels keep a row in registers
@@ -131,6 +136,7 @@ constexpr int COLSUM_ROWS = 16;      // rows per block in the column-sum kernel
 struct LnFwdArgs {
   const float* x;          // [M x d] input, or null: embedding mode (x = tok_emb[id] + pos_emb[m % S])
   const int32_t* ids; int S; int64_t tok_off, pos_off; float* x_out;  // embedding mode; x_out [M x d] may be null
+  int ids_rows;            // embedding mode: row r reads ids[r % ids_rows] (0 = M; stacked passes share one id array)
   ParamView pv; int64_t g_off, b_off;                                 // gamma / beta inside theta
   bf16_t* y; float* y32; float* mean; float* rstd;                    // y32 (fp32 copy for the residual path), mean, rstd may be null
   int M, d;

@@ -53,6 +53,12 @@ class Model {
   virtual void plan(BumpAlloc& ws, int max_b) = 0;
   // logits[B x C] (fp32, row stride C) for batch `b`; keep = retain what backward needs
   virtual void forward(hipStream_t st, const PassWeights& w, const sama_batch& b, bool keep, float* logits) = 0;
+  // The theta + eps v and theta - eps v passes of Eq. 5 on the same batch, forward only: logits [2B x C], the + pass
+  // first.  Models that gain from it run the two passes stacked in the same launches.
+  virtual void forward_pair(hipStream_t st, const PassWeights& wp, const PassWeights& wm, const sama_batch& b, float* logits) {
+    forward(st, wp, b, false, logits);
+    forward(st, wm, b, false, logits + (size_t)b.n * n_classes());
+  }
   // grad[n] = d/dtheta sum_i sum_c dlogits[i][c] z_ic, at the unperturbed theta of the last keep=true forward
   virtual void backward(hipStream_t st, const PassWeights& w, const sama_batch& b, const float* dlogits, float* grad) = 0;
   virtual int n_classes() const = 0;

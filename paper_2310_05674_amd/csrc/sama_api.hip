@@ -110,7 +110,8 @@ static size_t carve(sama_ctx* c, void* base) {
   c->counters = ws.take<int64_t>(4);
   const int mb = c->cfg.max_batch > c->cfg.max_meta_batch ? c->cfg.max_batch : c->cfg.max_meta_batch;
   const int C = c->cfg.dims[c->cfg.n_dims - 1];
-  c->logits = ws.take<float>((size_t)mb * C); c->dlogits = ws.take<float>((size_t)mb * C);
+  c->logits = ws.take<float>((size_t)2 * mb * C);   // room for the stacked + and - passes
+  c->dlogits = ws.take<float>((size_t)mb * C);
   c->losses = ws.take<float>(mb);
   if (c->model) c->model->plan(ws, mb);
   return ws.used();
@@ -292,11 +293,10 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
   launch_adapt_norm(st, c->g, c->m, c->v, c->gmeta, c->vdir, c->partial, c->n, ad, f.alpha, c->scalars, c->counters + 2);
   if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
   // passes 2 and 3: dL_base/dlambda at theta +- eps v; forward only, then the weight net's backward
+  c->model->forward_pair(st, pass_weights(c, 1.f), pass_weights(c, -1.f), *train, c->logits);
   for (int pass = 0; pass < 2; ++pass) {
-    const PassWeights wp = pass_weights(c, pass == 0 ? 1.f : -1.f);
-    c->model->forward(st, wp, *train, false, c->logits);
     SampleStageArgs sg{};
-    sg.logits = c->logits; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM;
+    sg.logits = c->logits + (size_t)pass * train->n * C; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM;
     sg.y = train->y; sg.mask = train->sample_mask; sg.lambda = c->lambda; sg.losses = c->losses;
     sg.glam = pass == 0 ? c->glam_p : c->glam_m;
     launch_sample_stage(st, sg);

@@ -116,7 +116,7 @@ CASES = [  # M, N, K, a_trans, b_trans, split
 
 @pytest.mark.parametrize("M,N,K,a_trans,b_trans,split", CASES)
 def test_gemm_bf16(M, N, K, a_trans, b_trans, split):
-    """Both block shapes (forced in turn) and the heuristic against numpy float64 on bf16-representable operands;
+    """Every block tile (forced in turn; the hi + lo tiles fall back to the heuristic on single-term problems) and the heuristic against numpy float64 on bf16-representable operands;
     several tiles and ragged edges in M and N."""
     import ctypes
     from paper_2310_05674_amd import binding as B
@@ -133,7 +133,7 @@ def test_gemm_bf16(M, N, K, a_trans, b_trans, split):
     tbias = _dev(bias)
     L = B.load_library()
     outs = []
-    for shape in (1, 2, 0):
+    for shape in (1, 2, 3, 4, 5, 11, 12, 13, 14, 15, 0):
         L.sama_dev_gemm_shape(ctypes.c_int32(shape))
         o32 = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
         o16 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
@@ -147,7 +147,7 @@ def test_gemm_bf16(M, N, K, a_trans, b_trans, split):
     L.sama_dev_gemm_shape(ctypes.c_int32(0))
     o32b = torch.empty((M, N), dtype=torch.float32, device=DEV)
     B.op_gemm_bf16(tA, tB, a_trans=a_trans, b_trans=b_trans, B2=tB2, bias=tbias, out32=o32b)
-    assert np.array_equal(o32b.cpu().numpy(), outs[2])                    # bit-stable from run to run
+    assert np.array_equal(o32b.cpu().numpy(), outs[-1])                    # bit-stable from run to run
 
 
 def test_gemm_rejects_unsupported_shapes():
