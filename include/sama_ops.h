@@ -33,7 +33,7 @@ sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void*
 
 /* Adaptation fused with the step size (Eq. 4-5, App. C): vdir = (du_adam/dg) . gmeta from the post-update moments at
  * step t, then scalars[0] = alpha / ||vdir||_2, scalars[1] = ||vdir||_2, status[0] = 1 if the norm is zero or not
- * finite (else 0).  partial: DEVICE scratch of 4096 doubles. */
+ * finite (else 0).  partial: DEVICE scratch of 65536 doubles. */
 sama_status sama_op_adapt_norm(const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
                                double* partial, int64_t n, int64_t t, float lr, float beta1, float beta2, float eps,
                                float alpha, float* scalars, int64_t* status, void* hip_stream);

@@ -22,7 +22,7 @@ struct ProfScope {
 void prof_enable(bool on);
 bool prof_read(int family, const char** name, int64_t* launches, double* total_ms, double* units);
 
-constexpr int EW_MAX_BLOCKS = 4096;  // grid cap of the elementwise kernels (also the size of the norm partials)
+constexpr int EW_MAX_BLOCKS = 65536;  // grid cap of the elementwise kernels (also the size of the norm partials)
 constexpr int MAX_BATCH = 2048;
 constexpr int MAX_WNET_HIDDEN = 256;
 

@@ -51,7 +51,7 @@ def test_adapt_norm_kernel(n):
     v[::11] = 0.0; m[::11] = 0.0; g[::11] = 0.0                        # zero-history elements
     g32, m32, v32, gm32 = (x.astype(np.float32) for x in (g, m, v, gm))
     out = torch.empty(n, dtype=torch.float32, device=DEV)
-    partial = torch.zeros(4096, dtype=torch.float64, device=DEV)
+    partial = torch.zeros(65536, dtype=torch.float64, device=DEV)
     scal = torch.zeros(4, dtype=torch.float32, device=DEV); status = torch.full((1,), 7, dtype=torch.int64, device=DEV)
     B.op_adapt_norm(_dev(g32), _dev(m32), _dev(v32), _dev(gm32), out, partial, 5, 1e-3, 0.9, 0.999, 1e-8, 0.5, scal, status)
     D = optim.adam_adaptation(g32.astype(np.float64), m32.astype(np.float64), v32.astype(np.float64), 5, 1e-3, 0.9, 0.999, 1e-8)
@@ -73,7 +73,7 @@ def test_adapt_norm_degenerate():
     from paper_2310_05674_amd import binding as B
     n = 1000
     z = torch.zeros(n, dtype=torch.float32, device=DEV)
-    out = torch.empty(n, dtype=torch.float32, device=DEV); partial = torch.zeros(4096, dtype=torch.float64, device=DEV)
+    out = torch.empty(n, dtype=torch.float32, device=DEV); partial = torch.zeros(65536, dtype=torch.float64, device=DEV)
     scal = torch.ones(4, dtype=torch.float32, device=DEV); status = torch.zeros(1, dtype=torch.int64, device=DEV)
     B.op_adapt_norm(z, z, z, torch.ones_like(z), out, partial, 3, 1e-3, 0.9, 0.999, 1e-8, 1.0, scal, status)
     assert float(scal[0]) == 0.0 and int(status.item()) == 1
