@@ -25,7 +25,7 @@ PEAK_FP32_MATRIX_TFLOPS = 157.3
 # HBM-side bytes per launch of the dominant kernel family (forward GEMM) on workload 5, from the two rocprofv3 --pmc
 # runs summarised in profiles/bench_workload5_hbm_traffic.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, calibrated on
 # the library's own copy kernel).  Not measured for other workloads / kernels: reported as null there.
-MEASURED_TRAFFIC_BYTES = {(5, "gemm_bf16_nt"): 117.0e6}
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def fwd_flops(wl, batch):
@@ -132,6 +132,8 @@ def main():
                 ent.update(bound="hbm", achieved=units / (ms * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s")
             if "achieved" in ent:
                 ent["frac"] = ent["achieved"] / ent["peak"]
+            if name.endswith("_hilo"):   # the same launches priced at 2 M N K (one weight term)
+                ent["frac_single_term"] = 0.5 * ent["frac"]
             kernels[name] = ent
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
         d = kernels[dom]

@@ -12,13 +12,16 @@ constexpr int WAVE = 64;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
-// round-to-nearest-even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// two floats -> packed bf16 pair (a in the low half), round-to-nearest-even in hardware (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  const f32x2_hw v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
 }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)pack_bf16x2(f, 0.f); }
 
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll

@@ -33,8 +33,8 @@ __device__ __forceinline__ void st_nt(float* p, int64_t j, f4 v) { __builtin_non
 // four bf16 (round to nearest even) at element offset 4 j
 __device__ __forceinline__ void st_bf16x4_nt(bf16_t* p, int64_t j, float a, float b, float c, float d) {
   u2 pk;
-  pk.x = (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-  pk.y = (uint32_t)f32_to_bf16(c) | ((uint32_t)f32_to_bf16(d) << 16);
+  pk.x = pack_bf16x2(a, b);
+  pk.y = pack_bf16x2(c, d);
   __builtin_nontemporal_store(pk, reinterpret_cast<u2*>(p) + j);
 }
 // the bf16 copy covers only the first n16 elements: whole vectors inside it, element by element across its end

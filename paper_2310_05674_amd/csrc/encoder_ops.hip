@@ -70,8 +70,8 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
       const float4 o = make_float4(fmaf((xr[j].x - mu) * rstd, g.x, b.x), fmaf((xr[j].y - mu) * rstd, g.y, b.y),
                                    fmaf((xr[j].z - mu) * rstd, g.z, b.z), fmaf((xr[j].w - mu) * rstd, g.w, b.w));
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(o.x) | ((uint32_t)f32_to_bf16(o.y) << 16);
-      pk.y = (uint32_t)f32_to_bf16(o.z) | ((uint32_t)f32_to_bf16(o.w) << 16);
+      pk.x = pack_bf16x2(o.x, o.y);
+      pk.y = pack_bf16x2(o.z, o.w);
       *reinterpret_cast<uint2*>(a.y + (int64_t)row * a.d + 4 * q) = pk;
       if (a.y32 != nullptr) reinterpret_cast<float4*>(a.y32 + (int64_t)row * a.d)[q] = o;
     }
@@ -127,8 +127,8 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
         if (a.dx32 != nullptr) reinterpret_cast<float4*>(a.dx32 + (int64_t)row * a.d)[q] = dx;
         if (a.dx16 != nullptr) {
           uint2 pk;
-          pk.x = (uint32_t)f32_to_bf16(dx.x) | ((uint32_t)f32_to_bf16(dx.y) << 16);
-          pk.y = (uint32_t)f32_to_bf16(dx.z) | ((uint32_t)f32_to_bf16(dx.w) << 16);
+          pk.x = pack_bf16x2(dx.x, dx.y);
+          pk.y = pack_bf16x2(dx.z, dx.w);
           *reinterpret_cast<uint2*>(a.dx16 + (int64_t)row * a.d + 4 * q) = pk;
         }
       }
@@ -271,8 +271,8 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(o[et][4 * c]) | ((uint32_t)f32_to_bf16(o[et][4 * c + 1]) << 16);
-      pk.y = (uint32_t)f32_to_bf16(o[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(o[et][4 * c + 3]) << 16);
+      pk.x = pack_bf16x2(o[et][4 * c], o[et][4 * c + 1]);
+      pk.y = pack_bf16x2(o[et][4 * c + 2], o[et][4 * c + 3]);
       *reinterpret_cast<uint2*>(orow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
     }
 }
@@ -353,8 +353,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(dq[et][4 * c]) | ((uint32_t)f32_to_bf16(dq[et][4 * c + 1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(dq[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(dq[et][4 * c + 3]) << 16);
+        pk.x = pack_bf16x2(dq[et][4 * c], dq[et][4 * c + 1]);
+        pk.y = pack_bf16x2(dq[et][4 * c + 2], dq[et][4 * c + 3]);
         *reinterpret_cast<uint2*>(dqrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
       }
   }
@@ -403,11 +403,11 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(dk[et][4 * c]) | ((uint32_t)f32_to_bf16(dk[et][4 * c + 1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(dk[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(dk[et][4 * c + 3]) << 16);
+        pk.x = pack_bf16x2(dk[et][4 * c], dk[et][4 * c + 1]);
+        pk.y = pack_bf16x2(dk[et][4 * c + 2], dk[et][4 * c + 3]);
         *reinterpret_cast<uint2*>(krow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
-        pk.x = (uint32_t)f32_to_bf16(dv[et][4 * c]) | ((uint32_t)f32_to_bf16(dv[et][4 * c + 1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(dv[et][4 * c + 2]) | ((uint32_t)f32_to_bf16(dv[et][4 * c + 3]) << 16);
+        pk.x = pack_bf16x2(dv[et][4 * c], dv[et][4 * c + 1]);
+        pk.y = pack_bf16x2(dv[et][4 * c + 2], dv[et][4 * c + 3]);
         *reinterpret_cast<uint2*>(vrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
       }
   }

@@ -170,24 +170,29 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
   // Direct global -> LDS loads: lane l of a wave-level load lands at (m0) + 16 l.  Written as inline assembly so
   // that the only waits on them are the explicit vmcnt waits below.
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void*)smem_raw;
+  // All NL wave-level loads of a slab are issued together right after the barrier that frees their stage (spreading
+  // them over the k-steps of the slab computed meanwhile measured 3-8% slower: it shortens the prefetch distance).
+  constexpr int KS = BK / 16;
   auto issue = [&](int sl) {
+    if (sl >= iters) return;
     const int stage = sl % NSTAGE;
     const int kq = sl >= nk ? sl - nk : sl;
     const char* ap = reinterpret_cast<const char*>(a.A) + kq * stepA;
     const char* bp = reinterpret_cast<const char*>(sl >= nk ? a.B2 : a.B) + kq * stepB;
+    const char* b2p = reinterpret_cast<const char*>(a.B2) + kq * stepB;
     const uint32_t sa = lds0 + stage * T::STAGE_BYTES + wave * 1024;
     const uint32_t sb = sa + T::A_BYTES;
-    const char* b2p = reinterpret_cast<const char*>(a.B2) + kq * stepB;
 #pragma unroll
-    for (int q = 0; q < T::NLA; ++q)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sa + q * WAVES * 1024), "v"(offA[q]), "s"(ap) : "memory", "m0");
-#pragma unroll
-    for (int q = 0; q < T::NLB; ++q)
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sb + q * WAVES * 1024), "v"(offB[q]), "s"(bp) : "memory", "m0");
-    if (DUAL) {
-#pragma unroll
-      for (int q = 0; q < T::NLB; ++q)
+    for (int t = 0; t < T::NL; ++t) {
+      if (t < T::NLA) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sa + t * WAVES * 1024), "v"(offA[t]), "s"(ap) : "memory", "m0");
+      } else if (t < T::NLA + T::NLB) {
+        const int q = t - T::NLA;
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sb + q * WAVES * 1024), "v"(offB[q]), "s"(bp) : "memory", "m0");
+      } else {
+        const int q = t - T::NLA - T::NLB;
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(sb + T::B_BYTES + q * WAVES * 1024), "v"(offB[q]), "s"(b2p) : "memory", "m0");
+      }
     }
   };
 
@@ -229,10 +234,8 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
   // step t + 1 are fetched from LDS before the MFMAs of step t are issued (also across the slab boundary, so the
   // LDS latency after a barrier hides behind the last MFMAs of the previous slab)
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
-    if (s < iters) issue(s);
+  for (int s = 0; s < NSTAGE - 1; ++s) issue(s);
 
-  constexpr int KS = BK / 16;
   static_assert(KS % 2 == 0, "operand double buffer parity");
   bf16x8 av[2][XT], bv[2][YT], bw[2][DUAL ? YT : 1];
   // make slab `sl` visible: own loads landed, then everyone's; afterwards the stage of slab sl - 1 is free
@@ -248,7 +251,7 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __builtin_amdgcn_s_barrier();
-    if (sl + NSTAGE - 1 < iters) issue(sl + NSTAGE - 1);
+    issue(sl + NSTAGE - 1);
   };
   auto fetch = [&](int sl, int ks, int buf) {
     const unsigned char* sa = smem_raw + (sl % NSTAGE) * T::STAGE_BYTES;
@@ -342,8 +345,8 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       }
       if (a.act == GEMM_ACT_GELU_FWD) {
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(c[0]) | ((uint32_t)f32_to_bf16(c[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(c[2]) | ((uint32_t)f32_to_bf16(c[3]) << 16);
+        pk.x = pack_bf16x2(c[0], c[1]);
+        pk.y = pack_bf16x2(c[2], c[3]);
         *reinterpret_cast<uint2*>(a.C16_pre + o) = pk;
         c[0] = gelu_f(bf16_to_f32((bf16_t)pk.x)); c[1] = gelu_f(bf16_to_f32((bf16_t)(pk.x >> 16)));
         c[2] = gelu_f(bf16_to_f32((bf16_t)pk.y)); c[3] = gelu_f(bf16_to_f32((bf16_t)(pk.y >> 16)));
@@ -355,8 +358,8 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       if (a.C32 != nullptr) *reinterpret_cast<float4*>(a.C32 + o) = make_float4(c[0], c[1], c[2], c[3]);
       if (a.C16 != nullptr) {
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(c[0]) | ((uint32_t)f32_to_bf16(c[1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(c[2]) | ((uint32_t)f32_to_bf16(c[3]) << 16);
+        pk.x = pack_bf16x2(c[0], c[1]);
+        pk.y = pack_bf16x2(c[2], c[3]);
         *reinterpret_cast<uint2*>(a.C16 + o) = pk;
       }
     }
@@ -467,7 +470,8 @@ const char* check_gemm_bf16_batch(const GemmBf16Args* p, int count) {
 void launch_gemm_bf16_batch(hipStream_t st, const GemmBf16Args* p, int count) {
   double flops = 0.0;
   for (int k = 0; k < count; ++k) flops += 2.0 * p[k].M * p[k].N * p[k].K * (p[k].B2 ? 2.0 : 1.0);   // hi + lo contracts over 2K
-  ProfScope ps(st, p[0].a_trans ? F_GEMM_TN : (p[0].b_trans ? F_GEMM_NT : F_GEMM_NN), flops);
+  const bool hilo = p[0].B2 != nullptr;
+  ProfScope ps(st, p[0].a_trans ? F_GEMM_TN : (p[0].b_trans ? (hilo ? F_GEMM_NT_HILO : F_GEMM_NT) : (hilo ? F_GEMM_NN_HILO : F_GEMM_NN)), flops);
   // a_trans = 0: A is [M][K], contraction contiguous.  b_trans = 1: B is [N][K], contraction contiguous.
   if (!p[0].a_trans && p[0].b_trans) launch_class<true, true>(st, p, count);
   else if (!p[0].a_trans && !p[0].b_trans) launch_class<true, false>(st, p, count);

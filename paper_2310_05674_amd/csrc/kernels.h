@@ -8,7 +8,7 @@ namespace sama {
 
 // ------------------------------------------------------------------ optional per-launch timing (profile.hip)
 enum Family {
-  F_GEMM_NT = 0, F_GEMM_NN, F_GEMM_TN, F_GEMM_F32, F_ATTN_FWD, F_ATTN_BWD, F_LN_FWD, F_LN_BWD, F_ADAM, F_ADAPT_NORM,
+  F_GEMM_NT = 0, F_GEMM_NN, F_GEMM_TN, F_GEMM_NT_HILO, F_GEMM_NN_HILO, F_GEMM_F32, F_ATTN_FWD, F_ATTN_BWD, F_LN_FWD, F_LN_BWD, F_ADAM, F_ADAPT_NORM,
   F_PERTURB, F_RESIDUAL, F_NUDGE, F_SAMPLE_STAGE, F_OTHER, F_COUNT
 };
 // While profiling is enabled every launcher brackets its kernel with two HIP events on the launch stream.

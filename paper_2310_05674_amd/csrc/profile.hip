@@ -11,7 +11,7 @@ std::mutex g_mu;
 bool g_on = false;
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
-const char* kNames[F_COUNT] = {"gemm_bf16_nt", "gemm_bf16_nn", "gemm_bf16_tn", "gemm_f32", "attention_fwd", "attention_bwd",
+const char* kNames[F_COUNT] = {"gemm_bf16_nt", "gemm_bf16_nn", "gemm_bf16_tn", "gemm_bf16_nt_hilo", "gemm_bf16_nn_hilo", "gemm_f32", "attention_fwd", "attention_bwd",
                                "layernorm_fwd", "layernorm_bwd", "adam", "adapt_norm", "perturb_lo", "residual_lo",
                                "nudge", "sample_stage", "other"};
 hipEvent_t take_event() {
