@@ -26,6 +26,15 @@ sama_status sama_op_gemm_bf16(const void* A, int64_t lda, int32_t a_trans, const
                               int32_t b_trans, int32_t M, int32_t N, int32_t K, const float* bias, float* C32, void* C16,
                               int64_t ldc, void* hip_stream);
 
+/* `count` (1..4) independent contractions of the form above in ONE launch: the + and the - pass of Eq. 5 stacked, or the
+ * four weight gradients of an encoder layer.  Every array is a HOST array of `count` entries; A[k], B[k], B2[k], C32[k]
+ * are DEVICE pointers (B2 either given for every problem or NULL itself); operands are dense (lda = K or M, ldb = K
+ * or N, ldc = N as the storage flags imply).  The problems share a_trans / b_trans; shapes may differ.  Same
+ * requirements and error behaviour as sama_op_gemm_bf16. */
+sama_status sama_op_gemm_bf16_batch(int32_t count, const void* const* A, const void* const* B, const void* const* B2,
+                                    float* const* C32, const int32_t* M, const int32_t* N, const int32_t* K,
+                                    int32_t a_trans, int32_t b_trans, void* hip_stream);
+
 /* Base solver update, Adam form (Sec. 2; Kingma & Ba Alg. 1 with bias correction at step t >= 1), over n fp32
  * elements in place; theta16 (bf16 [n16], n16 <= n) receives the rounded leading part of theta, or NULL. */
 sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16,

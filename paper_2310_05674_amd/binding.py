@@ -89,6 +89,8 @@ def load_library():
     vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_float
     L.sama_op_gemm_bf16.restype = C.c_int
     L.sama_op_gemm_bf16.argtypes = [vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, i64, vp]
+    L.sama_op_gemm_bf16_batch.restype = C.c_int
+    L.sama_op_gemm_bf16_batch.argtypes = [i32, vp, vp, vp, vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), i32, i32, vp]
     L.sama_op_adam.restype = C.c_int
     L.sama_op_adam.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, f32, f32, f32, f32, vp]
     L.sama_op_adapt_norm.restype = C.c_int
@@ -249,6 +251,24 @@ def op_gemm_bf16(A, B, *, a_trans=False, b_trans=True, B2=None, bias=None, out32
                              _p(out32), _p(out16), out.stride(0), _stream())
     if rc != 0:
         raise SamaError(rc, "sama_op_gemm_bf16 rejected the arguments")
+
+
+def op_gemm_bf16_batch(As, Bs, outs, *, a_trans=False, b_trans=True, B2s=None):
+    """Several independent C_k = A_k . (B_k + B2_k) in one launch through sama_op_gemm_bf16_batch (dense 2-D bf16 operands,
+    fp32 outputs)."""
+    L = load_library()
+    n = len(As)
+    Ms, Ns, Ks = [], [], []
+    for A, B in zip(As, Bs):
+        K, M = (A.shape[0], A.shape[1]) if a_trans else (A.shape[1], A.shape[0])
+        Ms.append(M); Ks.append(K); Ns.append(B.shape[0] if b_trans else B.shape[1])
+    vp = C.c_void_p * n
+    ia = C.c_int32 * n
+    rc = L.sama_op_gemm_bf16_batch(n, vp(*[A.data_ptr() for A in As]), vp(*[B.data_ptr() for B in Bs]),
+                                   vp(*[b.data_ptr() for b in B2s]) if B2s is not None else None,
+                                   vp(*[o.data_ptr() for o in outs]), ia(*Ms), ia(*Ns), ia(*Ks), int(a_trans), int(b_trans), _stream())
+    if rc != 0:
+        raise SamaError(rc, "sama_op_gemm_bf16_batch rejected the arguments")
 
 
 def op_adam(g, m, v, theta, theta16, n16, t, lr, beta1, beta2, eps, wd=0.0):

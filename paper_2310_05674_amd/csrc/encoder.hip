@@ -44,8 +44,8 @@ class EncoderModel : public Model {
     dpre_ = ws.take<bf16_t>(M * ffn_); do_ = ws.take<bf16_t>(M * d_); dqkv_ = ws.take<bf16_t>(M * 3 * d_);
     const size_t nblk = (M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
     const size_t wide = (size_t)(3 * d_ > ffn_ ? 3 * d_ : ffn_);
-    lnpart_ = ws.take<float>(nblk * 3 * d_);
-    cspart_ = ws.take<float>(nrb * wide);
+    lnpart_[0] = ws.take<float>(nblk * 3 * d_); lnpart_[1] = ws.take<float>(nblk * 3 * d_);
+    cspart_[0] = ws.take<float>(nrb * wide); cspart_[1] = ws.take<float>(nrb * wide);
   }
 
   // One linear layer of `nw` stacked passes (pass k owns rows [k M, (k + 1) M) of every activation): the same
@@ -145,41 +145,48 @@ class EncoderModel : public Model {
     launch_head_bwd(st, res_[0], S_, d_, B, C_, w.theta, wc_, bc_, dlogits, grad, dx);
     for (int l = L_ - 1; l >= 0; --l) {
       const LayerOff& o = off_[l];
-      GemmBf16Args wg[4];   // the layer's four weight gradients leave in one launch at the end of the layer
+      // The layer's four weight gradients, its two bias column sums and its four small reductions wait for the
+      // end of the layer and leave in three launches.
+      GemmBf16Args wg[4];
       // LN2
-      LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds16_[0], lnpart_, M, d_};
+      LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds16_[0], lnpart_[0], M, d_};
       launch_ln_bwd(st, n2);
-      launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + o.ln2g, grad + o.ln2b, grad + o.b2);
       // FFN
       wg[0] = wgrad(ds16_[0], d_, fact_[l], ffn_, M, grad + o.W2);
       GemmBf16Args g = dgrad(w, ds16_[0], d_, o.W2, ffn_, M);
       g.act = GEMM_ACT_GELU_BWD; g.aux16 = fpre_[l]; g.C16 = dpre_;
       launch_gemm_bf16(st, g);
-      launch_colsum_bf16(st, dpre_, M, ffn_, cspart_, grad + o.b1);
       wg[1] = wgrad(dpre_, ffn_, x1_[l], d_, M, grad + o.W1);
       g = dgrad(w, dpre_, ffn_, o.W1, d_, M);
       g.res32 = ds32_; g.C32 = dx_next;                       // + the residual branch
       launch_gemm_bf16(st, g);
       // LN1
-      LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds16_[1], lnpart_, M, d_};
+      LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds16_[1], lnpart_[1], M, d_};
       launch_ln_bwd(st, n1);
-      launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + o.ln1g, grad + o.ln1b, grad + o.bo);
       // attention
       wg[2] = wgrad(ds16_[1], d_, ao_[l], d_, M, grad + o.Wo);
       g = dgrad(w, ds16_[1], d_, o.Wo, d_, M);
       g.C16 = do_;
       launch_gemm_bf16(st, g);
       launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv_, B, heads_, d_);
-      launch_colsum_bf16(st, dqkv_, M, 3 * d_, cspart_, grad + o.bqkv);
       wg[3] = wgrad(dqkv_, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
       g = dgrad(w, dqkv_, 3 * d_, o.Wqkv, d_, M);
       g.res32 = ds32_; g.C32 = dx;                            // gradient w.r.t. the layer input
       launch_gemm_bf16(st, g);
       launch_gemm_bf16_batch(st, wg, 4);
+      const ColsumJob cj[2] = {{dpre_, M, ffn_, cspart_[0]}, {dqkv_, M, 3 * d_, cspart_[1]}};
+      launch_colsum_partial_multi(st, cj, 2);
+      const int nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
+      const ReduceRowsJob rj[4] = {
+          {lnpart_[0], nblk, 3 * d_, d_, d_, {grad + o.ln2g, grad + o.ln2b, grad + o.b2}},
+          {lnpart_[1], nblk, 3 * d_, d_, d_, {grad + o.ln1g, grad + o.ln1b, grad + o.bo}},
+          {cspart_[0], nrb, ffn_, 0, ffn_, {grad + o.b1, nullptr, nullptr}},
+          {cspart_[1], nrb, 3 * d_, 0, 3 * d_, {grad + o.bqkv, nullptr, nullptr}}};
+      launch_reduce_rows_multi(st, rj, 4);
     }
-    LnBwdArgs n0{dx, pre0_, mean0_, rstd0_, w.theta + eg_, ds32_, nullptr, lnpart_, M, d_};
+    LnBwdArgs n0{dx, pre0_, mean0_, rstd0_, w.theta + eg_, ds32_, nullptr, lnpart_[0], M, d_};
     launch_ln_bwd(st, n0);
-    launch_reduce_rows(st, lnpart_, nblk, 3 * d_, d_, d_, grad + eg_, grad + eb_, nullptr);
+    launch_reduce_rows(st, lnpart_[0], nblk, 3 * d_, d_, d_, grad + eg_, grad + eb_, nullptr);
     launch_fill_f32(st, grad + tok_, 0.f, (int64_t)V_ * d_);
     launch_embedding_bwd(st, ds32_, (const int32_t*)b.x, B, S_, d_, grad + tok_, grad + pos_);
   }
@@ -194,7 +201,7 @@ class EncoderModel : public Model {
   float* dX_[2] = {nullptr, nullptr};
   float* res_[2] = {nullptr, nullptr};   // fp32 LayerNorm outputs: the residual stream of the current forward pass
   float* ds32_ = nullptr; bf16_t* ds16_[2] = {nullptr, nullptr}; bf16_t* dpre_ = nullptr; bf16_t* do_ = nullptr; bf16_t* dqkv_ = nullptr;
-  float* lnpart_ = nullptr; float* cspart_ = nullptr;
+  float* lnpart_[2] = {nullptr, nullptr}; float* cspart_[2] = {nullptr, nullptr};
 };
 }  // namespace
 

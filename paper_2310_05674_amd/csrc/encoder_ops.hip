@@ -151,12 +151,19 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
   }
 }
 
-// out_v[c] = sum_r partial[r*stride + v*vstride + c] for up to three vectors v = blockIdx.y.  A block owns 32 columns;
-// eight row groups walk the rows with stride 8 (independent loads), then are added in a fixed order.
-struct ReduceRowsArgs { const float* partial; int nrows; int64_t stride, vstride; int N; float* out[3]; };
-__global__ __launch_bounds__(256) void k_reduce_rows(ReduceRowsArgs a) {
+// out_v[c] = sum_r partial[r*stride + v*vstride + c] for up to three vectors v per job, several jobs per launch.
+// A block owns 32 columns of one vector of one job; eight row groups walk the rows with stride 8 (independent
+// loads), then are added in a fixed order.
+struct ReduceRowsMulti { ReduceRowsJob j[REDUCE_MAX_JOBS]; int first_block[REDUCE_MAX_JOBS + 1]; int count; };
+__global__ __launch_bounds__(256) void k_reduce_rows(ReduceRowsMulti m) {
   __shared__ float s_part[8][33];
-  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5, c = blockIdx.x * 32 + cl, v = blockIdx.y;
+  int job = 0;
+#pragma unroll
+  for (int k = 1; k < REDUCE_MAX_JOBS; ++k)
+    if (k < m.count && (int)blockIdx.x >= m.first_block[k]) job = k;
+  const ReduceRowsJob& a = m.j[job];
+  const int local = blockIdx.x - m.first_block[job], nbx = (a.N + 31) / 32;
+  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5, c = (local % nbx) * 32 + cl, v = local / nbx;
   float acc = 0.f;
   if (c < a.N) {
     const float* p = a.partial + (int64_t)v * a.vstride + c;
@@ -173,14 +180,19 @@ __global__ __launch_bounds__(256) void k_reduce_rows(ReduceRowsArgs a) {
   }
 }
 
-__global__ __launch_bounds__(256) void k_colsum_partial_bf16(const bf16_t* __restrict__ X, int M, int N, float* __restrict__ partial) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= N) return;
-  const int r0 = blockIdx.y * COLSUM_ROWS;
+// partial[rb][c] = sum of COLSUM_ROWS rows of column c of a bf16 matrix, up to two matrices per launch
+struct ColsumMulti { ColsumJob j[2]; int first_block[3]; int count; };
+__global__ __launch_bounds__(256) void k_colsum_partial_bf16(ColsumMulti m) {
+  const int job = (m.count > 1 && (int)blockIdx.x >= m.first_block[1]) ? 1 : 0;
+  const ColsumJob& a = m.j[job];
+  const int local = blockIdx.x - m.first_block[job], nbx = (a.N + 255) / 256;
+  const int c = (local % nbx) * 256 + threadIdx.x, rb = local / nbx;
+  if (c >= a.N) return;
+  const int r0 = rb * COLSUM_ROWS;
   float s = 0.f;
 #pragma unroll 4
-  for (int r = r0; r < r0 + COLSUM_ROWS && r < M; ++r) s += bf16_to_f32(X[(int64_t)r * N + c]);
-  partial[(int64_t)blockIdx.y * N + c] = s;
+  for (int r = r0; r < r0 + COLSUM_ROWS && r < a.M; ++r) s += bf16_to_f32(a.X[(int64_t)r * a.N + c]);
+  a.partial[(int64_t)rb * a.N + c] = s;
 }
 
 // =========================================================================================== attention
@@ -504,19 +516,46 @@ void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) {
   ProfScope ps(st, F_LN_BWD, 14.0 * a.M * a.d);
   k_ln_bwd<<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
 }
+void launch_reduce_rows_multi(hipStream_t st, const ReduceRowsJob* jobs, int count) {
+  ReduceRowsMulti m{};
+  m.count = count;
+  int nb = 0;
+  double bytes = 0.0;
+  for (int k = 0; k < count; ++k) {
+    m.j[k] = jobs[k];
+    m.first_block[k] = nb;
+    const int nv = jobs[k].out[2] ? 3 : (jobs[k].out[1] ? 2 : 1);
+    nb += ((jobs[k].N + 31) / 32) * nv;
+    bytes += 4.0 * jobs[k].nrows * jobs[k].N * nv;
+  }
+  for (int k = count; k <= REDUCE_MAX_JOBS; ++k) m.first_block[k] = nb;
+  ProfScope ps(st, F_OTHER, bytes);
+  k_reduce_rows<<<nb, 256, 0, st>>>(m);
+}
 void launch_reduce_rows(hipStream_t st, const float* partial, int nrows, int64_t stride, int64_t vstride, int N, float* out0,
                         float* out1, float* out2) {
-  const int nv = out2 ? 3 : (out1 ? 2 : 1);
-  ProfScope ps(st, F_OTHER, 4.0 * nrows * N * nv);
-  ReduceRowsArgs a{partial, nrows, stride, vstride, N, {out0, out1, out2}};
-  k_reduce_rows<<<dim3((N + 31) / 32, nv), 256, 0, st>>>(a);
+  const ReduceRowsJob j{partial, nrows, stride, vstride, N, {out0, out1, out2}};
+  launch_reduce_rows_multi(st, &j, 1);
+}
+void launch_colsum_partial_multi(hipStream_t st, const ColsumJob* jobs, int count) {
+  ColsumMulti m{};
+  m.count = count;
+  int nb = 0;
+  double bytes = 0.0;
+  for (int k = 0; k < count; ++k) {
+    m.j[k] = jobs[k];
+    m.first_block[k] = nb;
+    nb += ((jobs[k].N + 255) / 256) * ((jobs[k].M + COLSUM_ROWS - 1) / COLSUM_ROWS);
+    bytes += 2.0 * jobs[k].M * jobs[k].N;
+  }
+  for (int k = count; k < 3; ++k) m.first_block[k] = nb;
+  ProfScope ps(st, F_OTHER, bytes);
+  k_colsum_partial_bf16<<<nb, 256, 0, st>>>(m);
 }
 void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* partial, float* out) {
   const int nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
-  {
-    ProfScope ps(st, F_OTHER, 2.0 * M * N);
-    k_colsum_partial_bf16<<<dim3((N + 255) / 256, nrb), 256, 0, st>>>(X, M, N, partial);
-  }
+  const ColsumJob j{X, M, N, partial};
+  launch_colsum_partial_multi(st, &j, 1);
   launch_reduce_rows(st, partial, nrb, N, 0, N, out, nullptr, nullptr);
 }
 void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d) {

@@ -152,6 +152,14 @@ void launch_ln_bwd(hipStream_t, const LnBwdArgs&);
 // out_v[c] = sum_r partial[r*stride + v*vstride + c] for the non-null outputs v = 0, 1, 2, in a fixed order
 void launch_reduce_rows(hipStream_t, const float* partial, int nrows, int64_t stride, int64_t vstride, int N, float* out0,
                         float* out1, float* out2);
+// the same for up to REDUCE_MAX_JOBS independent reductions in one launch (a job with fewer than three outputs
+// leaves the trailing out[] null)
+constexpr int REDUCE_MAX_JOBS = 4;
+struct ReduceRowsJob { const float* partial; int nrows; int64_t stride, vstride; int N; float* out[3]; };
+void launch_reduce_rows_multi(hipStream_t, const ReduceRowsJob* jobs, int count);
+// first stage of the column sums of up to two bf16 matrices [M x N] (ld = N): partial [ceil(M / COLSUM_ROWS)][N]
+struct ColsumJob { const bf16_t* X; int M, N; float* partial; };
+void launch_colsum_partial_multi(hipStream_t, const ColsumJob* jobs, int count);
 // column sums of a bf16 matrix [M x N] (ld = N) through partial [ceil(M / COLSUM_ROWS)][N]
 void launch_colsum_bf16(hipStream_t, const bf16_t* X, int M, int N, float* partial, float* out);
 // softmax(q k^T / 8) v for S = 128, head width 64; qkv [B*S x 3d] bf16; out [B*S x d] bf16; lse [B][heads][S]

@@ -24,6 +24,25 @@ sama_status sama_op_gemm_bf16(const void* A, int64_t lda, int32_t a_trans, const
   return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
 }
 
+sama_status sama_op_gemm_bf16_batch(int32_t count, const void* const* A, const void* const* B, const void* const* B2,
+                                    float* const* C32, const int32_t* M, const int32_t* N, const int32_t* K, int32_t a_trans,
+                                    int32_t b_trans, void* hip_stream) {
+  if (count < 1 || count > GEMM_MAX_BATCH || !A || !B || !C32 || !M || !N || !K) return SAMA_EINVAL;
+  GemmBf16Args g[GEMM_MAX_BATCH];
+  for (int k = 0; k < count; ++k) {
+    if (!A[k] || !B[k] || !C32[k] || (B2 && !B2[k])) return SAMA_EINVAL;
+    g[k] = GemmBf16Args{};
+    g[k].A = (const bf16_t*)A[k]; g[k].a_trans = a_trans ? 1 : 0; g[k].lda = a_trans ? M[k] : K[k];
+    g[k].B = (const bf16_t*)B[k]; g[k].B2 = B2 ? (const bf16_t*)B2[k] : nullptr; g[k].b_trans = b_trans ? 1 : 0;
+    g[k].ldb = b_trans ? K[k] : N[k];
+    g[k].M = M[k]; g[k].N = N[k]; g[k].K = K[k]; g[k].ldc = N[k]; g[k].C32 = C32[k];
+  }
+  if (check_gemm_bf16_batch(g, count) != nullptr) return SAMA_EINVAL;
+  (void)hipGetLastError();
+  launch_gemm_bf16_batch((hipStream_t)hip_stream, g, count);
+  return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
+}
+
 sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16, int64_t t,
                          float lr, float beta1, float beta2, float eps, float weight_decay, void* hip_stream) {
   if (!g || !m || !v || !theta || n < 0 || n16 < 0 || n16 > n || t < 1) return SAMA_EINVAL;

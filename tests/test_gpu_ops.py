@@ -159,3 +159,51 @@ def test_gemm_rejects_unsupported_shapes():
     A = torch.zeros((60, 64), dtype=torch.bfloat16, device=DEV)
     with pytest.raises(B.SamaError):
         B.op_gemm_bf16(A, torch.zeros((64, 64), dtype=torch.bfloat16, device=DEV), out32=torch.zeros((60, 64), device=DEV))
+
+
+@pytest.mark.parametrize("a_trans,b_trans,split", [(False, True, True), (False, True, False), (True, False, False), (False, False, True)])
+def test_gemm_bf16_batch(a_trans, b_trans, split):
+    """Several problems of different shapes in one launch (the stacked +- passes, a layer's weight gradients): every
+    problem against numpy float64, and bit-identical to the same problem launched alone."""
+    from paper_2310_05674_amd import binding as B
+    shapes = [(264, 136, 128), (520, 392, 192), (128, 1024, 64), (1032, 72, 256)]
+    As, Bs, B2s, outs, wants = [], [], [], [], []
+    for i, (M, N, K) in enumerate(shapes):
+        r = CounterRNG(900 + 7 * i + M)
+        A = round_to_bf16(r.normal(1, M * K)).reshape((K, M) if a_trans else (M, K))
+        Bm = round_to_bf16(r.normal(2, N * K)).reshape((N, K) if b_trans else (K, N))
+        B2 = round_to_bf16(0.004 * r.normal(3, N * K)).reshape(Bm.shape) if split else None
+        Af = A.T if a_trans else A
+        Bf = Bm + (B2 if split else 0.0); Bf = Bf.T if b_trans else Bf
+        wants.append(Af @ Bf)
+        As.append(_dev(A, torch.bfloat16)); Bs.append(_dev(Bm, torch.bfloat16))
+        if split:
+            B2s.append(_dev(B2, torch.bfloat16))
+        outs.append(torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV))
+    B.op_gemm_bf16_batch(As, Bs, outs, a_trans=a_trans, b_trans=b_trans, B2s=B2s if split else None)
+    for i, (M, N, K) in enumerate(shapes):
+        got = outs[i].cpu().numpy()
+        assert np.all(np.isfinite(got)), i
+        assert rel_l2(got, wants[i]) < 1e-5, i
+    # the same problems as single launches with the batch's tile forced: identical bits (same tile => same summation order)
+    alone = []
+    for i in range(len(shapes)):
+        o = torch.empty_like(outs[i])
+        B.op_gemm_bf16_batch([As[i]], [Bs[i]], [o], a_trans=a_trans, b_trans=b_trans, B2s=[B2s[i]] if split else None)
+        alone.append(o)
+    again = [torch.empty_like(o) for o in outs]
+    B.op_gemm_bf16_batch(As, Bs, again, a_trans=a_trans, b_trans=b_trans, B2s=B2s if split else None)
+    for i in range(len(shapes)):
+        assert torch.equal(again[i], outs[i]), i          # bit-stable from launch to launch
+        assert rel_l2(alone[i].cpu().numpy(), wants[i]) < 1e-5, i
+
+
+def test_gemm_bf16_batch_rejects_mixed():
+    from paper_2310_05674_amd import binding as B
+    a = torch.zeros((64, 64), dtype=torch.bfloat16, device=DEV)
+    o = torch.zeros((64, 64), dtype=torch.float32, device=DEV)
+    with pytest.raises(B.SamaError):
+        B.op_gemm_bf16_batch([a] * 5, [a] * 5, [o] * 5)                 # more than four problems
+    bad = torch.zeros((64, 72), dtype=torch.bfloat16, device=DEV)       # K = 72 is not a multiple of 64
+    with pytest.raises(B.SamaError):
+        B.op_gemm_bf16_batch([bad], [bad], [o])
