@@ -231,6 +231,47 @@ __global__ __launch_bounds__(EW_THREADS) void k_perturb_lo(const float* __restri
   }
 }
 
+// The same for a step that will also be applied (sama_meta_step): theta <- theta - eps v on the GEMM block right
+// away, hi = bf16 of the NEW theta, lo+- = bf16((theta_old +- eps v) - hi).  The +- passes then contract with the same
+// values theta_old +- eps v as above, and the later nudge only has the non-GEMM tail left.  eps = 0 (a skipped
+// step): theta and hi stay as they are, lo+- = the plain residual.
+__global__ __launch_bounds__(EW_THREADS) void k_perturb_nudge(float* __restrict__ theta, const float* __restrict__ vdir,
+                                                              const float* __restrict__ eps_ptr, bf16_t* __restrict__ theta16,
+                                                              bf16_t* __restrict__ lo_p, bf16_t* __restrict__ lo_m, int64_t n16) {
+  const float eps = *eps_ptr;
+  const bool skip = eps == 0.f;
+  const int64_t nv = n16 / EW_VEC, trip = (int64_t)gridDim.x * EW_TRIP;
+  for (int64_t base = (int64_t)blockIdx.x * EW_TRIP + threadIdx.x; base < nv; base += trip) {
+    f4 T[EW_U], V[EW_U];
+#pragma unroll
+    for (int u = 0; u < EW_U; ++u) {
+      const int64_t j = base + u * EW_THREADS;
+      if (j < nv) { T[u] = ld_nt(theta, j); V[u] = ld_nt(vdir, j); }
+    }
+#pragma unroll
+    for (int u = 0; u < EW_U; ++u) {
+      const int64_t j = base + u * EW_THREADS;
+      if (j < nv) {
+        f4 tn;
+        float p[4], q[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          tn[e] = skip ? T[u][e] : fmaf(-eps, V[u][e], T[u][e]);
+          const float hi = bf16_to_f32(f32_to_bf16(tn[e]));
+          p[e] = (skip ? T[u][e] : fmaf(eps, V[u][e], T[u][e])) - hi;
+          q[e] = tn[e] - hi;
+        }
+        if (!skip) {
+          st_nt(theta, j, tn);
+          st_bf16x4_nt(theta16, j, tn.x, tn.y, tn.z, tn.w);
+        }
+        st_bf16x4_nt(lo_p, j, p[0], p[1], p[2], p[3]);
+        st_bf16x4_nt(lo_m, j, q[0], q[1], q[2], q[3]);
+      }
+    }
+  }
+}
+
 __global__ __launch_bounds__(EW_THREADS) void k_residual_lo(const float* __restrict__ theta, bf16_t* __restrict__ lo, int64_t n16) {
   const int64_t nv = n16 / EW_VEC, trip = (int64_t)gridDim.x * EW_TRIP;
   for (int64_t base = (int64_t)blockIdx.x * EW_TRIP + threadIdx.x; base < nv; base += trip) {
@@ -339,6 +380,12 @@ void launch_perturb_lo(hipStream_t st, const float* theta, const float* vdir, co
   if (n16 <= 0) return;
   ProfScope ps(st, F_PERTURB, 12.0 * n16);
   k_perturb_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, lo_p, lo_m, n16);
+}
+void launch_perturb_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, bf16_t* lo_p,
+                          bf16_t* lo_m, int64_t n16) {
+  if (n16 <= 0) return;
+  ProfScope ps(st, F_PERTURB, 18.0 * n16);
+  k_perturb_nudge<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, theta16, lo_p, lo_m, n16);
 }
 void launch_residual_lo(hipStream_t st, const float* theta, bf16_t* lo, int64_t n16) {
   if (n16 <= 0) return;

@@ -49,6 +49,10 @@ void launch_adapt_norm(hipStream_t, const float* g, const float* m, const float*
                        int64_t* status);
 void launch_perturb_lo(hipStream_t, const float* theta, const float* vdir, const float* eps_ptr, bf16_t* lo_p,
                        bf16_t* lo_m, int64_t n16);
+// perturb_lo and the nudge of the first n16 elements (n16 % 4 == 0) in one pass: theta, theta16 <- theta - eps v,
+// lo_p / lo_m = low halves of theta_old +- eps v against the NEW theta16
+void launch_perturb_nudge(hipStream_t, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, bf16_t* lo_p,
+                          bf16_t* lo_m, int64_t n16);
 // lo[k] = bf16(theta[k] - float(bf16(theta[k]))): the part of the master weights the bf16 working copy cannot hold
 void launch_residual_lo(hipStream_t, const float* theta, bf16_t* lo, int64_t n16);
 void launch_nudge(hipStream_t, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, int64_t n,

@@ -291,7 +291,11 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
     ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
   }
   launch_adapt_norm(st, c->g, c->m, c->v, c->gmeta, c->vdir, c->partial, c->n, ad, f.alpha, c->scalars, c->counters + 2);
-  if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
+  // A step that is applied nudges the GEMM block of theta in the same pass that writes the low halves (one pass over
+  // theta and v instead of two); the non-GEMM tail is nudged after the two passes, which read it as theta +- eps v.
+  const bool fused_nudge = update && c->bf16 && c->n_gemm % 4 == 0;
+  if (fused_nudge) launch_perturb_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->lo_p, c->lo_m, c->n_gemm);
+  else if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
   // passes 2 and 3: dL_base/dlambda at theta +- eps v; forward only, then the weight net's backward
   c->model->forward_pair(st, pass_weights(c, 1.f), pass_weights(c, -1.f), *train, c->logits);
   for (int pass = 0; pass < 2; ++pass) {
@@ -308,7 +312,8 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
   mu.lambda = c->lambda; mu.meta_m = c->meta_m; mu.meta_v = c->meta_v; mu.nl = c->nl; mu.do_update = update ? 1 : 0;
   mu.lr = f.meta_lr; mu.beta1 = f.meta_beta1; mu.beta2 = f.meta_beta2; mu.eps = f.meta_eps;
   launch_meta_update(st, mu);
-  if (update) launch_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->n, c->n_gemm);
+  if (update && fused_nudge) launch_nudge(st, c->theta + c->n_gemm, c->vdir + c->n_gemm, c->scalars, nullptr, c->n - c->n_gemm, 0);
+  else if (update) launch_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->n, c->n_gemm);
   return check_hip(c, update ? "sama_meta_step" : "sama_meta_grad");
 }
 
