@@ -156,7 +156,12 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
   const int nk = a.K / BK;
-  const int iters = (!DUAL && a.B2 != nullptr) ? 2 * nk : nk;   // non-DUAL tiles contract with hi, then with lo
+  // The operand pointers live in registers for the whole k loop (read through `a` they would be re-fetched from the
+  // kernel-argument segment after every inline-assembly load, a scalar-memory round trip per slab).
+  const char* const pA = reinterpret_cast<const char*>(a.A);
+  const char* const pB = reinterpret_cast<const char*>(a.B);
+  const char* const pB2 = reinterpret_cast<const char*>(a.B2);
+  const int iters = (!DUAL && pB2 != nullptr) ? 2 * nk : nk;   // non-DUAL tiles contract with hi, then with lo
 
   // per-lane global offsets of this wave's loads
   uint32_t offA[T::NLA], offB[T::NLB];
@@ -177,9 +182,9 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
     if (sl >= iters) return;
     const int stage = sl % NSTAGE;
     const int kq = sl >= nk ? sl - nk : sl;
-    const char* ap = reinterpret_cast<const char*>(a.A) + kq * stepA;
-    const char* bp = reinterpret_cast<const char*>(sl >= nk ? a.B2 : a.B) + kq * stepB;
-    const char* b2p = reinterpret_cast<const char*>(a.B2) + kq * stepB;
+    const char* ap = pA + kq * stepA;
+    const char* bp = (sl >= nk ? pB2 : pB) + kq * stepB;
+    const char* b2p = pB2 + kq * stepB;
     const uint32_t sa = lds0 + stage * T::STAGE_BYTES + wave * 1024;
     const uint32_t sb = sa + T::A_BYTES;
 #pragma unroll
