@@ -93,10 +93,29 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
     gam[j] = (lane + 64 * j < nq) ? reinterpret_cast<const float4*>(a.gamma)[lane + 64 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const int r0 = blockIdx.x * LN_BWD_ROWS + wave * (LN_BWD_ROWS / 4);
-  for (int rr = 0; rr < LN_BWD_ROWS / 4; ++rr) {
+  constexpr int RW = LN_BWD_ROWS / 4;   // rows per wave: all of their loads are issued before the first row is reduced
+  float4 xin[RW][4], dyin[RW][4];
+  float mus[RW], rstds[RW];
+#pragma unroll
+  for (int rr = 0; rr < RW; ++rr) {
+    const int row = r0 + rr;
+    mus[rr] = rstds[rr] = 0.f;
+    if (row < a.M) { mus[rr] = a.mean[row]; rstds[rr] = a.rstd[row]; }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = lane + 64 * j;
+      xin[rr][j] = dyin[rr][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row < a.M && q < nq) {
+        xin[rr][j] = reinterpret_cast<const float4*>(a.x + (int64_t)row * a.d)[q];
+        dyin[rr][j] = reinterpret_cast<const float4*>(a.dy + (int64_t)row * a.d)[q];
+      }
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < RW; ++rr) {
     const int row = r0 + rr;
     if (row >= a.M) break;
-    const float mu = a.mean[row], rstd = a.rstd[row];
+    const float mu = mus[rr], rstd = rstds[rr];
     float4 xh[4], dyg[4];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -104,8 +123,8 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
       const int q = lane + 64 * j;
       xh[j] = dyg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (q < nq) {
-        const float4 x = reinterpret_cast<const float4*>(a.x + (int64_t)row * a.d)[q];
-        const float4 dy = reinterpret_cast<const float4*>(a.dy + (int64_t)row * a.d)[q];
+        const float4 x = xin[rr][j];
+        const float4 dy = dyin[rr][j];
         xh[j] = make_float4((x.x - mu) * rstd, (x.y - mu) * rstd, (x.z - mu) * rstd, (x.w - mu) * rstd);
         dyg[j] = make_float4(dy.x * gam[j].x, dy.y * gam[j].y, dy.z * gam[j].z, dy.w * gam[j].w);
         dg[j].x = fmaf(dy.x, xh[j].x, dg[j].x); dg[j].y = fmaf(dy.y, xh[j].y, dg[j].y);
@@ -500,9 +519,19 @@ __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb
     if (s_cnt > 0 && s_list[0] != m) return;   // an earlier position holds this id (the list is ascending)
   }
   const int cnt = s_cnt < 4096 ? s_cnt : 4096;
+  // a frequent id (position 0 of every sequence, the head of the Zipf law) has hundreds of rows: fetch them sixteen at
+  // a time so that their latencies overlap, add them in list order
   for (int c = threadIdx.x; c < d; c += 256) {
     float s = 0.f;
-    for (int i = 0; i < cnt; ++i) s += demb[(int64_t)s_list[i] * d + c];
+    int i = 0;
+    for (; i + 16 <= cnt; i += 16) {
+      float v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = demb[(int64_t)s_list[i + u] * d + c];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) s += v[u];
+    }
+    for (; i < cnt; ++i) s += demb[(int64_t)s_list[i] * d + c];
     g_tok[(int64_t)id * d + c] = s;
   }
 }
