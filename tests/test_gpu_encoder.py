@@ -95,6 +95,43 @@ def test_small_encoder_meta_step(scale):
     gpu.close()
 
 
+def test_meta_grad_is_pure_and_matches_meta_step():
+    """sama_meta_grad leaves theta, lambda and the moments untouched and returns the hypergradient that sama_meta_step
+    then applies.  The two take different routes through the elementwise chain (separate low halves and nudge against
+    the old bf16 copy / one fused pass against the new one), so the two hypergradients agree to rounding of the low
+    halves, not bit for bit; the applied step must still land on the oracle's theta."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    for s in range(4):
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(x, y)
+    (x, y), (xm, ym) = _batches(wl, 4)
+    _snap(orc)
+    push_state(orc, gpu)
+    tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+    before = {k: pull(gpu, k).copy() for k in ("THETA", "LAMBDA", "M", "V", "META_M", "META_V")}
+    gpu.meta_grad(tb, mb)
+    for k, v in before.items():
+        assert np.array_equal(pull(gpu, k), v), k
+    h_pure = pull(gpu, "HYPERGRAD").copy()
+    gpu.meta_grad(tb, mb)
+    assert np.array_equal(pull(gpu, "HYPERGRAD"), h_pure)          # and is repeatable bit for bit
+    r = orc.meta_step(x, y, xm, ym)
+    gpu.meta_step(tb, mb)
+    h = pull(gpu, "HYPERGRAD")
+    assert rel_l2(h_pure, r["h"]) < TOL and rel_l2(h, r["h"]) < TOL
+    assert rel_l2(h, h_pure) < 5e-3, rel_l2(h, h_pure)
+    assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    th = pull(gpu, "THETA")
+    # the nudge itself, fused block and tail alike: theta_old - eps v with the GPU's own eps and v, one fp32 rounding
+    want = before["THETA"].astype(np.float64) - float(pull(gpu, "SCALARS")[0]) * pull(gpu, "VDIR").astype(np.float64)
+    assert np.max(np.abs(th - want)) <= 2.0 ** -23 * np.max(np.abs(want))
+    for name, (off, shape) in orc.model.slices.items():           # every tensor moved, GEMM block and tail alike
+        sl = slice(off, off + int(np.prod(shape)))
+        assert not np.array_equal(th[sl], before["THETA"][sl]), name
+    gpu.close()
+
+
 # ------------------------------------------------------------------------------------------ full workloads 3-5
 def _full_workload_parity(cfg, n_train, n_meta):
     """Real shapes and hyper-parameters of workload `cfg`.  Base step 0 starts from the bf16-representable
