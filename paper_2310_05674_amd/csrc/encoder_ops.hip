@@ -202,16 +202,30 @@ __global__ __launch_bounds__(256) void k_reduce_rows(ReduceRowsMulti m) {
 // partial[rb][c] = sum of COLSUM_ROWS rows of column c of a bf16 matrix, up to two matrices per launch
 struct ColsumMulti { ColsumJob j[2]; int first_block[3]; int count; };
 __global__ __launch_bounds__(256) void k_colsum_partial_bf16(ColsumMulti m) {
+  // a thread owns 8 adjacent columns (one 16-byte load per row); N is a multiple of 8
   const int job = (m.count > 1 && (int)blockIdx.x >= m.first_block[1]) ? 1 : 0;
   const ColsumJob& a = m.j[job];
-  const int local = blockIdx.x - m.first_block[job], nbx = (a.N + 255) / 256;
-  const int c = (local % nbx) * 256 + threadIdx.x, rb = local / nbx;
+  const int local = blockIdx.x - m.first_block[job], nbx = (a.N + 2047) / 2048;
+  const int c = ((local % nbx) * 256 + threadIdx.x) * 8, rb = local / nbx;
   if (c >= a.N) return;
   const int r0 = rb * COLSUM_ROWS;
-  float s = 0.f;
-#pragma unroll 4
-  for (int r = r0; r < r0 + COLSUM_ROWS && r < a.M; ++r) s += bf16_to_f32(a.X[(int64_t)r * a.N + c]);
-  a.partial[(int64_t)rb * a.N + c] = s;
+  float s[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s[e] = 0.f;
+  uint4 v[COLSUM_ROWS];
+#pragma unroll
+  for (int r = 0; r < COLSUM_ROWS; ++r)
+    v[r] = (r0 + r < a.M) ? *reinterpret_cast<const uint4*>(a.X + (int64_t)(r0 + r) * a.N + c) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+  for (int r = 0; r < COLSUM_ROWS; ++r) {
+    if (r0 + r >= a.M) break;
+    const uint32_t w[4] = {v[r].x, v[r].y, v[r].z, v[r].w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s[e] += bf16_to_f32((bf16_t)(w[e >> 1] >> ((e & 1) * 16)));
+  }
+  float* out = a.partial + (int64_t)rb * a.N + c;
+  *reinterpret_cast<float4*>(out) = make_float4(s[0], s[1], s[2], s[3]);
+  *reinterpret_cast<float4*>(out + 4) = make_float4(s[4], s[5], s[6], s[7]);
 }
 
 // =========================================================================================== attention
@@ -574,7 +588,7 @@ void launch_colsum_partial_multi(hipStream_t st, const ColsumJob* jobs, int coun
   for (int k = 0; k < count; ++k) {
     m.j[k] = jobs[k];
     m.first_block[k] = nb;
-    nb += ((jobs[k].N + 255) / 256) * ((jobs[k].M + COLSUM_ROWS - 1) / COLSUM_ROWS);
+    nb += ((jobs[k].N + 2047) / 2048) * ((jobs[k].M + COLSUM_ROWS - 1) / COLSUM_ROWS);
     bytes += 2.0 * jobs[k].M * jobs[k].N;
   }
   for (int k = count; k < 3; ++k) m.first_block[k] = nb;
