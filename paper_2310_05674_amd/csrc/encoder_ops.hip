@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) void k_colsum_partial_bf16(ColsumMulti m) {
 }
 
 // =========================================================================================== attention
-constexpr int AS = 128, AD = 64, ALD = AS + 8;  // sequence length, head width, LDS row stride of transposed tiles
+constexpr int AS = 128, AD = 64;  // sequence length, head width
 
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ s16x4 ld_s16x4(const bf16_t* p) { return *reinterpret_cast<const s16x4*>(p); }
@@ -239,16 +239,22 @@ __device__ __forceinline__ s16x4 pack4(float a, float b, float c, float d) {
   return r;
 }
 
-// transposed copy of a [128 x 64] bf16 tile (row stride ld) into LDS as T[e][row], row stride ALD
-__device__ __forceinline__ void stage_transposed(const bf16_t* __restrict__ src, int64_t ld, bf16_t* __restrict__ T) {
+// A [128 x 64] bf16 tile (row stride ld) staged in LDS as it lies in memory, S[row][e] with row stride SLD (192 bytes:
+// the four rows one transposing read touches fall into four different 64-byte bank windows), and its transposed MFMA
+// operand: for the 32x32x8 MFMA, lane l gets S[k0 + 4 (l / 32) + 0..3][e32 + l % 32] through ds_read_b64_tr_b16.
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+constexpr int SLD = AD + 32;
+__device__ __forceinline__ void stage_rows(const bf16_t* __restrict__ src, int64_t ld, bf16_t* __restrict__ S) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int c = threadIdx.x + 256 * i, row = c >> 3, ec = c & 7;
-    const uint4 v = *reinterpret_cast<const uint4*>(src + (int64_t)row * ld + ec * 8);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) T[(ec * 8 + e) * ALD + row] = (bf16_t)(w[e >> 1] >> ((e & 1) * 16));
+    *reinterpret_cast<uint4*>(S + row * SLD + ec * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)row * ld + ec * 8);
   }
+}
+__device__ __forceinline__ s16x4 ld_transposed(const bf16_t* __restrict__ S, int e32, int k0, int lane) {
+  const int g = lane >> 4, j = lane & 15;
+  const bf16_t* p = S + (k0 + 4 * (g >> 1) + (j >> 2)) * SLD + e32 + 16 * (g & 1) + 4 * (j & 3);
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
 }
 
 // X^T-style product tile: acc[32 x 32] (+)= sum_e R[rbase + l%32][e] * Cc[cbase + l%32][e], both operands read
@@ -271,13 +277,13 @@ __device__ __forceinline__ f32x16 rows_dot_rows(const bf16_t* __restrict__ R, co
 // the B-operand layout of the 32x32x8 MFMA for O^T[e][q] = sum_key V^T[e][key] P^T[key][q].
 __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out, float* __restrict__ lse,
                                                   int heads, int d) {
-  __shared__ __attribute__((aligned(16))) bf16_t Vt[AD * ALD];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[AS * SLD];
   const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t ld = 3 * (int64_t)d;
   const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
   const bf16_t* K = Q + d;
   const bf16_t* V = Q + 2 * d;
-  stage_transposed(V, ld, Vt);
+  stage_rows(V, ld, Vs);
   f32x16 s[4];
 #pragma unroll
   for (int kt = 0; kt < 4; ++kt) s[kt] = rows_dot_rows(K, Q, ld, 32 * kt, 32 * wave, lane);
@@ -306,7 +312,7 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const s16x4 pb = pack4(s[kt][4 * c] * inv, s[kt][4 * c + 1] * inv, s[kt][4 * c + 2] * inv, s[kt][4 * c + 3] * inv);
-        const s16x4 va = ld_s16x4(Vt + (32 * et + (lane & 31)) * ALD + 32 * kt + 8 * c + 4 * (lane >> 5));
+        const s16x4 va = ld_transposed(Vs, 32 * et, 32 * kt + 8 * c, lane);
         o[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(va, pb, o[et], 0, 0, 0);
       }
   }
@@ -330,9 +336,9 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
 __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ out,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ lse,
                                                   bf16_t* __restrict__ dqkv, int heads, int d) {
-  __shared__ __attribute__((aligned(16))) bf16_t Kt[AD * ALD];
-  __shared__ __attribute__((aligned(16))) bf16_t Qt[AD * ALD];
-  __shared__ __attribute__((aligned(16))) bf16_t dOt[AD * ALD];
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[AS * SLD];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[AS * SLD];
+  __shared__ __attribute__((aligned(16))) bf16_t dOs[AS * SLD];
   __shared__ float s_D[AS], s_lse[AS];
   const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t ld = 3 * (int64_t)d;
@@ -341,9 +347,9 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
   const bf16_t* V = Q + 2 * d;
   const bf16_t* O = out + (int64_t)b * AS * d + h * AD;
   const bf16_t* dO = dout + (int64_t)b * AS * d + h * AD;
-  stage_transposed(K, ld, Kt);
-  stage_transposed(Q, ld, Qt);
-  stage_transposed(dO, d, dOt);
+  stage_rows(K, ld, Ks);
+  stage_rows(Q, ld, Qs);
+  stage_rows(dO, d, dOs);
   {
     const int q = threadIdx.x >> 1, half = threadIdx.x & 1;
     float acc = 0.f;
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
         const s16x4 dsb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
 #pragma unroll
         for (int et = 0; et < 2; ++et) {
-          const s16x4 ka = ld_s16x4(Kt + (32 * et + (lane & 31)) * ALD + 32 * kt + 8 * c + 4 * (lane >> 5));
+          const s16x4 ka = ld_transposed(Ks, 32 * et, 32 * kt + 8 * c, lane);
           dq[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ka, dsb, dq[et], 0, 0, 0);
         }
       }
@@ -435,9 +441,8 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
         const s16x4 dsb = pack4(ds[4 * c], ds[4 * c + 1], ds[4 * c + 2], ds[4 * c + 3]);
 #pragma unroll
         for (int et = 0; et < 2; ++et) {
-          const int off = (32 * et + (lane & 31)) * ALD + 32 * qt + 8 * c + 4 * (lane >> 5);
-          dv[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_s16x4(dOt + off), pb, dv[et], 0, 0, 0);
-          dk[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_s16x4(Qt + off), dsb, dk[et], 0, 0, 0);
+          dv[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_transposed(dOs, 32 * et, 32 * qt + 8 * c, lane), pb, dv[et], 0, 0, 0);
+          dk[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_transposed(Qs, 32 * et, 32 * qt + 8 * c, lane), dsb, dk[et], 0, 0, 0);
         }
       }
     }
