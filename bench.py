@@ -147,6 +147,7 @@ def main():
             "unit": d.get("unit"), "frac": d.get("frac"),
             "traffic": MEASURED_TRAFFIC_BYTES.get((cfg_id, dom)) if args.unroll == 1 and not args.fast_meta_pass else None,
             "avg_us": d["avg_us"],
+            "frac_single_term": d.get("frac_single_term"),   # hi + lo families priced at 2 M N K instead of 2 M N (2K); else null
             "elementwise_chain": {"bound": "hbm", "achieved": ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None,
                                   "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                   "frac": ew_bytes / (ew_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if ew_ms > 0 else None,
