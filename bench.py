@@ -108,7 +108,8 @@ def main():
                     "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
                    "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
                    "wnet_hidden": wl.H, "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
-                   "last_step_skipped": bool(skipped)},
+                   "last_step_skipped": bool(skipped),
+                   "workspace_bytes": int(s.lib.sama_workspace_bytes(__import__("ctypes").byref(cfg)))},
     }
 
     # ---------------------------------------------------------------- per-kernel roofline (instrumented replay)
