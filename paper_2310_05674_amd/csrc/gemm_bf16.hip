@@ -322,50 +322,83 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       bias.x = fmaf(s, bv.x, bias.x); bias.y = fmaf(s, bv.y, bias.y); bias.z = fmaf(s, bv.z, bias.z); bias.w = fmaf(s, bv.w, bias.w);
     }
   }
+  const bf16_t* const res16 = a.res16; const float* const res32 = a.res32; const bf16_t* const aux16 = a.aux16;
+  bf16_t* const C16_pre = a.C16_pre; bf16_t* const C16 = a.C16; float* const C32 = a.C32;
+  const int act = a.act, Mrows = a.M;
+  const int64_t ldc = a.ldc;
+  constexpr int NIT = 32 / RPP;
+  // one output vector: bias, residual, activation, stores
+  auto finish = [&](const float4& v, int64_t o, const float4& rr32, const uint2& rr16, const uint2& axv) {
+    float c[4] = {v.x + bias.x, v.y + bias.y, v.z + bias.z, v.w + bias.w};
+    if (res16 != nullptr) {
+      c[0] += bf16_to_f32((bf16_t)rr16.x); c[1] += bf16_to_f32((bf16_t)(rr16.x >> 16));
+      c[2] += bf16_to_f32((bf16_t)rr16.y); c[3] += bf16_to_f32((bf16_t)(rr16.y >> 16));
+    }
+    if (res32 != nullptr) { c[0] += rr32.x; c[1] += rr32.y; c[2] += rr32.z; c[3] += rr32.w; }
+    if (act == GEMM_ACT_GELU_FWD) {
+      uint2 pk;
+      pk.x = pack_bf16x2(c[0], c[1]);
+      pk.y = pack_bf16x2(c[2], c[3]);
+      *reinterpret_cast<uint2*>(C16_pre + o) = pk;
+      // the backward pass sees the rounded pre-activation, so the activation is taken from it too
+      c[0] = gelu_f(bf16_to_f32((bf16_t)pk.x)); c[1] = gelu_f(bf16_to_f32((bf16_t)(pk.x >> 16)));
+      c[2] = gelu_f(bf16_to_f32((bf16_t)pk.y)); c[3] = gelu_f(bf16_to_f32((bf16_t)(pk.y >> 16)));
+    } else if (act == GEMM_ACT_GELU_BWD) {
+      c[0] *= dgelu_f(bf16_to_f32((bf16_t)axv.x)); c[1] *= dgelu_f(bf16_to_f32((bf16_t)(axv.x >> 16)));
+      c[2] *= dgelu_f(bf16_to_f32((bf16_t)axv.y)); c[3] *= dgelu_f(bf16_to_f32((bf16_t)(axv.y >> 16)));
+    }
+    if (C32 != nullptr) *reinterpret_cast<float4*>(C32 + o) = make_float4(c[0], c[1], c[2], c[3]);
+    if (C16 != nullptr) {
+      uint2 pk;
+      pk.x = pack_bf16x2(c[0], c[1]);
+      pk.y = pack_bf16x2(c[2], c[3]);
+      *reinterpret_cast<uint2*>(C16 + o) = pk;
+    }
+  };
+  const bool side = res32 != nullptr || res16 != nullptr || act == GEMM_ACT_GELU_BWD;
 #pragma unroll
   for (int x = 0; x < XT; ++x) {
-    if (x > 0) __syncthreads();
+    // Side inputs of this 32-row slice (residual, saved pre-activation) are requested before the accumulators go
+    // through LDS, so that their latency hides behind the staging.  Launches without side inputs skip this path.
+    float4 r32[NIT];
+    uint2 r16[NIT], ax[NIT];
+    if (side && col_ok) {
+#pragma unroll
+      for (int itr = 0; itr < NIT; ++itr) {
+        const int gi = i0 + wr + x * 32 + rq + RPP * itr;
+        r32[itr] = make_float4(0.f, 0.f, 0.f, 0.f); r16[itr] = make_uint2(0u, 0u); ax[itr] = make_uint2(0u, 0u);
+        if (gi < Mrows) {
+          const int64_t o = (int64_t)gi * ldc + gj;
+          if (res32 != nullptr) r32[itr] = *reinterpret_cast<const float4*>(res32 + o);
+          if (res16 != nullptr) r16[itr] = *reinterpret_cast<const uint2*>(res16 + o);
+          if (act == GEMM_ACT_GELU_BWD) ax[itr] = *reinterpret_cast<const uint2*>(aux16 + o);
+        }
+      }
+    }
+    // the staging region is private to the wave: LDS operations of one wave complete in order, no block barrier
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 #pragma unroll
     for (int y = 0; y < YT; ++y)
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         epi[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * EPI_LD + y * 32 + (lane & 31)] = acc[x][y][r];
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     if (!col_ok) continue;
+    if (side) {
+#pragma unroll
+      for (int itr = 0; itr < NIT; ++itr) {
+        const int row = rq + RPP * itr, gi = i0 + wr + x * 32 + row;
+        if (gi >= Mrows) break;
+        finish(*reinterpret_cast<const float4*>(epi + row * EPI_LD + 4 * cg), (int64_t)gi * ldc + gj, r32[itr], r16[itr], ax[itr]);
+      }
+    } else {
+      const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      const uint2 z2 = make_uint2(0u, 0u);
 #pragma unroll 4
-    for (int itr = 0; itr < 32 / RPP; ++itr) {
-      const int row = rq + RPP * itr, gi = i0 + wr + x * 32 + row;
-      if (gi >= a.M) break;
-      const float4 v = *reinterpret_cast<const float4*>(epi + row * EPI_LD + 4 * cg);
-      const int64_t o = (int64_t)gi * a.ldc + gj;
-      float c[4] = {v.x + bias.x, v.y + bias.y, v.z + bias.z, v.w + bias.w};
-      if (a.res16 != nullptr) {
-        const uint2 rr = *reinterpret_cast<const uint2*>(a.res16 + o);
-        c[0] += bf16_to_f32((bf16_t)rr.x); c[1] += bf16_to_f32((bf16_t)(rr.x >> 16));
-        c[2] += bf16_to_f32((bf16_t)rr.y); c[3] += bf16_to_f32((bf16_t)(rr.y >> 16));
-      }
-      if (a.res32 != nullptr) {
-        const float4 rr = *reinterpret_cast<const float4*>(a.res32 + o);
-        c[0] += rr.x; c[1] += rr.y; c[2] += rr.z; c[3] += rr.w;
-      }
-      if (a.act == GEMM_ACT_GELU_FWD) {
-        uint2 pk;
-        pk.x = pack_bf16x2(c[0], c[1]);
-        pk.y = pack_bf16x2(c[2], c[3]);
-        *reinterpret_cast<uint2*>(a.C16_pre + o) = pk;
-        c[0] = gelu_f(bf16_to_f32((bf16_t)pk.x)); c[1] = gelu_f(bf16_to_f32((bf16_t)(pk.x >> 16)));
-        c[2] = gelu_f(bf16_to_f32((bf16_t)pk.y)); c[3] = gelu_f(bf16_to_f32((bf16_t)(pk.y >> 16)));
-      } else if (a.act == GEMM_ACT_GELU_BWD) {
-        const uint2 ax = *reinterpret_cast<const uint2*>(a.aux16 + o);
-        c[0] *= dgelu_f(bf16_to_f32((bf16_t)ax.x)); c[1] *= dgelu_f(bf16_to_f32((bf16_t)(ax.x >> 16)));
-        c[2] *= dgelu_f(bf16_to_f32((bf16_t)ax.y)); c[3] *= dgelu_f(bf16_to_f32((bf16_t)(ax.y >> 16)));
-      }
-      if (a.C32 != nullptr) *reinterpret_cast<float4*>(a.C32 + o) = make_float4(c[0], c[1], c[2], c[3]);
-      if (a.C16 != nullptr) {
-        uint2 pk;
-        pk.x = pack_bf16x2(c[0], c[1]);
-        pk.y = pack_bf16x2(c[2], c[3]);
-        *reinterpret_cast<uint2*>(a.C16 + o) = pk;
+      for (int itr = 0; itr < NIT; ++itr) {
+        const int row = rq + RPP * itr, gi = i0 + wr + x * 32 + row;
+        if (gi >= Mrows) break;
+        finish(*reinterpret_cast<const float4*>(epi + row * EPI_LD + 4 * cg), (int64_t)gi * ldc + gj, z4, z2, z2);
       }
     }
   }
