@@ -48,7 +48,7 @@ struct Tile {
   static constexpr int NL = NLA + (DUAL ? 2 : 1) * NLB;
   static_assert(LDS_MAX >= NSTAGE * STAGE_BYTES, "stages exceed the 160 KB of LDS");
   static constexpr int LDS_MAIN = NSTAGE * STAGE_BYTES;
-  static constexpr int EPI_LD = WN + 4;
+  static constexpr int EPI_LD = WN + 8;   // 4 rows apart = 32 banks apart: the two lane halves of a staging write do not collide
   static constexpr int LDS_EPI = WAVES * 32 * EPI_LD * 4;
   static constexpr int LDS_BYTES = LDS_MAIN > LDS_EPI ? LDS_MAIN : LDS_EPI;
   static_assert(A_BYTES % (1024 * WAVES) == 0 && B_BYTES % (1024 * WAVES) == 0, "slab must split into whole wave loads");
