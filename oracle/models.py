@@ -3,6 +3,7 @@
 Two families: a ReLU MLP (zero hidden layers = multinomial logistic regression) and a post-LN
 transformer encoder classifier (the BERT/RoBERTa-shaped base learners of Sec. 4.1).  Both expose
     losses(theta, x, y)            -> l[B]            per-sample CE, l_i = logsumexp(z_i) - z_i[y_i]
+                                                      (y may also be soft targets [B, C]: l_i = -sum_k y_ik log p_ik)
     loss_grad(theta, x, y, coef)   -> (l[B], d/dtheta sum_i coef_i l_i)
 theta is one flat vector.  Layout (the interface of the C library, restated here independently):
 every weight matrix ([out x in], row-major) in layer order, then every other tensor in layer order.
@@ -12,16 +13,25 @@ from scipy.special import erf
 
 
 def _ce(logits, y):
+    """Per-sample cross-entropy against integer labels y[B], or against soft targets y[B, C] (rows summing to 1):
+    l_i = -sum_k y_ik log softmax(z_i)_k = logsumexp(z_i) - y_i . z_i."""
     zmax = logits.max(axis=1, keepdims=True)
     lse = np.log(np.exp(logits - zmax).sum(axis=1)) + zmax[:, 0]
+    y = np.asarray(y)
+    if y.ndim == 2:
+        return lse - (y * logits).sum(axis=1)
     return lse - logits[np.arange(len(y)), y]
 
 
 def _dce(logits, y, coef):
-    """d/dlogits of sum_i coef_i l_i = coef_i (softmax(z_i) - onehot(y_i))."""
+    """d/dlogits of sum_i coef_i l_i = coef_i (softmax(z_i) - target_i), target = onehot(y_i) or the soft row y_i."""
     p = np.exp(logits - logits.max(axis=1, keepdims=True))
     p /= p.sum(axis=1, keepdims=True)
-    p[np.arange(len(y)), y] -= 1.0
+    y = np.asarray(y)
+    if y.ndim == 2:
+        p -= y
+    else:
+        p[np.arange(len(y)), y] -= 1.0
     return p * coef[:, None]
 
 

@@ -7,7 +7,7 @@ one `unroll` of base steps followed by one meta step (Sec. 2, Sec. 3.2).  Float6
 Readings where the paper is silent are marked "reading:" below.
 """
 import numpy as np
-from . import optim, sama_core, wnet
+from . import corrector, optim, sama_core, wnet
 
 SGD, ADAM = 0, 1
 
@@ -15,7 +15,7 @@ SGD, ADAM = 0, 1
 class SamaOracle:
     def __init__(self, model, theta0, lambda0, *, base_opt=ADAM, base_lr=1e-3, beta1=0.9, beta2=0.999,
                  adam_eps=1e-8, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999, meta_eps=1e-8,
-                 alpha=1.0, adapt_mode=optim.ADAPT_ADAM):
+                 alpha=1.0, adapt_mode=optim.ADAPT_ADAM, corr_hidden=0, corr_kappa=4.0, n_classes=None):
         self.model = model
         self.theta = np.array(theta0, dtype=np.float64)
         self.lam = np.array(lambda0, dtype=np.float64)
@@ -28,6 +28,16 @@ class SamaOracle:
         self.meta_lr, self.meta_beta1, self.meta_beta2, self.meta_eps = meta_lr, meta_beta1, meta_beta2, meta_eps
         self.alpha, self.adapt_mode = alpha, adapt_mode
         self.status = 0                # 1 after a meta step skipped for ||v|| = 0 / non-finite
+        # label correction (Sec. 4.1): lambda = [lambda_r | lambda_c]; corr_hidden = 0 turns it off
+        self.Hc, self.kappa, self.C = int(corr_hidden), float(corr_kappa), n_classes
+        if self.Hc > 0:
+            if n_classes is None:
+                raise ValueError("label correction needs n_classes")
+            self.nr = self.lam.size - corrector.size(n_classes, self.Hc)
+            if self.nr < 4 or (self.nr - 1) % 3 != 0:
+                raise ValueError("lambda0 must hold [weight net | corrector]")
+        else:
+            self.nr = self.lam.size
 
     # ------------------------------------------------------------------ base level
     def base_step(self, x, y, mask=None):
@@ -35,10 +45,11 @@ class SamaOracle:
         (reading: no gradient through the weight net's input, the Meta-Weight-Net convention);
         normalisation is 1/B_eff, B_eff = sum mask (reading of 1/|D_noisy|).  Returns L_base."""
         mask = np.ones(len(y)) if mask is None else np.asarray(mask, dtype=np.float64)
-        l = self.model.losses(self.theta, x, y)
-        w = wnet.weights(l, self.lam)
+        target = self.targets(self.theta, x, y)
+        l = self.model.losses(self.theta, x, target)
+        w = wnet.weights(l, self.lam[:self.nr])
         coef = mask * w / mask.sum()
-        l, g = self.model.loss_grad(self.theta, x, y, coef)
+        l, g = self.model.loss_grad(self.theta, x, target, coef)
         self.g = g
         self.t += 1
         if self.base_opt == ADAM:
@@ -60,10 +71,35 @@ class SamaOracle:
                                          self.adam_eps)
         return optim.sgd_adaptation(self.g, self.base_lr)
 
+    def targets(self, theta, x, y):
+        """What the base loss compares the prediction with: the labels themselves, or the corrected soft labels
+        c(x, y; lambda_c) of the label-correction meta learner (constants of every theta-gradient)."""
+        if self.Hc == 0:
+            return y
+        p = corrector.softmax(self.model.logits(theta, x))
+        return corrector.forward(self.lam[self.nr:], np.asarray(y), p, self.Hc, self.kappa)[0]
+
     def glam(self, theta, x, y, mask=None):
-        """dL_base(theta, lambda)/dlambda: a forward pass for l_i(theta), then the weight net's backward."""
-        l = self.model.losses(theta, x, y)
-        return wnet.base_loss_grad_lambda(l, self.lam, mask)
+        """dL_base(theta, lambda)/dlambda: a forward pass for l_i(theta), then the weight net's backward and, with label
+        correction, the corrector's backward.  reading: the weight net's input l_i and the corrector's input
+        softmax(z_i) are constants (the same stop-gradients as in the base step), so
+            d/dlambda_r = (1/B_eff) sum_i mask_i l_i dw_i/dlambda_r,
+            d/dlambda_c = (1/B_eff) sum_i mask_i w_i sum_k (-log p_ik) dc_ik/dlambda_c."""
+        if self.Hc == 0:
+            l = self.model.losses(theta, x, y)
+            return wnet.base_loss_grad_lambda(l, self.lam, mask)
+        mk = np.ones(len(y)) if mask is None else np.asarray(mask, dtype=np.float64)
+        z = self.model.logits(theta, x)
+        p = corrector.softmax(z)
+        logp = z - z.max(axis=1, keepdims=True)
+        logp = logp - np.log(np.exp(logp).sum(axis=1, keepdims=True))
+        c, cache = corrector.forward(self.lam[self.nr:], np.asarray(y), p, self.Hc, self.kappa)
+        l = -(c * logp).sum(axis=1)
+        g_r = wnet.base_loss_grad_lambda(l, self.lam[:self.nr], mask)
+        w = wnet.weights(l, self.lam[:self.nr])
+        dc = (mk * w / mk.sum())[:, None] * (-logp)
+        g_c = corrector.backward(self.lam[self.nr:], cache, dc, self.Hc)
+        return np.concatenate([g_r, g_c])
 
     def meta_grad(self, xt, yt, xm, ym, mask_t=None, mask_m=None):
         """Eq. 5 on the current state; changes nothing.  Returns dict(h, eps, v, g_meta, glam_p, glam_m).
