@@ -124,12 +124,14 @@ def test_label_correction_moves_both_lambda_groups_and_changes_the_base_gradient
         e = np.zeros(model.n); e[k] = 1e-6
         assert abs((S(th + e) - S(th - e)) / 2e-6 - corr.g[k]) < 1e-7 * (1 + abs(corr.g[k]))
     corr.base_step(x, y)
+    # Eq. 5 for the whole lambda: the central difference of glam along v, taken on the untouched state
+    r0 = corr.meta_grad(x, y, xm, ym)
+    gp = corr.glam(corr.theta + r0["eps"] * r0["v"], x, y); gm = corr.glam(corr.theta - r0["eps"] * r0["v"], x, y)
+    assert np.allclose(r0["h"], -(gp - gm) / (2 * r0["eps"]), rtol=1e-12, atol=0)
     lam_before = corr.lam.copy()
     r = corr.meta_step(x, y, xm, ym)
     nr = len(lam_r)
+    assert np.array_equal(r["h"], r0["h"])
     assert np.all(np.isfinite(r["h"])) and np.linalg.norm(r["h"][:nr]) > 0 and np.linalg.norm(r["h"][nr:]) > 0
     moved = corr.lam != lam_before                             # dead ReLU units keep their parameters
     assert moved[:nr].sum() > nr // 2 and moved[nr:].sum() > (len(moved) - nr) // 2
-    # Eq. 5 for the whole lambda: the central difference of glam along v
-    gp = corr.glam(corr.theta + 2 * r["eps"] * r["v"], x, y); gm = corr.glam(corr.theta, x, y)   # theta was nudged by -eps v
-    assert np.allclose(r["h"], -(gp - gm) / (2 * r["eps"]), rtol=1e-9, atol=1e-14)
