@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--workload", type=int, default=5, help="BASELINE.json config number 1..5")
     ap.add_argument("--unroll", type=int, default=1)
     ap.add_argument("--fast-meta-pass", type=int, default=0)
+    ap.add_argument("--corr-hidden", type=int, default=0,
+                    help="label correction (Sec. 4.1) with a corrector of this hidden width; 0 = the headline data-reweighting workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -55,7 +57,7 @@ def main():
 
     import numpy as np
     import torch
-    from datagen import make_workload, init_theta, init_lambda
+    from datagen import make_workload, init_theta, init_lambda, init_lambda_corr
     import paper_2310_05674_amd as pkg
 
     dev = torch.device("cuda:0")
@@ -66,9 +68,11 @@ def main():
     wl = make_workload(cfg_id, n_train=min(wl0.batch * nb, 12800) if cfg_id != 1 else None,
                        n_meta=min(wl0.meta_batch * nb, 1280) if cfg_id != 1 else None)
     th0, lam0 = init_theta(wl), init_lambda(wl)
+    if args.corr_hidden > 0:
+        lam0 = np.concatenate([lam0, init_lambda_corr(wl, args.corr_hidden)])
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch,
                               base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
-                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass)
+                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass, corr_hidden=args.corr_hidden)
     s = pkg.Sama(cfg, th0, lam0)
     n, n16 = s.n, s.lib.sama_gemm_param_count(__import__("ctypes").byref(cfg))
     batches = []
@@ -107,7 +111,7 @@ def main():
                    ("MLP " + "-".join(map(str, wl.dims)) if wl.kind == "mlp" else
                     "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
                    "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
-                   "wnet_hidden": wl.H, "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
+                   "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
                    "last_step_skipped": bool(skipped),
                    "workspace_bytes": int(s.lib.sama_workspace_bytes(__import__("ctypes").byref(cfg)))},
     }
@@ -165,7 +169,8 @@ def main():
         cb = {1: wl.batch, 2: wl.batch, 3: 8, 4: 2, 5: 1}[cfg_id]       # samples per batch in the CPU sample
         cm = min(cb, wl.meta_batch)
         orc = SamaOracle(models.make_model(wl.kind, wl.dims), th0, lam0, base_lr=wl.base_lr, meta_lr=wl.meta_lr,
-                         alpha=wl.alpha)
+                         alpha=wl.alpha, corr_hidden=args.corr_hidden,
+                         n_classes=wl.dims[-1] if args.corr_hidden > 0 else None)
         it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
         x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
         orc.base_step(x, y)                                               # history (untimed)

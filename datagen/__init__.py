@@ -6,5 +6,5 @@ parameters / batches, and bit-level helpers (bf16 rounding of *inputs*).
 """
 from .rng import CounterRNG, mix64
 from .workloads import (WORKLOADS, Workload, make_workload, param_count,
-                        param_layout, init_theta, init_lambda, round_to_bf16,
+                        param_layout, init_theta, init_lambda, init_lambda_corr, round_to_bf16,
                         flip_labels)

@@ -12,7 +12,7 @@ BASE_SEED = 20231005
 
 # stream numbers (one namespace per workload seed)
 S_X, S_TEACHER, S_FLIP_PERM, S_FLIP_LABEL, S_XMETA, S_MEANS, S_CLASS, S_CLASS_META = 1, 2, 3, 4, 5, 6, 7, 8
-S_TOK, S_TOK_META, S_THETA, S_LAMBDA, S_EPOCH_PERM = 9, 10, 11, 12, 1000
+S_TOK, S_TOK_META, S_THETA, S_LAMBDA, S_LAMBDA_CORR, S_EPOCH_PERM = 9, 10, 11, 12, 13, 1000
 
 
 @dataclass
@@ -157,6 +157,17 @@ def init_lambda(wl):
     H = wl.H
     z = CounterRNG(wl.seed).normal(S_LAMBDA, 3 * H + 1)
     lam = np.concatenate([z[:H], z[H:2 * H], z[2 * H:3 * H] / np.sqrt(H), [0.0]])
+    return lam.astype(np.float32).astype(np.float64)
+
+
+def init_lambda_corr(wl, corr_hidden):
+    """Label-corrector parameters, flat [W1(Hc x 2C), b1(Hc), W2(C x Hc), b2(C)], float32-representable: small
+    random weights, first-layer biases positive so that most hidden units start active."""
+    C, Hc = wl.dims[-1], corr_hidden
+    n1, n2 = Hc * 2 * C, C * Hc
+    z = CounterRNG(wl.seed).normal(S_LAMBDA_CORR, n1 + Hc + n2 + C)
+    lam = np.concatenate([z[:n1] / np.sqrt(2 * C), 0.25 + 0.25 * np.abs(z[n1:n1 + Hc]),
+                          z[n1 + Hc:n1 + Hc + n2] / np.sqrt(Hc), 0.1 * z[n1 + Hc + n2:]])
     return lam.astype(np.float32).astype(np.float64)
 
 

@@ -30,7 +30,13 @@
  *         then per layer l: bqkv[3d], bo[d], ln1_g[d], ln1_b[d], b1[ffn], b2[d], ln2_g[d], ln2_b[d];
  *         then tok_emb[V x d], pos_emb[S x d], emb_ln_g[d], emb_ln_b[d], Wc[C x d], bc[C].
  *    sama_param_tensor() enumerates the same table.
- * lambda layout, flat fp32, n_lambda = 3H + 1:  W1[H], b1[H], W2[H], b2[1].
+ * lambda layout, flat fp32, n_lambda = sama_lambda_count():  the weighting net W1[H], b1[H], W2[H], b2[1]; then, when
+ *    label correction is on (corr_hidden = Hc > 0), the corrector  W1c[Hc x 2C], b1c[Hc], W2c[C x Hc], b2c[C].
+ *
+ * Label correction (the second meta learner of Sec. 4.1): the base loss of a noisy sample becomes the cross-entropy
+ * against a corrected soft label, l_i = -sum_k c_ik log softmax(z_i)_k.  The paper names the corrector only as a
+ * 2-layer MLP; here c_i = softmax(kappa onehot(y_i) + W2c relu(W1c [onehot(y_i), softmax(z_i)] + b1c) + b2c), with
+ * softmax(z_i) entering as a constant.  The meta batch keeps its hard labels.
  */
 #ifndef SAMA_H
 #define SAMA_H
@@ -78,6 +84,8 @@ typedef struct {
                              two-term split hi + lo of the fp32 master weights, so dL_meta/dtheta is taken at theta
                              and not at bf16(theta) (costs two extra forward-equivalents of GEMM work per meta
                              step).  1: that pass uses the bf16 working copy like a base step. */
+  int32_t corr_hidden;    /* Hc: hidden width of the label corrector, 0 = no label correction, at most 128; needs C <= 16 */
+  float corr_kappa;       /* kappa >= 0: fixed prior on the given label inside the corrector */
 } sama_config;
 
 /* One batch.  x: DEVICE, fp32 [n x d0] row-major (MLP) or int32 token ids [n x S] (ENCODER), ids in [0, V).

@@ -25,6 +25,8 @@ bool prof_read(int family, const char** name, int64_t* launches, double* total_m
 constexpr int EW_MAX_BLOCKS = 65536;  // grid cap of the elementwise kernels (also the size of the norm partials)
 constexpr int MAX_BATCH = 2048;
 constexpr int MAX_WNET_HIDDEN = 256;
+constexpr int MAX_CORR_HIDDEN = 128;   // label corrector: hidden width and number of classes it supports
+constexpr int MAX_CORR_CLASSES = 16;
 
 // ------------------------------------------------------------------ elementwise chain (elementwise.hip)
 struct AdamArgs {
@@ -69,12 +71,14 @@ struct SampleStageArgs {
   int ld, C, B, H, mode;
   const int32_t* y;
   const uint8_t* mask;  // may be null
-  const float* lambda;  // [3H+1]
+  const float* lambda;  // [3H+1] weighting net, then the corrector [Hc*2C + Hc + C*Hc + C] when Hc > 0
+  int Hc; float kappa;  // label corrector (BASE and GLAM): Hc = 0 turns it off
+  double* corr_scratch; // [B x 2C] device scratch of the corrector's backward (GLAM with Hc > 0)
   float* losses;        // [B] out
   float* dlogits;       // [B x C] out, row stride C (BASE, META)
   float* loss_scalar;   // out: sum_i coef_i l_i
   float* loss_user;     // optional second destination
-  double* glam;         // [3H+1] out (GLAM)
+  double* glam;         // [n_lambda] out (GLAM), same layout as lambda
 };
 void launch_sample_stage(hipStream_t, const SampleStageArgs&);
 struct MetaUpdateArgs {

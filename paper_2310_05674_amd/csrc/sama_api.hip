@@ -63,7 +63,7 @@ struct sama_ctx {
   float *theta, *m, *v, *g, *gmeta, *vdir;
   bf16_t *theta16, *lo_p, *lo_m;
   float *lambda, *meta_m, *meta_v, *hyper, *glam_p32, *glam_m32;
-  double *glam_p, *glam_m, *partial;
+  double *glam_p, *glam_m, *partial, *corr_scratch;
   float* scalars;     // {eps, ||v||, L_base, L_meta}
   int64_t* counters;  // {t (mirror), meta_t, status, 0}
   float *logits, *dlogits, *losses;
@@ -72,6 +72,11 @@ struct sama_ctx {
 };
 
 static thread_local std::string g_init_err;
+
+static int lambda_count(const sama_config& c) {
+  const int C = c.dims[c.n_dims - 1], Hc = c.corr_hidden;
+  return 3 * c.wnet_hidden + 1 + (Hc > 0 ? Hc * 2 * C + Hc + C * Hc + C : 0);
+}
 
 static bool validate(const sama_config* c, std::string& err) {
   if (!c) { err = "null config"; return false; }
@@ -90,6 +95,9 @@ static bool validate(const sama_config* c, std::string& err) {
         c->meta_beta1 < 1.f && c->meta_beta2 >= 0.f && c->meta_beta2 < 1.f)) { err = "betas must be in [0, 1)"; return false; }
   if (c->fast_meta_pass != 0 && c->fast_meta_pass != 1) { err = "fast_meta_pass must be 0 or 1"; return false; }
   if (c->adam_eps < 0.f || c->meta_eps < 0.f || c->weight_decay < 0.f) { err = "negative eps / weight_decay"; return false; }
+  if (c->corr_hidden < 0 || c->corr_hidden > MAX_CORR_HIDDEN) { err = "corr_hidden must be 0..128"; return false; }
+  if (c->corr_hidden > 0 && c->dims[c->n_dims - 1] > MAX_CORR_CLASSES) { err = "label correction supports at most 16 classes"; return false; }
+  if (c->corr_hidden > 0 && !(c->corr_kappa >= 0.f)) { err = "corr_kappa must be >= 0"; return false; }
   return true;
 }
 
@@ -113,6 +121,7 @@ static size_t carve(sama_ctx* c, void* base) {
   c->logits = ws.take<float>((size_t)2 * mb * C);   // room for the stacked + and - passes
   c->dlogits = ws.take<float>((size_t)mb * C);
   c->losses = ws.take<float>(mb);
+  c->corr_scratch = c->cfg.corr_hidden > 0 ? ws.take<double>((size_t)c->cfg.max_batch * 2 * C) : nullptr;
   if (c->model) c->model->plan(ws, mb);
   return ws.used();
 }
@@ -122,7 +131,7 @@ static sama_ctx* make_host_ctx(const sama_config* cfg, std::string& err) {
   std::unique_ptr<sama_ctx> c(new sama_ctx());
   c->cfg = *cfg;
   build_layout(*cfg, c->layout, c->n, c->n_gemm, err);
-  c->nl = 3 * cfg->wnet_hidden + 1;
+  c->nl = lambda_count(*cfg);
   c->bf16 = cfg->param_dtype == SAMA_DTYPE_BF16;
   if (cfg->model_kind == SAMA_MODEL_MLP) c->model.reset(make_mlp(*cfg, c->layout));
   else c->model.reset(make_encoder(*cfg, c->layout, err));
@@ -160,8 +169,9 @@ int64_t sama_gemm_param_count(const sama_config* cfg) {
   return ng;
 }
 int32_t sama_lambda_count(const sama_config* cfg) {
-  if (!cfg || cfg->wnet_hidden < 1 || cfg->wnet_hidden > MAX_WNET_HIDDEN) return 0;
-  return 3 * cfg->wnet_hidden + 1;
+  std::string err;
+  if (!validate(cfg, err)) return 0;
+  return lambda_count(*cfg);
 }
 int32_t sama_param_tensor_count(const sama_config* cfg) {
   std::string e; std::vector<TensorInfo> l; int64_t n, ng;
@@ -234,7 +244,7 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
   c->model->forward(st, w, *train, true, c->logits);
   SampleStageArgs sa{};
   sa.logits = c->logits; sa.ld = c->model->n_classes(); sa.C = sa.ld; sa.B = train->n; sa.H = c->cfg.wnet_hidden;
-  sa.mode = STAGE_BASE; sa.y = train->y; sa.mask = train->sample_mask; sa.lambda = c->lambda;
+  sa.mode = STAGE_BASE; sa.Hc = c->cfg.corr_hidden; sa.kappa = c->cfg.corr_kappa; sa.y = train->y; sa.mask = train->sample_mask; sa.lambda = c->lambda;
   sa.losses = c->losses; sa.dlogits = c->dlogits; sa.loss_scalar = c->scalars + 2; sa.loss_user = loss_out;
   launch_sample_stage(st, sa);
   c->model->backward(st, w, *train, c->dlogits, c->g);
@@ -300,7 +310,7 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
   c->model->forward_pair(st, pass_weights(c, 1.f), pass_weights(c, -1.f), *train, c->logits);
   for (int pass = 0; pass < 2; ++pass) {
     SampleStageArgs sg{};
-    sg.logits = c->logits + (size_t)pass * train->n * C; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM;
+    sg.logits = c->logits + (size_t)pass * train->n * C; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM; sg.Hc = f.corr_hidden; sg.kappa = f.corr_kappa; sg.corr_scratch = c->corr_scratch;
     sg.y = train->y; sg.mask = train->sample_mask; sg.lambda = c->lambda; sg.losses = c->losses;
     sg.glam = pass == 0 ? c->glam_p : c->glam_m;
     launch_sample_stage(st, sg);

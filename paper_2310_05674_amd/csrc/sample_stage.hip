@@ -2,6 +2,10 @@
 //   l_i = logsumexp(z_i) - z_i[y_i];  w_i = sigmoid(W2 . relu(W1 l_i + b1) + b2);  B_eff = sum mask
 //   BASE: coef_i = mask_i w_i / B_eff   META: coef_i = mask_i / B_eff   -> dz_i = coef_i (softmax(z_i) - e_{y_i})
 //   GLAM: dL_base/dlambda = (1/B_eff) sum_i mask_i l_i dw(l_i; lambda)/dlambda   (weight-net backward only)
+// With label correction (Sec. 4.1; Hc > 0) the BASE and GLAM modes compare the prediction with the corrected soft label
+//   c_i = softmax(kappa e_{y_i} + W2c relu(W1c [e_{y_i}, softmax(z_i)] + b1c) + b2c),  l_i = -sum_k c_ik log softmax(z_i)_k,
+//   BASE: dz_i = coef_i (softmax(z_i) - c_i)
+//   GLAM: additionally d/dlambda_c = sum_i coef_i sum_k (-log p_ik) dc_ik/dlambda_c  (corrector backward; its inputs are constants)
 // and the finite-difference combine + Adam step on lambda (Eq. 5, Table 4).
 // Batches are at most a few hundred samples: one workgroup, samples staged in LDS, every sum in a fixed order,
 // arithmetic in double so that the +-eps difference of Eq. 5 is not lost to rounding.
@@ -29,11 +33,16 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   __shared__ double s_dz[MAX_BATCH];   // per-sample dL/dz of the weight net (GLAM) or coef (BASE/META)
   __shared__ float s_lam[3 * MAX_WNET_HIDDEN + 1];
   __shared__ double red[256];
+  __shared__ float s_lc[MAX_CORR_HIDDEN * 2 * MAX_CORR_CLASSES + MAX_CORR_HIDDEN + MAX_CORR_CLASSES * MAX_CORR_HIDDEN + MAX_CORR_CLASSES];
   const int tid = threadIdx.x, H = a.H, B = a.B, C = a.C;
+  const int Hc = a.mode == STAGE_META ? 0 : a.Hc;      // the clean batch keeps its hard labels
   for (int i = tid; i < 3 * H + 1; i += 256) s_lam[i] = a.lambda[i];
+  const int nlc = Hc > 0 ? Hc * 2 * C + Hc + C * Hc + C : 0;
+  for (int i = tid; i < nlc; i += 256) s_lc[i] = a.lambda[3 * H + 1 + i];
   __syncthreads();
   const float* W1 = s_lam; const float* b1 = s_lam + H; const float* W2 = s_lam + 2 * H;
   const double b2 = (double)s_lam[3 * H];
+  const float* W1c = s_lc; const float* b1c = s_lc + Hc * 2 * C; const float* W2c = b1c + Hc; const float* b2c = W2c + C * Hc;
 
   double cnt = 0.0;
   for (int i = tid; i < B; i += 256) cnt += (a.mask == nullptr || a.mask[i] != 0) ? 1.0 : 0.0;
@@ -49,8 +58,27 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
     for (int c = 0; c < C; ++c) se += exp((double)z[c] - zmax);
     const double lse = log(se) + zmax;
     const int yi = a.y[i];
-    const double l = lse - (double)z[yi];
     const double mk = (a.mask == nullptr || a.mask[i] != 0) ? 1.0 : 0.0;
+    double l;
+    double cs[MAX_CORR_CLASSES];                       // corrected soft label (Hc > 0)
+    if (Hc > 0) {
+      double sc[MAX_CORR_CLASSES], pk[MAX_CORR_CLASSES];
+      for (int k = 0; k < C; ++k) { sc[k] = (double)b2c[k] + (k == yi ? (double)a.kappa : 0.0); pk[k] = exp((double)z[k] - lse); }
+      for (int j = 0; j < Hc; ++j) {
+        double aj = (double)b1c[j] + (double)W1c[j * 2 * C + yi];
+        for (int k = 0; k < C; ++k) aj += (double)W1c[j * 2 * C + C + k] * pk[k];
+        if (aj > 0.0)
+          for (int k = 0; k < C; ++k) sc[k] += (double)W2c[k * Hc + j] * aj;
+      }
+      double smax = sc[0];
+      for (int k = 1; k < C; ++k) smax = fmax(smax, sc[k]);
+      double ssum = 0.0;
+      for (int k = 0; k < C; ++k) { cs[k] = exp(sc[k] - smax); ssum += cs[k]; }
+      l = 0.0;
+      for (int k = 0; k < C; ++k) { cs[k] /= ssum; l -= cs[k] * ((double)z[k] - lse); }
+    } else {
+      l = lse - (double)z[yi];
+    }
     a.losses[i] = (float)l;
     s_l[i] = l;
     double w = 1.0;
@@ -61,12 +89,23 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
     }
     if (a.mode == STAGE_GLAM) {
       s_dz[i] = w * (1.0 - w) * l * mk * inv_beff;
+      if (Hc > 0) {
+        // ds_ik = c_ik (dc_ik - sum_k' c_ik' dc_ik'), dc_ik = -coef_i log p_ik; kept with p_i for the second phase
+        const double coef = mk * w * inv_beff;
+        double dot = 0.0;
+        for (int k = 0; k < C; ++k) dot += cs[k] * (-coef * ((double)z[k] - lse));
+        for (int k = 0; k < C; ++k) {
+          a.corr_scratch[(int64_t)i * 2 * C + k] = cs[k] * (-coef * ((double)z[k] - lse) - dot);
+          a.corr_scratch[(int64_t)i * 2 * C + C + k] = exp((double)z[k] - lse);
+        }
+      }
     } else {
       const double coef = mk * w * inv_beff;
       lsum += coef * l;
       for (int c = 0; c < C; ++c) {
         const double p = exp((double)z[c] - lse);
-        a.dlogits[(int64_t)i * C + c] = (float)(coef * (p - (c == yi ? 1.0 : 0.0)));
+        const double target = Hc > 0 ? cs[c] : (c == yi ? 1.0 : 0.0);
+        a.dlogits[(int64_t)i * C + c] = (float)(coef * (p - target));
       }
     }
   }
@@ -99,6 +138,41 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   for (int i = tid; i < B; i += 256) dsum += s_dz[i];
   const double db2 = block_sum_d(dsum, red);
   if (tid == 0) a.glam[3 * H] = db2;
+  if (Hc == 0) return;
+  // corrector backward: thread j owns hidden unit j (row j of W1c, b1c[j], column j of W2c) and walks the samples in
+  // order; threads Hc .. Hc + C - 1 own b2c.  The per-sample ds_i and p_i come back from the scratch written above
+  // (same block: the barrier inside block_sum_d orders the writes before these reads).
+  double* gc = a.glam + 3 * H + 1;
+  for (int j = tid; j < Hc + C; j += 256) {
+    if (j >= Hc) {
+      const int k = j - Hc;
+      double acc = 0.0;
+      for (int i = 0; i < B; ++i) acc += a.corr_scratch[(int64_t)i * 2 * C + k];
+      gc[Hc * 2 * C + Hc + C * Hc + k] = acc;
+      continue;
+    }
+    double dW1[2 * MAX_CORR_CLASSES], dW2[MAX_CORR_CLASSES];
+    for (int q = 0; q < 2 * C; ++q) dW1[q] = 0.0;
+    for (int k = 0; k < C; ++k) dW2[k] = 0.0;
+    double db1 = 0.0;
+    for (int i = 0; i < B; ++i) {
+      const double* ds = a.corr_scratch + (int64_t)i * 2 * C;
+      const double* p = ds + C;
+      const int yi = a.y[i];
+      double aj = (double)b1c[j] + (double)W1c[j * 2 * C + yi];
+      for (int k = 0; k < C; ++k) aj += (double)W1c[j * 2 * C + C + k] * p[k];
+      if (aj > 0.0) {
+        double t = 0.0;
+        for (int k = 0; k < C; ++k) { dW2[k] += ds[k] * aj; t += (double)W2c[k * Hc + j] * ds[k]; }
+        db1 += t;
+        dW1[yi] += t;
+        for (int k = 0; k < C; ++k) dW1[C + k] += t * p[k];
+      }
+    }
+    for (int q = 0; q < 2 * C; ++q) gc[j * 2 * C + q] = dW1[q];
+    gc[Hc * 2 * C + j] = db1;
+    for (int k = 0; k < C; ++k) gc[Hc * 2 * C + Hc + k * Hc + j] = dW2[k];
+  }
 }
 
 // h = -(glam+ - glam-) / (2 eps); then (optionally) Adam on lambda.  A raised status word (counters[2]) zeroes h

@@ -20,11 +20,12 @@ def make_pair(wl, theta0, lambda0, **over):
     kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps")})
     base_opt = over.get("base_opt", "adam")
     adapt = over.get("adapt_mode", 0)
+    corr = {k: over[k] for k in ("corr_hidden", "corr_kappa") if k in over}
     orc = SamaOracle(models.make_model(wl.kind, wl.dims), theta0, lambda0, base_opt=ADAM if base_opt == "adam" else SGD,
-                     adapt_mode=adapt, **kw)
+                     adapt_mode=adapt, n_classes=wl.dims[-1] if corr.get("corr_hidden") else None, **corr, **kw)
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=over.get("max_batch", wl.batch),
                               max_meta_batch=over.get("max_meta_batch", wl.meta_batch),
-                              base_opt=pkg.OPT_ADAM if base_opt == "adam" else pkg.OPT_SGD, adapt_mode=adapt, **kw)
+                              base_opt=pkg.OPT_ADAM if base_opt == "adam" else pkg.OPT_SGD, adapt_mode=adapt, **corr, **kw)
     gpu = pkg.Sama(cfg, theta0, lambda0)
     return orc, gpu
 

@@ -62,5 +62,15 @@ def test_bad_configs_rejected(lib):
                 pkg.SamaConfig.make("encoder", (2, 30, 4, 64, 128, 100, 3), **good)):
         assert lib.sama_workspace_bytes(C.byref(bad)) == 0
         assert lib.sama_last_error(None) != b""
+    # label correction: lambda grows by the corrector [Hc x 2C, Hc, C x Hc, C]; limits on Hc, C and kappa
+    cc = pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=5, corr_kappa=2.0, **good)
+    assert lib.sama_lambda_count(C.byref(cc)) == 3 * 16 + 1 + 5 * 6 + 5 + 3 * 5 + 3
+    assert lib.sama_workspace_bytes(C.byref(cc)) > lib.sama_workspace_bytes(C.byref(c))
+    for bad in (pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=129, **good), pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=-1, **good),
+                pkg.SamaConfig.make("mlp", (4, 17), corr_hidden=4, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=4, corr_kappa=-1.0, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=4, corr_kappa=float("nan"), **good)):
+        assert lib.sama_lambda_count(C.byref(bad)) == 0
+        assert lib.sama_workspace_bytes(C.byref(bad)) == 0
     h = C.c_void_p()
     assert lib.sama_init(C.byref(c), None, 0, None, None, None, C.byref(h)) != 0
