@@ -13,6 +13,7 @@ BASE_SEED = 20231005
 # stream numbers (one namespace per workload seed)
 S_X, S_TEACHER, S_FLIP_PERM, S_FLIP_LABEL, S_XMETA, S_MEANS, S_CLASS, S_CLASS_META = 1, 2, 3, 4, 5, 6, 7, 8
 S_TOK, S_TOK_META, S_THETA, S_LAMBDA, S_LAMBDA_CORR, S_EPOCH_PERM = 9, 10, 11, 12, 13, 1000
+S_TOK_AUX, S_AUX_COUNT, S_AUX_PERM = 14, 15, 2000000
 
 
 @dataclass
@@ -34,6 +35,7 @@ class Workload:
     beta1: float = 0.9
     beta2: float = 0.999
     adam_eps: float = 1e-8
+    mlm: bool = False              # encoder with a masked-token head (auxiliary-task reweighting)
     # filled by make_workload
     x_train: np.ndarray = field(default=None, repr=False)
     y_train: np.ndarray = field(default=None, repr=False)      # noisy labels (int32)
@@ -86,10 +88,11 @@ WORKLOADS = {
 
 
 # ----------------------------------------------------------------------------- parameters
-def param_layout(kind, dims):
+def param_layout(kind, dims, mlm=False):
     """Flat layout of theta: list of (name, shape, offset).  Rule: every GEMM weight matrix
     (stored [out x in], row-major) in layer order first, then every remaining tensor in layer
-    order.  This restates the interface documented in include/sama.h; the oracle and the HIP
+    order.  mlm: the encoder carries a masked-token head, its decoder Wmlm [V x d] last among
+    the GEMM matrices and its bias bmlm [V] last of all.  This restates the interface documented in include/sama.h; the oracle and the HIP
     library each hold their own statement of it and tests compare the three."""
     mats, vecs = [], []
     if kind == "mlp":
@@ -106,6 +109,9 @@ def param_layout(kind, dims):
                      (f"l{l}.ln2_g", (d,)), (f"l{l}.ln2_b", (d,))]
         vecs += [("tok_emb", (V, d)), ("pos_emb", (S, d)), ("emb_ln_g", (d,)), ("emb_ln_b", (d,)),
                  ("Wc", (C, d)), ("bc", (C,))]
+        if mlm:
+            mats.append(("Wmlm", (V, d)))
+            vecs.append(("bmlm", (V,)))
     else:
         raise ValueError(kind)
     out, off = [], 0
@@ -115,8 +121,8 @@ def param_layout(kind, dims):
     return out
 
 
-def param_count(kind, dims):
-    name, shape, off = param_layout(kind, dims)[-1]
+def param_count(kind, dims, mlm=False):
+    name, shape, off = param_layout(kind, dims, mlm)[-1]
     return off + int(np.prod(shape))
 
 
@@ -133,8 +139,8 @@ def init_theta(wl, scale=0.02):
     """Initial base parameters (float64 array holding float32- or bf16-representable values).
     `scale` is the std of the encoder's matrices and embeddings."""
     rng = CounterRNG(wl.seed)
-    lay = param_layout(wl.kind, wl.dims)
-    n = param_count(wl.kind, wl.dims)
+    lay = param_layout(wl.kind, wl.dims, wl.mlm)
+    n = param_count(wl.kind, wl.dims, wl.mlm)
     z = rng.normal(S_THETA, n)
     th = np.zeros(n, dtype=np.float64)
     for name, shape, off in lay:
@@ -195,6 +201,25 @@ def _zipf_tokens(rng, stream, n_seq, S, V, a=1.1):
     ids = np.minimum(np.searchsorted(cdf, u, side="right") + 1, V - 1).astype(np.int32).reshape(n_seq, S)
     ids[:, 0] = 0
     return ids
+
+
+def make_aux_batch(wl, step, n_pt, lo=0.10, hi=0.20):
+    """Masked-token batch `step` of the auxiliary task of an encoder workload: n_pt sequences of the token recipe
+    (own stream), in each a seeded choice of between lo*S and hi*S positions (never position 0) whose ids are replaced
+    by the mask id V-1 in the input and kept as targets.  Returns (ids [n_pt, S] int32, seq [n_mask] int32,
+    pos [n_mask] int32, tgt [n_mask] int32) with (seq, pos) ascending."""
+    L, d, heads, ffn, S, V, C = wl.dims
+    rng = CounterRNG(wl.seed + 7919 * (step + 1))
+    ids = _zipf_tokens(rng, S_TOK_AUX, n_pt, S, V)
+    k = np.floor(S * (lo + (hi - lo) * rng.uniform(S_AUX_COUNT, n_pt))).astype(np.int64).clip(1, S - 1)
+    seq, pos = [], []
+    for i in range(n_pt):
+        p = np.sort(1 + rng.permutation(S_AUX_PERM + i, S - 1)[:k[i]])
+        seq.append(np.full(len(p), i)); pos.append(p)
+    seq, pos = np.concatenate(seq).astype(np.int32), np.concatenate(pos).astype(np.int32)
+    tgt = ids[seq, pos].astype(np.int32)
+    ids[seq, pos] = V - 1
+    return ids, seq, pos, tgt
 
 
 def make_workload(cfg, n_train=None, n_meta=None, **override):

@@ -108,11 +108,14 @@ def _dgelu(a):
 
 class Encoder:
     """Post-LN encoder: x0 = LN(tok[ids] + pos); per layer x <- LN1(x + Attn(x)), x <- LN2(x + FFN(x));
-    logits = x_L[:, 0] Wc^T + bc.  erf-GELU, LN eps 1e-5, softmax(q k^T / sqrt(d_h)), no masks."""
+    logits = x_L[:, 0] Wc^T + bc.  erf-GELU, LN eps 1e-5, softmax(q k^T / sqrt(d_h)), no masks.
+    mlm=True adds the masked-token head of the auxiliary task (Sec. 4.3): token logits x_L[b, s] Wmlm^T + bmlm at the
+    masked positions (reading: an untied linear decoder on the last LayerNorm's output)."""
     LN_EPS = 1e-5
 
-    def __init__(self, L, d, heads, ffn, S, V, C):
+    def __init__(self, L, d, heads, ffn, S, V, C, mlm=False):
         self.L, self.d, self.heads, self.ffn, self.S, self.V, self.C = L, d, heads, ffn, S, V, C
+        self.mlm = bool(mlm)
         self.slices = {}
         off = 0
 
@@ -123,6 +126,8 @@ class Encoder:
         for l in range(L):
             add(f"l{l}.Wqkv", (3 * d, d)); add(f"l{l}.Wo", (d, d))
             add(f"l{l}.W1", (ffn, d)); add(f"l{l}.W2", (d, ffn))
+        if mlm:
+            add("Wmlm", (V, d))
         for l in range(L):
             add(f"l{l}.bqkv", (3 * d,)); add(f"l{l}.bo", (d,))
             add(f"l{l}.ln1_g", (d,)); add(f"l{l}.ln1_b", (d,))
@@ -131,6 +136,8 @@ class Encoder:
         add("tok_emb", (V, d)); add("pos_emb", (S, d))
         add("emb_ln_g", (d,)); add("emb_ln_b", (d,))
         add("Wc", (C, d)); add("bc", (C,))
+        if mlm:
+            add("bmlm", (V,))
         self.n = off
 
     def get(self, theta, name):
@@ -169,7 +176,22 @@ class Encoder:
     def losses(self, theta, ids, y):
         return _ce(self.logits(theta, ids), y)
 
+    def mlm_logits(self, xL, theta, seq, pos):
+        return xL[seq, pos, :] @ self.get(theta, "Wmlm").T + self.get(theta, "bmlm")
+
+    def mlm_losses(self, theta, ids, seq, pos, tgt):
+        """Cross-entropy over the vocabulary at each masked position (seq[j], pos[j]) against tgt[j]."""
+        xL = self._forward(theta, np.asarray(ids), False)[1][2]
+        return _ce(self.mlm_logits(xL, theta, seq, pos), tgt)
+
     def loss_grad(self, theta, ids, y, coef):
+        """(l, g): l_i = CE(z_i, y_i), g = d/dtheta sum_i coef_i l_i."""
+        l, _, g = self.loss_grad_mlm(theta, ids, y, coef, None, None, None, None)
+        return l, g
+
+    def loss_grad_mlm(self, theta, ids, y, coef, seq, pos, tgt, coef_pos):
+        """(l, l_pos, g): classification losses l_i, masked-token losses l_pos_j, and
+        g = d/dtheta [sum_i coef_i l_i + sum_j coef_pos_j l_pos_j] from ONE forward/backward over `ids`."""
         ids = np.asarray(ids)
         P = lambda name: self.get(theta, name)
         g = np.zeros(self.n)
@@ -184,6 +206,14 @@ class Encoder:
         G("bc")[...] = dlog.sum(axis=0)
         dx = np.zeros((B, S, d))
         dx[:, 0, :] = dlog @ P("Wc")
+        l_pos = None
+        if seq is not None:
+            zt = self.mlm_logits(xL, theta, seq, pos)                      # [n_mask, V]
+            l_pos = _ce(zt, tgt)
+            dzt = _dce(zt, tgt, np.asarray(coef_pos, dtype=np.float64))
+            G("Wmlm")[...] = dzt.T @ xL[seq, pos, :]
+            G("bmlm")[...] = dzt.sum(axis=0)
+            np.add.at(dx, (seq, pos), dzt @ P("Wmlm"))
         for l_ in reversed(range(self.L)):
             p = f"l{l_}."
             x, q, k, v, pr, o, c1, x1, a, hgelu, c2 = cache[l_]
@@ -213,12 +243,12 @@ class Encoder:
         G("emb_ln_g")[...] = dg_; G("emb_ln_b")[...] = db_
         G("pos_emb")[:S] = demb.sum(axis=0)
         np.add.at(G("tok_emb"), ids.reshape(-1), demb.reshape(-1, d))
-        return l, g
+        return l, l_pos, g
 
 
-def make_model(kind, dims):
+def make_model(kind, dims, mlm=False):
     if kind == "mlp":
         return MLP(dims)
     if kind == "encoder":
-        return Encoder(*dims)
+        return Encoder(*dims, mlm=mlm)
     raise ValueError(kind)
