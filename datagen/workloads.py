@@ -92,7 +92,7 @@ def param_layout(kind, dims, mlm=False):
     """Flat layout of theta: list of (name, shape, offset).  Rule: every GEMM weight matrix
     (stored [out x in], row-major) in layer order first, then every remaining tensor in layer
     order.  mlm: the encoder carries a masked-token head, its decoder Wmlm [V x d] last among
-    the GEMM matrices and its bias bmlm [V] last of all.  This restates the interface documented in include/sama.h; the oracle and the HIP
+    the GEMM matrices and its bias bmlm [V] just before the classifier head (Wc, bc).  This restates the interface documented in include/sama.h; the oracle and the HIP
     library each hold their own statement of it and tests compare the three."""
     mats, vecs = [], []
     if kind == "mlp":
@@ -107,11 +107,11 @@ def param_layout(kind, dims, mlm=False):
             vecs += [(f"l{l}.bqkv", (3 * d,)), (f"l{l}.bo", (d,)), (f"l{l}.ln1_g", (d,)),
                      (f"l{l}.ln1_b", (d,)), (f"l{l}.b1", (ffn,)), (f"l{l}.b2", (d,)),
                      (f"l{l}.ln2_g", (d,)), (f"l{l}.ln2_b", (d,))]
-        vecs += [("tok_emb", (V, d)), ("pos_emb", (S, d)), ("emb_ln_g", (d,)), ("emb_ln_b", (d,)),
-                 ("Wc", (C, d)), ("bc", (C,))]
+        vecs += [("tok_emb", (V, d)), ("pos_emb", (S, d)), ("emb_ln_g", (d,)), ("emb_ln_b", (d,))]
         if mlm:
             mats.append(("Wmlm", (V, d)))
             vecs.append(("bmlm", (V,)))
+        vecs += [("Wc", (C, d)), ("bc", (C,))]
     else:
         raise ValueError(kind)
     out, off = [], 0

@@ -29,6 +29,8 @@
  *                      Wo[d x d], W1[ffn x d], W2[d x ffn];
  *         then per layer l: bqkv[3d], bo[d], ln1_g[d], ln1_b[d], b1[ffn], b2[d], ln2_g[d], ln2_b[d];
  *         then tok_emb[V x d], pos_emb[S x d], emb_ln_g[d], emb_ln_b[d], Wc[C x d], bc[C].
+ *         With aux_mlm = 1 (masked-token head, token logits = x_L[row] Wmlm^T + bmlm): Wmlm[V x d] follows the last
+ *         layer's W2 among the matrices and bmlm[V] sits between emb_ln_b and Wc.
  *    sama_param_tensor() enumerates the same table.
  * lambda layout, flat fp32, n_lambda = sama_lambda_count():  the weighting net W1[H], b1[H], W2[H], b2[1]; then, when
  *    label correction is on (corr_hidden = Hc > 0), the corrector  W1c[Hc x 2C], b1c[Hc], W2c[C x Hc], b2c[C].
@@ -86,6 +88,12 @@ typedef struct {
                              step).  1: that pass uses the bf16 working copy like a base step. */
   int32_t corr_hidden;    /* Hc: hidden width of the label corrector, 0 = no label correction, at most 128; needs C <= 16 */
   float corr_kappa;       /* kappa >= 0: fixed prior on the given label inside the corrector */
+  int32_t aux_mlm;        /* 1: auxiliary-task reweighting (Sec. 4.3).  ENCODER only; theta gains a masked-token head
+                             (Wmlm [V x d] after the layers' matrices, bmlm [V] before Wc); V must be a multiple of 64;
+                             cannot be combined with corr_hidden > 0.  The sama_aux_* entry points need it. */
+  int32_t max_aux_batch;  /* aux_mlm: largest number of auxiliary sequences per batch; (max_batch + max_aux_batch) * S
+                             and max_meta_batch * S must stay within the encoder's 4096-token limit */
+  int32_t max_aux_masked; /* aux_mlm: largest number of masked positions per auxiliary batch, 1..max_aux_batch * S */
 } sama_config;
 
 /* One batch.  x: DEVICE, fp32 [n x d0] row-major (MLP) or int32 token ids [n x S] (ENCODER), ids in [0, V).
@@ -98,13 +106,25 @@ typedef struct {
   int32_t n;
 } sama_batch;
 
+/* One batch of the auxiliary (masked-token) task.  ids: DEVICE int32 [n_seq x S], the input tokens with the masked
+ * positions already replaced by the caller.  mask_row: DEVICE int32 [n_mask], token row sequence * S + position of
+ * each masked position, all distinct, every sequence owning at least one; mask_tgt: DEVICE int32 [n_mask], the token
+ * to predict there.  Out-of-range rows / targets are clamped into range, not reported.  Read-only; caller-owned. */
+typedef struct {
+  const int32_t* ids;
+  const int32_t* mask_row;
+  const int32_t* mask_tgt;
+  int32_t n_seq, n_mask;
+} sama_aux_batch;
+
 /* Selectors of sama_get_state / sama_set_state.  Sizes in elements:
  * THETA, M, V, G, GMETA, VDIR: n fp32 (M, V = Adam moments m, v of App. C; G = g_base of the last base step,
  * Eq. 4; GMETA = dL_meta/dtheta, Eq. 1; VDIR = the perturbation vector v of Eq. 5);
  * LAMBDA, META_M, META_V, HYPERGRAD, GLAM_PLUS, GLAM_MINUS: n_lambda fp32;
  * COUNTERS: 4 int64 = {base step count t, meta step count, status word (0 ok, 1 = last meta step skipped), 0};
  * SCALARS: 4 fp32 = {eps of the last meta gradient, ||v||_2, L_base of the last base step, L_meta of the last meta pass};
- * LOSSES: max(max_batch, max_meta_batch) fp32, per-sample losses of the most recent forward pass. */
+ * LOSSES: max(max_batch (+ max_aux_batch with aux_mlm), max_meta_batch) fp32, per-sample losses of the most recent
+ * forward pass. */
 enum {
   SAMA_STATE_THETA = 0, SAMA_STATE_LAMBDA = 1, SAMA_STATE_M = 2, SAMA_STATE_V = 3, SAMA_STATE_G = 4,
   SAMA_STATE_GMETA = 5, SAMA_STATE_VDIR = 6, SAMA_STATE_META_M = 7, SAMA_STATE_META_V = 8,
@@ -147,6 +167,21 @@ sama_status sama_meta_grad(sama_ctx* ctx, const sama_batch* train, const sama_ba
 /* sama_meta_grad, then one Adam step on lambda with h (Table 4), then theta <- theta - eps v (end of
  * Sec. 3.2).  The base moments and step count are not touched. */
 sama_status sama_meta_step(sama_ctx* ctx, const sama_batch* train, const sama_batch* meta);
+
+/* Auxiliary-task reweighting (Sec. 4.3): L_base = L_ft(ft) + (1/n_seq) sum_x w(L_pt(x); lambda) L_pt(x) over the
+ * auxiliary sequences x, L_ft the mean classifier cross-entropy on `ft` (its sample_mask honoured), L_pt(x) the mean
+ * masked-token cross-entropy over x's masked positions, w the weight net on that loss (a constant of the backward
+ * pass).  One forward / backward over the concatenated batch, then the base solver's update as in sama_base_step.
+ * ft->n <= max_batch, pt->n_seq <= max_aux_batch, pt->n_mask <= max_aux_masked.  Afterwards LOSSES holds
+ * [classifier losses of ft | L_pt of the auxiliary sequences].  loss_out as in sama_base_step. */
+sama_status sama_aux_base_step(sama_ctx* ctx, const sama_batch* ft, const sama_aux_batch* pt, float* loss_out /*DEVICE*/);
+
+/* Eq. 5 for that problem: g_meta = dL_ft/dtheta on `meta`; v, eps as in sama_meta_grad; the two lambda-gradients are
+ * taken on `pt` alone (the finetuning term of L_base does not depend on lambda).  `pt` is the auxiliary batch of the
+ * last sama_aux_base_step.  sama_aux_meta_step then updates lambda and nudges theta like sama_meta_step. */
+sama_status sama_aux_meta_grad(sama_ctx* ctx, const sama_aux_batch* pt, const sama_batch* meta,
+                               float* hypergrad_out /*DEVICE*/, float* eps_out /*DEVICE*/);
+sama_status sama_aux_meta_step(sama_ctx* ctx, const sama_aux_batch* pt, const sama_batch* meta);
 
 /* Copy a state vector out of / into the context (DEVICE pointers; sizes above).  Enqueued on the context's
  * stream.  sama_set_state(COUNTERS) synchronises the stream (the base step count lives on the host);

@@ -135,9 +135,9 @@ class Encoder:
             add(f"l{l}.ln2_g", (d,)); add(f"l{l}.ln2_b", (d,))
         add("tok_emb", (V, d)); add("pos_emb", (S, d))
         add("emb_ln_g", (d,)); add("emb_ln_b", (d,))
-        add("Wc", (C, d)); add("bc", (C,))
         if mlm:
             add("bmlm", (V,))
+        add("Wc", (C, d)); add("bc", (C,))
         self.n = off
 
     def get(self, theta, name):

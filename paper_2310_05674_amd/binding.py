@@ -19,13 +19,14 @@ class SamaConfig(C.Structure):
                 ("weight_decay", C.c_float), ("meta_lr", C.c_float), ("meta_beta1", C.c_float),
                 ("meta_beta2", C.c_float), ("meta_eps", C.c_float), ("alpha", C.c_float),
                 ("adapt_mode", C.c_int32), ("max_batch", C.c_int32), ("max_meta_batch", C.c_int32),
-                ("fast_meta_pass", C.c_int32), ("corr_hidden", C.c_int32), ("corr_kappa", C.c_float)]
+                ("fast_meta_pass", C.c_int32), ("corr_hidden", C.c_int32), ("corr_kappa", C.c_float),
+                ("aux_mlm", C.c_int32), ("max_aux_batch", C.c_int32), ("max_aux_masked", C.c_int32)]
 
     @classmethod
     def make(cls, kind, dims, *, H, max_batch, max_meta_batch, base_opt=OPT_ADAM, base_lr=1e-3, beta1=0.9,
              beta2=0.999, adam_eps=1e-8, weight_decay=0.0, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999,
              meta_eps=1e-8, alpha=1.0, adapt_mode=ADAPT_OPTIMIZER, bf16=None, fast_meta_pass=0, corr_hidden=0,
-             corr_kappa=4.0):
+             corr_kappa=4.0, aux_mlm=0, max_aux_batch=0, max_aux_masked=0):
         c = cls()
         c.model_kind = MODEL_MLP if kind == "mlp" else MODEL_ENCODER
         c.n_dims = len(dims)
@@ -40,6 +41,7 @@ class SamaConfig(C.Structure):
         c.alpha, c.adapt_mode, c.max_batch, c.max_meta_batch = alpha, adapt_mode, max_batch, max_meta_batch
         c.fast_meta_pass = fast_meta_pass
         c.corr_hidden, c.corr_kappa = corr_hidden, corr_kappa
+        c.aux_mlm, c.max_aux_batch, c.max_aux_masked = aux_mlm, max_aux_batch, max_aux_masked
         return c
 
 
@@ -55,6 +57,10 @@ class SamaError(RuntimeError):
 
 def lib_path():
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libsama.so")
+
+
+class SamaAuxBatch(C.Structure):
+    _fields_ = [("ids", C.c_void_p), ("mask_row", C.c_void_p), ("mask_tgt", C.c_void_p), ("n_seq", C.c_int32), ("n_mask", C.c_int32)]
 
 
 _lib = None
@@ -81,6 +87,10 @@ def load_library():
     L.sama_base_step.restype = C.c_int; L.sama_base_step.argtypes = [C.c_void_p, bp, C.c_void_p]
     L.sama_meta_grad.restype = C.c_int; L.sama_meta_grad.argtypes = [C.c_void_p, bp, bp, C.c_void_p, C.c_void_p]
     L.sama_meta_step.restype = C.c_int; L.sama_meta_step.argtypes = [C.c_void_p, bp, bp]
+    ap = C.POINTER(SamaAuxBatch)
+    L.sama_aux_base_step.restype = C.c_int; L.sama_aux_base_step.argtypes = [C.c_void_p, bp, ap, C.c_void_p]
+    L.sama_aux_meta_grad.restype = C.c_int; L.sama_aux_meta_grad.argtypes = [C.c_void_p, ap, bp, C.c_void_p, C.c_void_p]
+    L.sama_aux_meta_step.restype = C.c_int; L.sama_aux_meta_step.argtypes = [C.c_void_p, ap, bp]
     L.sama_get_state.restype = C.c_int; L.sama_get_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.sama_set_state.restype = C.c_int; L.sama_set_state.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
     L.sama_profile_family_count.restype = C.c_int32; L.sama_profile_family_count.argtypes = []
@@ -144,7 +154,7 @@ class Sama:
             raise SamaError(rc, self.lib.sama_last_error(None).decode())
         self.h = h
         self._keep = [th, lam]
-        self.max_b = max(cfg.max_batch, cfg.max_meta_batch)
+        self.max_b = max(cfg.max_batch + (cfg.max_aux_batch if cfg.aux_mlm else 0), cfg.max_meta_batch)
 
     def _dev_f32(self, a, count):
         torch = self.torch
@@ -179,6 +189,28 @@ class Sama:
 
     def meta_step(self, train, meta):
         self._check(self.lib.sama_meta_step(self.h, C.byref(train), C.byref(meta)))
+
+    def aux_batch(self, ids, mask_row, mask_tgt):
+        """Device int32 tensors (ids [n_seq, S], mask_row [n_mask] = sequence * S + position, mask_tgt [n_mask]) ->
+        sama_aux_batch."""
+        torch = self.torch
+        for t in (ids, mask_row, mask_tgt):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == torch.int32
+        assert mask_row.numel() == mask_tgt.numel()
+        b = SamaAuxBatch(ids.data_ptr(), mask_row.data_ptr(), mask_tgt.data_ptr(), int(ids.shape[0]), int(mask_row.numel()))
+        b._keep = (ids, mask_row, mask_tgt)
+        return b
+
+    def aux_base_step(self, ft, pt, loss_out=None):
+        self._check(self.lib.sama_aux_base_step(self.h, C.byref(ft), C.byref(pt), None if loss_out is None else loss_out.data_ptr()))
+
+    def aux_meta_grad(self, pt, meta, hypergrad_out=None, eps_out=None):
+        self._check(self.lib.sama_aux_meta_grad(self.h, C.byref(pt), C.byref(meta),
+                                                None if hypergrad_out is None else hypergrad_out.data_ptr(),
+                                                None if eps_out is None else eps_out.data_ptr()))
+
+    def aux_meta_step(self, pt, meta):
+        self._check(self.lib.sama_aux_meta_step(self.h, C.byref(pt), C.byref(meta)))
 
     def get_state(self, name):
         torch = self.torch

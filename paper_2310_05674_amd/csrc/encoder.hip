@@ -20,8 +20,12 @@ class EncoderModel : public Model {
                       find(p + "ln1_g"), find(p + "ln1_b"), find(p + "b1"), find(p + "b2"), find(p + "ln2_g"), find(p + "ln2_b")});
     }
     tok_ = find("tok_emb"); pos_ = find("pos_emb"); eg_ = find("emb_ln_g"); eb_ = find("emb_ln_b"); wc_ = find("Wc"); bc_ = find("bc");
+    wm_ = find("Wmlm"); bm_ = find("bmlm");
+    P_ = wm_ >= 0 ? (c.max_aux_masked + 63) / 64 * 64 : 0;
   }
   int n_classes() const override { return C_; }
+  bool has_mlm() const override { return wm_ >= 0; }
+  int mlm_stride() const override { return P_; }
 
   void plan(BumpAlloc& ws, int max_b) override {
     const size_t M = (size_t)max_b * S_;
@@ -46,6 +50,11 @@ class EncoderModel : public Model {
     const size_t wide = (size_t)(3 * d_ > ffn_ ? 3 * d_ : ffn_);
     lnpart_[0] = ws.take<float>(nblk * 3 * d_); lnpart_[1] = ws.take<float>(nblk * 3 * d_);
     cspart_[0] = ws.take<float>(nrb * wide); cspart_[1] = ws.take<float>(nrb * wide);
+    if (has_mlm()) {   // masked-token head: P_ positions (a multiple of 64, zero rows beyond the batch's), two stacked passes
+      hm_ = ws.take<bf16_t>((size_t)2 * P_ * d_); zt_ = ws.take<float>((size_t)2 * P_ * V_); lse_pos_ = ws.take<float>((size_t)2 * P_);
+      dzt_ = ws.take<bf16_t>((size_t)P_ * V_); dhm_ = ws.take<float>((size_t)GEMM_MAX_BATCH * P_ * d_);
+      cs_mlm_ = ws.take<float>((size_t)((P_ + COLSUM_ROWS - 1) / COLSUM_ROWS) * V_);
+    }
   }
 
   // One linear layer of `nw` stacked passes (pass k owns rows [k M, (k + 1) M) of every activation): the same
@@ -119,6 +128,16 @@ class EncoderModel : public Model {
     run_forward(st, w, 2, b, false, logits);
   }
 
+  void mlm_forward(hipStream_t st, const PassWeights* w, int nw, int pass_rows, bool kept, const MlmBatch& mb,
+                   float* loss_pos) override {
+    const bf16_t* xl = kept ? X_[L_] : X_[L_ & 1];      // bf16 output of the last LayerNorm
+    launch_gather_rows(st, xl, pass_rows, mb.row_base, mb.rows_in_batch, mb.rows, mb.n_mask, P_, d_, nw, hm_);
+    GemmBf16Args g{};
+    g.C32 = zt_;
+    fwd_linear(st, w, nw, hm_, d_, wm_, V_, bm_, P_, g);
+    launch_mlm_ce(st, zt_, V_, P_, mb.tgt, mb.n_mask, nw, loss_pos, lse_pos_);
+  }
+
   // dW[N x K] = dY^T . X into `out`
   GemmBf16Args wgrad(const bf16_t* dY, int N, const bf16_t* X, int K, int M, float* out) const {
     GemmBf16Args g{};
@@ -137,12 +156,47 @@ class EncoderModel : public Model {
   }
 
   void backward(hipStream_t st, const PassWeights& w, const sama_batch& b, const float* dlogits, float* grad) override {
+    run_backward(st, w, b, dlogits, grad, nullptr, nullptr);
+  }
+  void backward_mlm(hipStream_t st, const PassWeights& w, const sama_batch& b, const float* dlogits, float* grad,
+                    const MlmBatch& mb, const float* coef_pos) override {
+    run_backward(st, w, b, dlogits, grad, &mb, coef_pos);
+  }
+
+  // The masked-token head's backward: dZ = coef (softmax - onehot) in bf16; the hidden-state gradient dZ . Wmlm has a
+  // small output and a vocabulary-long contraction, so it runs as up to GEMM_MAX_BATCH K-chunks in one launch whose
+  // partial results the scatter adds into the token rows of dx; then dWmlm = dZ^T . H and dbmlm = column sums of dZ.
+  void mlm_backward(hipStream_t st, const PassWeights& w, const MlmBatch& mb, const float* coef_pos, float* grad, float* dx) {
+    launch_mlm_dz(st, zt_, V_, mb.tgt, coef_pos, lse_pos_, mb.n_mask, P_, dzt_);
+    const int slabs = V_ / 64, np = slabs < GEMM_MAX_BATCH ? slabs : GEMM_MAX_BATCH;
+    GemmBf16Args g[GEMM_MAX_BATCH];
+    for (int k = 0; k < np; ++k) {
+      const int64_t k0 = (int64_t)(slabs * k / np) * 64, k1 = (int64_t)(slabs * (k + 1) / np) * 64;
+      g[k] = GemmBf16Args{};
+      g[k].A = dzt_ + k0; g[k].lda = V_; g[k].a_trans = 0;
+      g[k].B = w.hi + wm_ + k0 * d_; g[k].B2 = w.lo ? w.lo + wm_ + k0 * d_ : nullptr; g[k].ldb = d_; g[k].b_trans = 0;
+      g[k].M = P_; g[k].N = d_; g[k].K = (int)(k1 - k0); g[k].ldc = d_;
+      g[k].C32 = dhm_ + (int64_t)k * P_ * d_;
+    }
+    launch_gemm_bf16_batch(st, g, np);
+    launch_scatter_add_rows(st, dhm_, np, (int64_t)P_ * d_, mb.row_base, mb.rows_in_batch, mb.rows, mb.n_mask, d_, dx);
+    launch_gemm_bf16(st, wgrad(dzt_, V_, hm_, d_, P_, grad + wm_));
+    launch_colsum_bf16(st, dzt_, P_, V_, cs_mlm_, grad + bm_);
+  }
+
+  void run_backward(hipStream_t st, const PassWeights& w, const sama_batch& b, const float* dlogits, float* grad,
+                    const MlmBatch* mb, const float* coef_pos) {
     const int B = b.n, M = B * S_;
     const int nblk = (M + LN_BWD_ROWS - 1) / LN_BWD_ROWS;
     float* dx = dX_[0];
     float* dx_next = dX_[1];
     launch_fill_f32(st, dx, 0.f, (int64_t)M * d_);
     launch_head_bwd(st, res_[0], S_, d_, B, C_, w.theta, wc_, bc_, dlogits, grad, dx);
+    if (mb) mlm_backward(st, w, *mb, coef_pos, grad, dx);
+    else if (has_mlm()) {   // a loss without masked-token terms leaves the head's gradient at zero
+      launch_fill_f32(st, grad + wm_, 0.f, (int64_t)V_ * d_);
+      launch_fill_f32(st, grad + bm_, 0.f, V_);
+    }
     for (int l = L_ - 1; l >= 0; --l) {
       const LayerOff& o = off_[l];
       // The layer's four weight gradients, its two bias column sums and its four small reductions wait for the
@@ -194,7 +248,10 @@ class EncoderModel : public Model {
  private:
   int L_, d_, heads_, ffn_, S_, V_, C_;
   std::vector<LayerOff> off_;
-  int64_t tok_, pos_, eg_, eb_, wc_, bc_;
+  int64_t tok_, pos_, eg_, eb_, wc_, bc_, wm_, bm_;
+  int P_ = 0;   // masked-token head: padded maximum number of positions
+  bf16_t* hm_ = nullptr; float* zt_ = nullptr; float* lse_pos_ = nullptr; bf16_t* dzt_ = nullptr; float* dhm_ = nullptr;
+  float* cs_mlm_ = nullptr;
   std::vector<bf16_t*> X_, qkv_, ao_, x1_, fpre_, fact_;
   std::vector<float*> lse_, pre1_, mean1_, rstd1_, pre2_, mean2_, rstd2_;
   float *pre0_ = nullptr, *mean0_ = nullptr, *rstd0_ = nullptr;
@@ -211,8 +268,10 @@ Model* make_encoder(const sama_config& c, const std::vector<TensorInfo>& layout,
   if (d / heads != 64 || d % heads != 0) { err = "the attention kernels are built for head width d/heads = 64"; return nullptr; }
   if (d > LN_MAX_D) { err = "d must be <= 1024"; return nullptr; }
   if (ffn % 64 != 0) { err = "ffn must be a multiple of 64"; return nullptr; }
-  const int mb = c.max_batch > c.max_meta_batch ? c.max_batch : c.max_meta_batch;
-  if ((int64_t)mb * S > 4096) { err = "max batch * S must be <= 4096 tokens"; return nullptr; }
+  const int tb = c.max_batch + (c.aux_mlm ? c.max_aux_batch : 0);
+  const int mb = tb > c.max_meta_batch ? tb : c.max_meta_batch;
+  if ((int64_t)mb * S > 4096) { err = "max batch (+ max auxiliary batch) * S must be <= 4096 tokens"; return nullptr; }
+  if (c.aux_mlm && c.dims[5] % 64 != 0) { err = "the masked-token head needs a vocabulary size that is a multiple of 64"; return nullptr; }
   return new EncoderModel(c, layout);
 }
 

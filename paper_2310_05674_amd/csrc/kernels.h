@@ -9,7 +9,7 @@ namespace sama {
 // ------------------------------------------------------------------ optional per-launch timing (profile.hip)
 enum Family {
   F_GEMM_NT = 0, F_GEMM_NN, F_GEMM_TN, F_GEMM_NT_HILO, F_GEMM_NN_HILO, F_GEMM_F32, F_ATTN_FWD, F_ATTN_BWD, F_LN_FWD, F_LN_BWD, F_ADAM, F_ADAPT_NORM,
-  F_PERTURB, F_RESIDUAL, F_NUDGE, F_SAMPLE_STAGE, F_OTHER, F_COUNT
+  F_PERTURB, F_RESIDUAL, F_NUDGE, F_SAMPLE_STAGE, F_MLM_SOFTMAX, F_OTHER, F_COUNT
 };
 // While profiling is enabled every launcher brackets its kernel with two HIP events on the launch stream.
 // `units` = algorithmic flops (GEMM, attention) or algorithmic bytes (everything else) of that launch.
@@ -79,6 +79,11 @@ struct SampleStageArgs {
   float* loss_scalar;   // out: sum_i coef_i l_i
   float* loss_user;     // optional second destination
   double* glam;         // [n_lambda] out (GLAM), same layout as lambda
+  // Sequence mode (pos_loss != null; BASE or GLAM): sample i is sequence i of B, its loss the mean of pos_loss[j] over
+  // the positions with pos_row[j] / S == i (0 without any); logits, y, dlogits are unused.  BASE writes
+  // pos_coef[j] = mask_i w_i / (B_eff count_i) and ADDS sum_i coef_i l_i to *loss_scalar (and *loss_user).
+  const float* pos_loss; const int32_t* pos_row; int n_pos, S;
+  float* pos_coef;
 };
 void launch_sample_stage(hipStream_t, const SampleStageArgs&);
 struct MetaUpdateArgs {
@@ -183,5 +188,24 @@ void launch_head_bwd(hipStream_t, const float* x, int S, int d, int B, int C, co
 // embedding gradients from demb [B*S x d]: pos_emb rows summed over the batch; tok_emb rows summed over the
 // occurrences of each id in ascending position order (the tok_emb part of grad must be zero on entry)
 void launch_embedding_bwd(hipStream_t, const float* demb, const int32_t* ids, int B, int S, int d, float* g_tok, float* g_pos);
+
+
+// ------------------------------------------------------------------ masked-token head (mlm_head.hip)
+// ids_out = [ids_ft | ids_pt] ([n x S] token rows), y_out = [y_ft | 0], mask_out = [mask_ft (null = ones) | 0]
+void launch_aux_cat(hipStream_t, const int32_t* ids_ft, const int32_t* y_ft, const uint8_t* mask_ft, int n_ft,
+                    const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out, uint8_t* mask_out);
+// out[(k P + j)][:] = X[k pass_rows + row_base + rows[j]][:], j < n_mask, k < nw; rows n_mask..P-1 zero; rows[] is
+// clamped to [0, rows_in_batch)
+void launch_gather_rows(hipStream_t, const bf16_t* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
+                        int n_mask, int P, int d, int nw, bf16_t* out);
+// loss_pos[k P + j] = logsumexp(Z[k P + j][:V]) - Z[k P + j][tgt[j]], lse_pos likewise (V % 4 == 0)
+void launch_mlm_ce(hipStream_t, const float* Z, int V, int P, const int32_t* tgt, int n_mask, int nw, float* loss_pos,
+                   float* lse_pos);
+// dZ [P x V] bf16 = coef_pos[j] (softmax(Z[j]) - onehot(tgt[j])), zero rows from n_mask on
+void launch_mlm_dz(hipStream_t, const float* Z, int V, const int32_t* tgt, const float* coef_pos, const float* lse_pos,
+                   int n_mask, int P, bf16_t* dZ);
+// dx[row_base + rows[j]][:] += sum_{k < nparts} part[k * part_stride + j * d + :]; the rows must be distinct
+void launch_scatter_add_rows(hipStream_t, const float* part, int nparts, int64_t part_stride, int row_base, int rows_in_batch,
+                             const int32_t* rows, int n_mask, int d, float* dx);
 
 }  // namespace sama

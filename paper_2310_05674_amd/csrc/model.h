@@ -46,6 +46,15 @@ class BumpAlloc {  // carves 256-byte aligned pieces out of the caller's workspa
   size_t off_;
 };
 
+// Masked-token positions of an auxiliary-task batch (device arrays; values are clamped into range by the kernels).
+struct MlmBatch {
+  const int32_t* rows;  // [n_mask] token row (sequence * S + position) inside the auxiliary sequences, all distinct
+  const int32_t* tgt;   // [n_mask] target token ids
+  int n_mask;
+  int row_base;         // token row of the first auxiliary sequence within the batch the model ran on
+  int rows_in_batch;    // token rows of the auxiliary sequences (n_pt * S)
+};
+
 class Model {
  public:
   virtual ~Model() {}
@@ -62,6 +71,17 @@ class Model {
   // grad[n] = d/dtheta sum_i sum_c dlogits[i][c] z_ic, at the unperturbed theta of the last keep=true forward
   virtual void backward(hipStream_t st, const PassWeights& w, const sama_batch& b, const float* dlogits, float* grad) = 0;
   virtual int n_classes() const = 0;
+  // ---- masked-token head (models built with one)
+  virtual bool has_mlm() const { return false; }
+  virtual int mlm_stride() const { return 0; }   // positions per pass in loss_pos (the padded maximum)
+  // loss_pos[k * mlm_stride() + j] = masked-token loss of position j under pass k (k < nw) of the last forward
+  // (kept = true, nw = 1) or forward_pair (kept = false, nw = 2); pass_rows = token rows of one pass.
+  virtual void mlm_forward(hipStream_t, const PassWeights*, int /*nw*/, int /*pass_rows*/, bool /*kept*/, const MlmBatch&,
+                           float* /*loss_pos*/) {}
+  // backward() with the head's loss added: grad = d/dtheta [sum dlogits . z + sum_j coef_pos[j] loss_pos_j], after a
+  // kept forward and mlm_forward on the same batch
+  virtual void backward_mlm(hipStream_t, const PassWeights&, const sama_batch&, const float* /*dlogits*/, float* /*grad*/,
+                            const MlmBatch&, const float* /*coef_pos*/) {}
 };
 
 Model* make_mlp(const sama_config& cfg, const std::vector<TensorInfo>& layout);

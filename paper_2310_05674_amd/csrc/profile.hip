@@ -13,7 +13,7 @@ std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 const char* kNames[F_COUNT] = {"gemm_bf16_nt", "gemm_bf16_nn", "gemm_bf16_tn", "gemm_bf16_nt_hilo", "gemm_bf16_nn_hilo", "gemm_f32", "attention_fwd", "attention_bwd",
                                "layernorm_fwd", "layernorm_bwd", "adam", "adapt_norm", "perturb_lo", "residual_lo",
-                               "nudge", "sample_stage", "other"};
+                               "nudge", "sample_stage", "mlm_softmax", "other"};
 hipEvent_t take_event() {
   if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
   hipEvent_t e = nullptr;

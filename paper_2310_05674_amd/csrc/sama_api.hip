@@ -37,7 +37,9 @@ bool build_layout(const sama_config& c, std::vector<TensorInfo>& out, int64_t& n
       V(p + "bqkv", 3 * d, 1); V(p + "bo", d, 1); V(p + "ln1_g", d, 1); V(p + "ln1_b", d, 1);
       V(p + "b1", ffn, 1); V(p + "b2", d, 1); V(p + "ln2_g", d, 1); V(p + "ln2_b", d, 1);
     }
-    V("tok_emb", Vv, d); V("pos_emb", S, d); V("emb_ln_g", d, 1); V("emb_ln_b", d, 1); V("Wc", C, d); V("bc", C, 1);
+    V("tok_emb", Vv, d); V("pos_emb", S, d); V("emb_ln_g", d, 1); V("emb_ln_b", d, 1);
+    if (c.aux_mlm) { M("Wmlm", Vv, d); V("bmlm", Vv, 1); }   // masked-token head of the auxiliary task (bmlm 16-byte aligned)
+    V("Wc", C, d); V("bc", C, 1);
   } else {
     err = "unknown model_kind"; return false;
   }
@@ -67,11 +69,19 @@ struct sama_ctx {
   float* scalars;     // {eps, ||v||, L_base, L_meta}
   int64_t* counters;  // {t (mirror), meta_t, status, 0}
   float *logits, *dlogits, *losses;
+  // auxiliary task: concatenated [ft | pt] batch, per-position losses (two stacked passes) and coefficients
+  int32_t *ids_cat, *y_cat; uint8_t* mask_cat; float *loss_pos, *coef_pos;
   int64_t t;  // base step count (host)
   std::string err;
 };
 
 static thread_local std::string g_init_err;
+
+// largest number of samples / sequences one pass runs over
+static int max_rows(const sama_config& c) {
+  const int tb = c.max_batch + (c.aux_mlm ? c.max_aux_batch : 0);
+  return tb > c.max_meta_batch ? tb : c.max_meta_batch;
+}
 
 static int lambda_count(const sama_config& c) {
   const int C = c.dims[c.n_dims - 1], Hc = c.corr_hidden;
@@ -98,6 +108,15 @@ static bool validate(const sama_config* c, std::string& err) {
   if (c->corr_hidden < 0 || c->corr_hidden > MAX_CORR_HIDDEN) { err = "corr_hidden must be 0..128"; return false; }
   if (c->corr_hidden > 0 && c->dims[c->n_dims - 1] > MAX_CORR_CLASSES) { err = "label correction supports at most 16 classes"; return false; }
   if (c->corr_hidden > 0 && !(c->corr_kappa >= 0.f)) { err = "corr_kappa must be >= 0"; return false; }
+  if (c->aux_mlm != 0) {
+    if (c->aux_mlm != 1) { err = "aux_mlm must be 0 or 1"; return false; }
+    if (c->model_kind != SAMA_MODEL_ENCODER) { err = "aux_mlm needs the ENCODER model"; return false; }
+    if (c->corr_hidden > 0) { err = "aux_mlm cannot be combined with label correction"; return false; }
+    if (c->max_aux_batch < 1) { err = "max_aux_batch must be >= 1"; return false; }
+    if (c->max_aux_masked < 1 || (int64_t)c->max_aux_masked > (int64_t)c->max_aux_batch * c->dims[4]) {
+      err = "max_aux_masked must be 1..max_aux_batch * S"; return false;
+    }
+  }
   return true;
 }
 
@@ -116,12 +135,19 @@ static size_t carve(sama_ctx* c, void* base) {
   c->partial = ws.take<double>(EW_MAX_BLOCKS);
   c->scalars = ws.take<float>(4);
   c->counters = ws.take<int64_t>(4);
-  const int mb = c->cfg.max_batch > c->cfg.max_meta_batch ? c->cfg.max_batch : c->cfg.max_meta_batch;
+  const int mb = max_rows(c->cfg);
   const int C = c->cfg.dims[c->cfg.n_dims - 1];
   c->logits = ws.take<float>((size_t)2 * mb * C);   // room for the stacked + and - passes
   c->dlogits = ws.take<float>((size_t)mb * C);
   c->losses = ws.take<float>(mb);
   c->corr_scratch = c->cfg.corr_hidden > 0 ? ws.take<double>((size_t)c->cfg.max_batch * 2 * C) : nullptr;
+  if (c->cfg.aux_mlm) {
+    const size_t P = (size_t)(c->cfg.max_aux_masked + 63) / 64 * 64;
+    c->ids_cat = ws.take<int32_t>((size_t)mb * c->cfg.dims[4]); c->y_cat = ws.take<int32_t>(mb); c->mask_cat = ws.take<uint8_t>(mb);
+    c->loss_pos = ws.take<float>(2 * P); c->coef_pos = ws.take<float>(P);
+  } else {
+    c->ids_cat = c->y_cat = nullptr; c->mask_cat = nullptr; c->loss_pos = c->coef_pos = nullptr;
+  }
   if (c->model) c->model->plan(ws, mb);
   return ws.used();
 }
@@ -234,6 +260,8 @@ static PassWeights pass_weights(sama_ctx* c, float sign) {
   return w;
 }
 
+static void base_update(sama_ctx* c);
+
 sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out) {
   if (!c) return SAMA_EINVAL;
   sama_status s = check_batch(c, train, c->cfg.max_batch, "train");
@@ -248,6 +276,13 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
   sa.losses = c->losses; sa.dlogits = c->dlogits; sa.loss_scalar = c->scalars + 2; sa.loss_user = loss_out;
   launch_sample_stage(st, sa);
   c->model->backward(st, w, *train, c->dlogits, c->g);
+  base_update(c);
+  return check_hip(c, "sama_base_step");
+}
+
+// the base solver's update with the gradient in c->g (App. C for Adam); advances the step count
+static void base_update(sama_ctx* c) {
+  hipStream_t st = c->stream;
   c->t += 1;
   const sama_config& f = c->cfg;
   if (f.base_opt == SAMA_OPT_ADAM) {
@@ -262,7 +297,58 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
     launch_sgd(st, c->g, c->theta, c->theta16, c->n, c->n_gemm, f.base_lr, f.weight_decay);
   }
   launch_fill_i64x4(st, c->counters, c->t, 0, 0, 0, 1);
-  return check_hip(c, "sama_base_step");
+}
+
+// First half of a meta gradient: g_meta = dL_meta/dtheta on the clean batch (Eq. 1), v = (du/dg) . g_meta,
+// eps = alpha / ||v|| (Eq. 4-5, App. C), and the low halves of theta +- eps v.  Returns whether the GEMM block of
+// theta was nudged already (sama_meta_step on bf16 models: one pass over theta and v instead of two).
+static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
+  hipStream_t st = c->stream;
+  const sama_config& f = c->cfg;
+  const int C = c->model->n_classes();
+  PassWeights w0 = pass_weights(c, 0.f);
+  if (c->bf16 && !f.fast_meta_pass) {   // hi + lo of the master weights: the gradient is taken at theta, not bf16(theta)
+    launch_residual_lo(st, c->theta, c->lo_p, c->n_gemm);
+    w0.lo = c->lo_p;
+  }
+  c->model->forward(st, w0, *meta, true, c->logits);
+  SampleStageArgs sa{};
+  sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = meta->n; sa.H = f.wnet_hidden; sa.mode = STAGE_META;
+  sa.y = meta->y; sa.mask = meta->sample_mask; sa.lambda = c->lambda; sa.losses = c->losses; sa.dlogits = c->dlogits;
+  sa.loss_scalar = c->scalars + 3;
+  launch_sample_stage(st, sa);
+  c->model->backward(st, w0, *meta, c->dlogits, c->gmeta);
+  AdaptArgs ad{};
+  if (f.adapt_mode == SAMA_ADAPT_NONE) { ad.mode = 1; ad.scalar = 1.f; }
+  else if (f.base_opt == SAMA_OPT_SGD) { ad.mode = 1; ad.scalar = f.base_lr; }
+  else {
+    const double c1 = 1.0 / (1.0 - pow((double)f.beta1, (double)c->t));
+    const double c2 = 1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t));
+    ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)f.beta1); ad.one_m_beta2 = (float)(1.0 - (double)f.beta2);
+    ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
+  }
+  launch_adapt_norm(st, c->g, c->m, c->v, c->gmeta, c->vdir, c->partial, c->n, ad, f.alpha, c->scalars, c->counters + 2);
+  // A step that is applied nudges the GEMM block of theta in the same pass that writes the low halves; the non-GEMM
+  // tail is nudged after the two passes, which read it as theta +- eps v.
+  const bool fused_nudge = update && c->bf16 && c->n_gemm % 4 == 0;
+  if (fused_nudge) launch_perturb_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->lo_p, c->lo_m, c->n_gemm);
+  else if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
+  return fused_nudge;
+}
+
+// Second half: h from the two lambda-gradients (Eq. 5), Adam on lambda and the nudge of theta when `update`.
+static void meta_finish(sama_ctx* c, float* hyper_out, float* eps_out, bool update, bool fused_nudge) {
+  hipStream_t st = c->stream;
+  const sama_config& f = c->cfg;
+  MetaUpdateArgs mu{};
+  mu.glam_p = c->glam_p; mu.glam_m = c->glam_m; mu.scalars = c->scalars; mu.counters = c->counters;
+  mu.hypergrad = c->hyper; mu.hypergrad_user = hyper_out; mu.eps_user = eps_out;
+  mu.glam_p_f32 = c->glam_p32; mu.glam_m_f32 = c->glam_m32;
+  mu.lambda = c->lambda; mu.meta_m = c->meta_m; mu.meta_v = c->meta_v; mu.nl = c->nl; mu.do_update = update ? 1 : 0;
+  mu.lr = f.meta_lr; mu.beta1 = f.meta_beta1; mu.beta2 = f.meta_beta2; mu.eps = f.meta_eps;
+  launch_meta_update(st, mu);
+  if (update && fused_nudge) launch_nudge(st, c->theta + c->n_gemm, c->vdir + c->n_gemm, c->scalars, nullptr, c->n - c->n_gemm, 0);
+  else if (update) launch_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->n, c->n_gemm);
 }
 
 static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_batch* meta, float* hyper_out,
@@ -277,54 +363,92 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
   (void)hipGetLastError();
   const sama_config& f = c->cfg;
   const int C = c->model->n_classes();
-  // pass 1: direct gradient dL_meta/dtheta on the clean batch (Eq. 1)
-  PassWeights w0 = pass_weights(c, 0.f);
-  if (c->bf16 && !f.fast_meta_pass) {   // hi + lo of the master weights: the gradient is taken at theta, not bf16(theta)
-    launch_residual_lo(st, c->theta, c->lo_p, c->n_gemm);
-    w0.lo = c->lo_p;
-  }
-  c->model->forward(st, w0, *meta, true, c->logits);
-  SampleStageArgs sa{};
-  sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = meta->n; sa.H = f.wnet_hidden; sa.mode = STAGE_META;
-  sa.y = meta->y; sa.mask = meta->sample_mask; sa.lambda = c->lambda; sa.losses = c->losses; sa.dlogits = c->dlogits;
-  sa.loss_scalar = c->scalars + 3;
-  launch_sample_stage(st, sa);
-  c->model->backward(st, w0, *meta, c->dlogits, c->gmeta);
-  // analytic pass: v = (du/dg) . g_meta, eps = alpha / ||v|| (Eq. 4-5, App. C)
-  AdaptArgs ad{};
-  if (f.adapt_mode == SAMA_ADAPT_NONE) { ad.mode = 1; ad.scalar = 1.f; }
-  else if (f.base_opt == SAMA_OPT_SGD) { ad.mode = 1; ad.scalar = f.base_lr; }
-  else {
-    const double c1 = 1.0 / (1.0 - pow((double)f.beta1, (double)c->t));
-    const double c2 = 1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t));
-    ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)f.beta1); ad.one_m_beta2 = (float)(1.0 - (double)f.beta2);
-    ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
-  }
-  launch_adapt_norm(st, c->g, c->m, c->v, c->gmeta, c->vdir, c->partial, c->n, ad, f.alpha, c->scalars, c->counters + 2);
-  // A step that is applied nudges the GEMM block of theta in the same pass that writes the low halves (one pass over
-  // theta and v instead of two); the non-GEMM tail is nudged after the two passes, which read it as theta +- eps v.
-  const bool fused_nudge = update && c->bf16 && c->n_gemm % 4 == 0;
-  if (fused_nudge) launch_perturb_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->lo_p, c->lo_m, c->n_gemm);
-  else if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
+  const bool fused_nudge = meta_direction(c, meta, update);
   // passes 2 and 3: dL_base/dlambda at theta +- eps v; forward only, then the weight net's backward
   c->model->forward_pair(st, pass_weights(c, 1.f), pass_weights(c, -1.f), *train, c->logits);
   for (int pass = 0; pass < 2; ++pass) {
     SampleStageArgs sg{};
-    sg.logits = c->logits + (size_t)pass * train->n * C; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM; sg.Hc = f.corr_hidden; sg.kappa = f.corr_kappa; sg.corr_scratch = c->corr_scratch;
+    sg.logits = c->logits + (size_t)pass * train->n * C; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM;
+    sg.Hc = f.corr_hidden; sg.kappa = f.corr_kappa; sg.corr_scratch = c->corr_scratch;
     sg.y = train->y; sg.mask = train->sample_mask; sg.lambda = c->lambda; sg.losses = c->losses;
     sg.glam = pass == 0 ? c->glam_p : c->glam_m;
     launch_sample_stage(st, sg);
   }
-  MetaUpdateArgs mu{};
-  mu.glam_p = c->glam_p; mu.glam_m = c->glam_m; mu.scalars = c->scalars; mu.counters = c->counters;
-  mu.hypergrad = c->hyper; mu.hypergrad_user = hyper_out; mu.eps_user = eps_out;
-  mu.glam_p_f32 = c->glam_p32; mu.glam_m_f32 = c->glam_m32;
-  mu.lambda = c->lambda; mu.meta_m = c->meta_m; mu.meta_v = c->meta_v; mu.nl = c->nl; mu.do_update = update ? 1 : 0;
-  mu.lr = f.meta_lr; mu.beta1 = f.meta_beta1; mu.beta2 = f.meta_beta2; mu.eps = f.meta_eps;
-  launch_meta_update(st, mu);
-  if (update && fused_nudge) launch_nudge(st, c->theta + c->n_gemm, c->vdir + c->n_gemm, c->scalars, nullptr, c->n - c->n_gemm, 0);
-  else if (update) launch_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->n, c->n_gemm);
+  meta_finish(c, hyper_out, eps_out, update, fused_nudge);
   return check_hip(c, update ? "sama_meta_step" : "sama_meta_grad");
+}
+
+// ------------------------------------------------------------------ auxiliary-task reweighting (Sec. 4.3)
+static sama_status check_aux(sama_ctx* c, const sama_aux_batch* pt) {
+  if (!c->cfg.aux_mlm || !c->model->has_mlm()) return fail(c, SAMA_EINVAL, "the context was not created with aux_mlm = 1");
+  if (!pt || !pt->ids || !pt->mask_row || !pt->mask_tgt) return fail(c, SAMA_EINVAL, "aux: null batch / ids / mask_row / mask_tgt");
+  if (pt->n_seq < 1 || pt->n_seq > c->cfg.max_aux_batch) return fail(c, SAMA_EINVAL, "aux: n_seq outside 1..max_aux_batch");
+  if (pt->n_mask < 1 || pt->n_mask > c->cfg.max_aux_masked) return fail(c, SAMA_EINVAL, "aux: n_mask outside 1..max_aux_masked");
+  if ((int64_t)pt->n_mask > (int64_t)pt->n_seq * c->cfg.dims[4]) return fail(c, SAMA_EINVAL, "aux: more masked positions than tokens");
+  return SAMA_OK;
+}
+
+// the sequence-mode stage on the masked-token losses of one pass
+static void aux_stage(sama_ctx* c, const sama_aux_batch* pt, int mode, const float* loss_pos, float* losses, double* glam,
+                      float* loss_user) {
+  SampleStageArgs sa{};
+  sa.B = pt->n_seq; sa.H = c->cfg.wnet_hidden; sa.mode = mode; sa.lambda = c->lambda; sa.losses = losses;
+  sa.pos_loss = loss_pos; sa.pos_row = pt->mask_row; sa.n_pos = pt->n_mask; sa.S = c->cfg.dims[4];
+  sa.pos_coef = c->coef_pos; sa.loss_scalar = c->scalars + 2; sa.loss_user = loss_user; sa.glam = glam;
+  launch_sample_stage(c->stream, sa);
+}
+
+sama_status sama_aux_base_step(sama_ctx* c, const sama_batch* ft, const sama_aux_batch* pt, float* loss_out) {
+  if (!c) return SAMA_EINVAL;
+  sama_status s = check_batch(c, ft, c->cfg.max_batch, "ft");
+  if (s != SAMA_OK) return s;
+  s = check_aux(c, pt);
+  if (s != SAMA_OK) return s;
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  const int S = c->cfg.dims[4], C = c->model->n_classes(), n_ft = ft->n, n_pt = pt->n_seq;
+  launch_aux_cat(st, (const int32_t*)ft->x, ft->y, ft->sample_mask, n_ft, pt->ids, n_pt, S, c->ids_cat, c->y_cat, c->mask_cat);
+  const sama_batch cat{c->ids_cat, c->y_cat, c->mask_cat, n_ft + n_pt};
+  const PassWeights w = pass_weights(c, 0.f);
+  c->model->forward(st, w, cat, true, c->logits);
+  // finetuning term: mean cross-entropy over the ft rows (the auxiliary rows are masked out of the classifier loss)
+  SampleStageArgs sa{};
+  sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = cat.n; sa.H = c->cfg.wnet_hidden; sa.mode = STAGE_META;
+  sa.y = cat.y; sa.mask = cat.sample_mask; sa.lambda = c->lambda; sa.losses = c->losses; sa.dlogits = c->dlogits;
+  sa.loss_scalar = c->scalars + 2; sa.loss_user = loss_out;
+  launch_sample_stage(st, sa);
+  // weighted pretraining term
+  const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, n_ft * S, n_pt * S};
+  c->model->mlm_forward(st, &w, 1, cat.n * S, true, mb, c->loss_pos);
+  aux_stage(c, pt, STAGE_BASE, c->loss_pos, c->losses + n_ft, nullptr, loss_out);
+  c->model->backward_mlm(st, w, cat, c->dlogits, c->g, mb, c->coef_pos);
+  base_update(c);
+  return check_hip(c, "sama_aux_base_step");
+}
+
+static sama_status aux_meta_common(sama_ctx* c, const sama_aux_batch* pt, const sama_batch* meta, float* hyper_out,
+                                   float* eps_out, bool update) {
+  if (!c) return SAMA_EINVAL;
+  sama_status s = check_aux(c, pt);
+  if (s != SAMA_OK) return s;
+  s = check_batch(c, meta, c->cfg.max_meta_batch, "meta");
+  if (s != SAMA_OK) return s;
+  if (c->t < 1) return fail(c, SAMA_ESTATE, "meta gradient requested before any base step");
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  const int S = c->cfg.dims[4];
+  const bool fused_nudge = meta_direction(c, meta, update);
+  // passes 2 and 3 on the auxiliary sequences alone: the finetuning term of L_base does not depend on lambda
+  const sama_batch ptb{pt->ids, nullptr, nullptr, pt->n_seq};
+  const PassWeights w[2] = {pass_weights(c, 1.f), pass_weights(c, -1.f)};
+  c->model->forward_pair(st, w[0], w[1], ptb, c->logits);
+  const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, 0, pt->n_seq * S};
+  c->model->mlm_forward(st, w, 2, pt->n_seq * S, false, mb, c->loss_pos);
+  const int P = c->model->mlm_stride();
+  for (int pass = 0; pass < 2; ++pass)
+    aux_stage(c, pt, STAGE_GLAM, c->loss_pos + (size_t)pass * P, c->losses, pass == 0 ? c->glam_p : c->glam_m, nullptr);
+  meta_finish(c, hyper_out, eps_out, update, fused_nudge);
+  return check_hip(c, update ? "sama_aux_meta_step" : "sama_aux_meta_grad");
 }
 
 sama_status sama_meta_grad(sama_ctx* c, const sama_batch* train, const sama_batch* meta, float* hypergrad_out,
@@ -333,6 +457,13 @@ sama_status sama_meta_grad(sama_ctx* c, const sama_batch* train, const sama_batc
 }
 sama_status sama_meta_step(sama_ctx* c, const sama_batch* train, const sama_batch* meta) {
   return meta_common(c, train, meta, nullptr, nullptr, true);
+}
+sama_status sama_aux_meta_grad(sama_ctx* c, const sama_aux_batch* pt, const sama_batch* meta, float* hypergrad_out,
+                               float* eps_out) {
+  return aux_meta_common(c, pt, meta, hypergrad_out, eps_out, false);
+}
+sama_status sama_aux_meta_step(sama_ctx* c, const sama_aux_batch* pt, const sama_batch* meta) {
+  return aux_meta_common(c, pt, meta, nullptr, nullptr, true);
 }
 
 static bool state_ptr(sama_ctx* c, int32_t which, void** p, size_t* bytes, bool* writable) {
@@ -354,7 +485,7 @@ static bool state_ptr(sama_ctx* c, int32_t which, void** p, size_t* bytes, bool*
     case SAMA_STATE_GLAM_MINUS: *p = c->glam_m32; *bytes = lb; *writable = false; return true;
     case SAMA_STATE_SCALARS: *p = c->scalars; *bytes = 16; *writable = false; return true;
     case SAMA_STATE_LOSSES: {
-      const int mb = c->cfg.max_batch > c->cfg.max_meta_batch ? c->cfg.max_batch : c->cfg.max_meta_batch;
+      const int mb = max_rows(c->cfg);
       *p = c->losses; *bytes = (size_t)mb * 4; *writable = false; return true;
     }
   }

@@ -35,7 +35,8 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   __shared__ double red[256];
   __shared__ float s_lc[MAX_CORR_HIDDEN * 2 * MAX_CORR_CLASSES + MAX_CORR_HIDDEN + MAX_CORR_CLASSES * MAX_CORR_HIDDEN + MAX_CORR_CLASSES];
   const int tid = threadIdx.x, H = a.H, B = a.B, C = a.C;
-  const int Hc = a.mode == STAGE_META ? 0 : a.Hc;      // the clean batch keeps its hard labels
+  const bool seq_mode = a.pos_loss != nullptr;          // per-sequence losses from masked-token positions
+  const int Hc = (a.mode == STAGE_META || seq_mode) ? 0 : a.Hc;      // the clean batch keeps its hard labels
   for (int i = tid; i < 3 * H + 1; i += 256) s_lam[i] = a.lambda[i];
   const int nlc = Hc > 0 ? Hc * 2 * C + Hc + C * Hc + C : 0;
   for (int i = tid; i < nlc; i += 256) s_lc[i] = a.lambda[3 * H + 1 + i];
@@ -50,7 +51,39 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   const double inv_beff = beff > 0.0 ? 1.0 / beff : 0.0;
 
   double lsum = 0.0;
-  for (int i = tid; i < B; i += 256) {
+  float* s_cnt = s_lc;                                  // sequence mode: positions per sequence (the corrector is off)
+  for (int i = tid; seq_mode && i < B; i += 256) {
+    double acc = 0.0, n_i = 0.0;
+    for (int j = 0; j < a.n_pos; ++j) {
+      int r = a.pos_row[j];
+      r = r < 0 ? 0 : (r >= B * a.S ? B * a.S - 1 : r);
+      if (r / a.S == i) { acc += (double)a.pos_loss[j]; n_i += 1.0; }
+    }
+    const double l = n_i > 0.0 ? acc / n_i : 0.0;
+    const double mk = (a.mask == nullptr || a.mask[i] != 0) ? 1.0 : 0.0;
+    a.losses[i] = (float)l;
+    s_l[i] = l;
+    s_cnt[i] = (float)n_i;
+    double zz = b2;
+    for (int h = 0; h < H; ++h) zz += (double)W2[h] * fmax((double)W1[h] * l + (double)b1[h], 0.0);
+    const double w = 1.0 / (1.0 + exp(-zz));
+    if (a.mode == STAGE_GLAM) {
+      s_dz[i] = w * (1.0 - w) * l * mk * inv_beff;
+    } else {
+      s_dz[i] = mk * w * inv_beff;
+      lsum += s_dz[i] * l;
+    }
+  }
+  if (seq_mode && a.mode != STAGE_GLAM) {
+    __syncthreads();
+    for (int j = tid; j < a.n_pos; j += 256) {
+      int r = a.pos_row[j];
+      r = r < 0 ? 0 : (r >= B * a.S ? B * a.S - 1 : r);
+      const int i = r / a.S;
+      a.pos_coef[j] = (float)(s_dz[i] / (double)s_cnt[i]);     // s_cnt[i] >= 1: position j itself belongs to i
+    }
+  }
+  for (int i = tid; !seq_mode && i < B; i += 256) {
     const float* z = a.logits + (int64_t)i * a.ld;
     double zmax = (double)z[0];
     for (int c = 1; c < C; ++c) zmax = fmax(zmax, (double)z[c]);
@@ -112,8 +145,8 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   if (a.mode != STAGE_GLAM) {
     const double L = block_sum_d(lsum, red);
     if (tid == 0) {
-      if (a.loss_scalar) *a.loss_scalar = (float)L;
-      if (a.loss_user) *a.loss_user = (float)L;
+      if (a.loss_scalar) *a.loss_scalar = seq_mode ? *a.loss_scalar + (float)L : (float)L;
+      if (a.loss_user) *a.loss_user = seq_mode ? *a.loss_user + (float)L : (float)L;
     }
     return;
   }

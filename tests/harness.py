@@ -30,6 +30,27 @@ def make_pair(wl, theta0, lambda0, **over):
     return orc, gpu
 
 
+def make_aux_pair(wl, theta0, lambda0, max_aux_batch, max_aux_masked, **over):
+    """(AuxTaskOracle, gpu context) for an encoder workload with the masked-token head (wl.mlm must be set)."""
+    import paper_2310_05674_amd as pkg
+    from oracle import models
+    from oracle.auxtask import AuxTaskOracle
+    kw = dict(base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
+              adam_eps=wl.adam_eps)
+    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps")})
+    orc = AuxTaskOracle(models.make_model(wl.kind, wl.dims, mlm=True), theta0, lambda0, **kw)
+    cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch, aux_mlm=1,
+                              max_aux_batch=max_aux_batch, max_aux_masked=max_aux_masked, **kw)
+    return orc, pkg.Sama(cfg, theta0, lambda0)
+
+
+def dev_aux_batch(gpu, ids, seq, pos, tgt):
+    import torch
+    S = ids.shape[1]
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a).astype(np.int32), device=gpu.dev)
+    return gpu.aux_batch(t(ids), t(seq.astype(np.int64) * S + pos), t(tgt))
+
+
 def dev_batch(gpu, x, y, mask=None):
     import torch
     xt = torch.as_tensor(np.ascontiguousarray(x), device=gpu.dev)

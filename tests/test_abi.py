@@ -49,6 +49,30 @@ def test_layout_matches_datagen(lib, cfg):
     assert ng == sum(r * cc for n, o, r, cc in want if n.split(".")[-1] in ("Wqkv", "Wo", "W1", "W2") or (w["kind"] == "mlp" and n.startswith("W")))
 
 
+def test_masked_token_head_layout_and_limits(lib):
+    import paper_2310_05674_amd as pkg
+    from paper_2310_05674_amd.binding import param_tensors
+    dims = (2, 128, 2, 256, 128, 640, 3)
+    good = dict(H=8, max_batch=4, max_meta_batch=4)
+    c = pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=100, **good)
+    want = [(n, o, s[0], s[1] if len(s) > 1 else 1) for n, s, o in param_layout("encoder", dims, mlm=True)]
+    assert param_tensors(c) == want
+    assert lib.sama_param_count(C.byref(c)) == param_count("encoder", dims, mlm=True)
+    plain = pkg.SamaConfig.make("encoder", dims, **good)
+    assert lib.sama_gemm_param_count(C.byref(c)) == lib.sama_gemm_param_count(C.byref(plain)) + 640 * 128
+    assert lib.sama_workspace_bytes(C.byref(c)) > lib.sama_workspace_bytes(C.byref(plain)) > 0
+    for bad in (pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 128, 600, 3), aux_mlm=1, max_aux_batch=4, max_aux_masked=100, **good),
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=0, max_aux_masked=100, **good),
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=0, **good),
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=4 * 128 + 1, **good),
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=30, max_aux_masked=100, **good),   # 34 * 128 tokens
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=2, max_aux_batch=4, max_aux_masked=100, **good),
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=100, corr_hidden=4, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), aux_mlm=1, max_aux_batch=4, max_aux_masked=100, **good)):
+        assert lib.sama_workspace_bytes(C.byref(bad)) == 0
+        assert lib.sama_last_error(None) != b""
+
+
 def test_bad_configs_rejected(lib):
     import paper_2310_05674_amd as pkg
     good = dict(H=16, max_batch=8, max_meta_batch=8)

@@ -1,0 +1,131 @@
+"""GPU parity of auxiliary-task reweighting (Sec. 4.3: L_base = L_ft + weighted masked-token loss of the auxiliary
+sequences, L_meta = L_ft): the HIP path through the C ABI against the float64 oracle on the same seeded inputs,
+teacher-forced, on a small encoder with a 640-token vocabulary (bf16 GEMM operands; GEMM weights snapped to bf16 on
+both sides so that the bar measures the kernels' arithmetic)."""
+import numpy as np
+import pytest
+from datagen import make_workload, make_aux_batch, init_theta, init_lambda, round_to_bf16
+from harness import rel_l2, make_aux_pair, dev_batch, dev_aux_batch, push_state, pull
+
+pytestmark = pytest.mark.gpu
+KTOL, TOL = 1e-2, 2e-2
+SMALL = dict(dims=(2, 192, 3, 320, 128, 640, 3), batch=5, meta_batch=3, mlm=True)
+GEMM_LEAVES = ("Wqkv", "Wo", "W1", "W2", "Wmlm")
+
+
+def _snap(orc):
+    ng = sum(int(np.prod(sh)) for nm, (o, sh) in orc.model.slices.items() if nm.split(".")[-1] in GEMM_LEAVES)
+    orc.theta[:ng] = round_to_bf16(orc.theta[:ng])
+
+
+def _setup(n_pt=4, scale=0.02):
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    orc, gpu = make_aux_pair(wl, init_theta(wl, scale), init_lambda(wl), max_aux_batch=n_pt, max_aux_masked=n_pt * 26,
+                             base_lr=1e-3)
+    return wl, orc, gpu
+
+
+def _ft(wl, step):
+    it, im = wl.train_batch(step), wl.meta_batch_idx(step)
+    return (wl.x_train[it], wl.y_train[it]), (wl.x_meta[im], wl.y_meta[im])
+
+
+def _group_errors(orc, got, want):
+    out = {}
+    for name, (off, shape) in orc.model.slices.items():
+        sl = slice(off, off + int(np.prod(shape)))
+        out[name] = rel_l2(got[sl], want[sl])
+    return out
+
+
+def test_aux_base_step_parity():
+    wl, orc, gpu = _setup()
+    for s in range(2):
+        ft, _ = _ft(wl, s)
+        pt = make_aux_batch(wl, s, 4)
+        _snap(orc)
+        push_state(orc, gpu)
+        th = orc.theta.copy()
+        l_ft = orc.model.losses(th, ft[0], ft[1])
+        l_pos = orc.model.mlm_losses(th, pt[0], pt[1], pt[2], pt[3])
+        l_seq = np.array([l_pos[pt[1] == i].mean() for i in range(4)])
+        lo = orc.base_step(ft, pt)
+        gpu.aux_base_step(dev_batch(gpu, ft[0], ft[1]), dev_aux_batch(gpu, *pt))
+        losses = pull(gpu, "LOSSES")
+        assert np.max(np.abs(losses[:5] - l_ft)) < 2e-2 * max(1.0, np.max(l_ft))
+        assert np.max(np.abs(losses[5:9] - l_seq)) < 2e-2 * np.max(l_seq), (losses[5:9], l_seq)
+        assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 1e-2 * abs(lo)
+        g = pull(gpu, "G")
+        errs = _group_errors(orc, g, orc.g)
+        worst = max(errs, key=errs.get)
+        print(f"aux base step {s}: L_base {lo:.4f} rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {worst} {errs[worst]:.3e}; "
+              f"Wmlm {errs['Wmlm']:.3e} bmlm {errs['bmlm']:.3e}")
+        assert rel_l2(g, orc.g) < KTOL
+        assert errs["Wmlm"] < KTOL and errs["bmlm"] < KTOL and errs["tok_emb"] < TOL
+        assert all(e < TOL for e in errs.values()), errs
+        # the first Adam steps are sign-like (|update| = lr whatever |g|), so theta carries the gradient's rounding noise
+        assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+        assert int(pull(gpu, "COUNTERS")[0]) == orc.t
+    gpu.close()
+
+
+def test_aux_meta_step_parity():
+    wl, orc, gpu = _setup()
+    nw = orc.model.slices["Wmlm"]
+    for s in range(3):
+        ft, _ = _ft(wl, s)
+        orc.base_step(ft, make_aux_batch(wl, s, 4))
+    for s in range(3, 5):
+        ft, meta = _ft(wl, s)
+        pt = make_aux_batch(wl, s, 4 if s == 3 else 3)          # the second round with a smaller auxiliary batch
+        orc.base_step(ft, pt)
+        _snap(orc)
+        push_state(orc, gpu)
+        ptb, mb = dev_aux_batch(gpu, *pt), dev_batch(gpu, meta[0], meta[1])
+        gpu.aux_meta_grad(ptb, mb)
+        assert np.array_equal(pull(gpu, "THETA"), orc.theta.astype(np.float32))
+        h_pure = pull(gpu, "HYPERGRAD")
+        r = orc.meta_step(pt, meta)
+        gpu.aux_meta_step(ptb, mb)
+        gm = pull(gpu, "GMETA")
+        assert np.all(gm[nw[0]:nw[0] + int(np.prod(nw[1]))] == 0)      # L_ft does not touch the masked-token head
+        h = pull(gpu, "HYPERGRAD")
+        e = dict(gmeta=rel_l2(gm, r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+                 eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(h, r["h"]),
+                 glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), glam_m=rel_l2(pull(gpu, "GLAM_MINUS"), r["glam_m"]),
+                 theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+        print(f"aux meta step {s}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+        # two routes through the elementwise chain (separate low halves / one fused pass): agreement to the rounding of
+        # the low halves, amplified by the difference of Eq. 5, not bit for bit
+        assert rel_l2(h_pure, r["h"]) < TOL and rel_l2(h, h_pure) < TOL
+        assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["glam_m"] < KTOL and e["eps"] < KTOL and e["v"] < TOL
+        assert e["h"] < TOL, e
+        assert e["theta"] < TOL and e["lam"] < TOL
+        assert int(pull(gpu, "COUNTERS")[2]) == 0 and int(pull(gpu, "COUNTERS")[1]) == orc.meta_t
+    gpu.close()
+
+
+def test_aux_entry_points_reject_bad_batches():
+    import torch
+    import paper_2310_05674_amd as pkg
+    wl, orc, gpu = _setup()
+    ft, meta = _ft(wl, 0)
+    pt = make_aux_batch(wl, 0, 4)
+    good = dev_aux_batch(gpu, *pt)
+    with pytest.raises(pkg.SamaError):      # meta gradient before any base step
+        gpu.aux_meta_step(good, dev_batch(gpu, meta[0], meta[1]))
+    big = make_aux_batch(wl, 0, 5)
+    with pytest.raises(pkg.SamaError):      # more sequences than max_aux_batch
+        gpu.aux_base_step(dev_batch(gpu, ft[0], ft[1]), dev_aux_batch(gpu, *big))
+    many = gpu.aux_batch(good._keep[0], torch.arange(4 * 26 + 1, dtype=torch.int32, device=gpu.dev),
+                         torch.zeros(4 * 26 + 1, dtype=torch.int32, device=gpu.dev))
+    with pytest.raises(pkg.SamaError):      # more masked positions than max_aux_masked
+        gpu.aux_base_step(dev_batch(gpu, ft[0], ft[1]), many)
+    gpu.close()
+    # a context without the head refuses the auxiliary entry points
+    wl2 = make_workload(3, n_train=40, n_meta=12, dims=SMALL["dims"], batch=5, meta_batch=3)
+    from harness import make_pair
+    _, plain = make_pair(wl2, init_theta(wl2), init_lambda(wl2))
+    with pytest.raises(pkg.SamaError):
+        plain.aux_base_step(dev_batch(plain, ft[0], ft[1]), dev_aux_batch(plain, *pt))
+    plain.close()
