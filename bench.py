@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--fast-meta-pass", type=int, default=0)
     ap.add_argument("--corr-hidden", type=int, default=0,
                     help="label correction (Sec. 4.1) with a corrector of this hidden width; 0 = the headline data-reweighting workload")
+    ap.add_argument("--aux", action="store_true",
+                    help="auxiliary-task reweighting (Sec. 4.3) instead of the headline workload: the 12-layer encoder with a "
+                         "50304-token masked-token head, 16 finetuning + 16 auxiliary sequences per base step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -57,22 +60,29 @@ def main():
 
     import numpy as np
     import torch
-    from datagen import make_workload, init_theta, init_lambda, init_lambda_corr
+    from datagen import make_workload, init_theta, init_lambda, init_lambda_corr, make_aux_workload, make_aux_batch, AUX_TASK
     import paper_2310_05674_amd as pkg
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg_id = args.workload
     nb = 4                                                  # distinct synthetic batches cycled through
-    wl0 = make_workload(cfg_id, n_train=8, n_meta=8)        # shapes only
-    wl = make_workload(cfg_id, n_train=min(wl0.batch * nb, 12800) if cfg_id != 1 else None,
-                       n_meta=min(wl0.meta_batch * nb, 1280) if cfg_id != 1 else None)
+    if args.aux:
+        if args.corr_hidden:
+            sys.exit("bench.py: --aux and --corr-hidden cannot be combined")
+        cfg_id = AUX_TASK["base"]
+        wl = make_aux_workload(n_train=AUX_TASK["batch"] * nb, n_meta=AUX_TASK["meta_batch"] * nb)
+    else:
+        wl0 = make_workload(cfg_id, n_train=8, n_meta=8)        # shapes only
+        wl = make_workload(cfg_id, n_train=min(wl0.batch * nb, 12800) if cfg_id != 1 else None,
+                           n_meta=min(wl0.meta_batch * nb, 1280) if cfg_id != 1 else None)
     th0, lam0 = init_theta(wl), init_lambda(wl)
     if args.corr_hidden > 0:
         lam0 = np.concatenate([lam0, init_lambda_corr(wl, args.corr_hidden)])
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch,
                               base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
-                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass, corr_hidden=args.corr_hidden)
+                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass, corr_hidden=args.corr_hidden,
+                              **(dict(aux_mlm=1, max_aux_batch=AUX_TASK["n_pt"], max_aux_masked=AUX_TASK["n_pt"] * 26) if args.aux else {}))
     s = pkg.Sama(cfg, th0, lam0)
     n, n16 = s.n, s.lib.sama_gemm_param_count(__import__("ctypes").byref(cfg))
     batches = []
@@ -83,13 +93,29 @@ def main():
                         s.batch(torch.as_tensor(np.ascontiguousarray(wl.x_meta[im]), device=dev),
                                 torch.as_tensor(wl.y_meta[im].astype(np.int32), device=dev))))
 
+    aux = []
+    if args.aux:
+        S = wl.dims[4]
+        for k in range(nb):
+            ids, seq, pos, tgt = make_aux_batch(wl, k, AUX_TASK["n_pt"])
+            t = lambda a: torch.as_tensor(np.ascontiguousarray(a).astype(np.int32), device=dev)
+            aux.append(s.aux_batch(t(ids), t(seq.astype(np.int64) * S + pos), t(tgt)))
+
     def step(k):
         tb, mb = batches[k % nb]
+        if args.aux:
+            for _ in range(args.unroll):
+                s.aux_base_step(tb, aux[k % nb])
+            s.aux_meta_step(aux[k % nb], mb)
+            return
         for _ in range(args.unroll):
             s.base_step(tb)
         s.meta_step(tb, mb)
 
-    s.base_step(batches[0][0])                              # one step of Adam history before anything is timed
+    if args.aux:
+        s.aux_base_step(batches[0][0], aux[0])
+    else:
+        s.base_step(batches[0][0])                          # one step of Adam history before anything is timed
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize(dev)
@@ -107,7 +133,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"BASELINE.json configs[{cfg_id - 1}]: " +
+        "config": {"workload": ("auxiliary-task reweighting (Sec. 4.3; not a BASELINE.json config), {} auxiliary sequences / {} masked "
+                                "positions per base step: ".format(AUX_TASK["n_pt"], aux[0].n_mask) if args.aux else
+                                f"BASELINE.json configs[{cfg_id - 1}]: ") +
                    ("MLP " + "-".join(map(str, wl.dims)) if wl.kind == "mlp" else
                     "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
                    "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
@@ -133,7 +161,7 @@ def main():
                 ent.update(bound="mfma", achieved=units / (ms * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
             elif name == "gemm_f32":
                 ent.update(bound="mfma", achieved=units / (ms * 1e-3) / 1e12, peak=PEAK_FP32_MATRIX_TFLOPS, unit="TFLOP/s")
-            elif units > 0:
+            elif units > 0:   # every other family is priced in algorithmic bytes
                 ent.update(bound="hbm", achieved=units / (ms * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s")
             if "achieved" in ent:
                 ent["frac"] = ent["achieved"] / ent["peak"]
@@ -144,6 +172,10 @@ def main():
         d = kernels[dom]
         U = args.unroll
         paper_flops = (3 * U + 5) * fwd_flops(wl, wl.batch)   # three-pass count of Sec. 3.3 (train and meta batches are equal here)
+        if args.aux:   # base steps run over ft + auxiliary sequences and the vocabulary head; the +- passes over the auxiliary ones
+            n_pt, head = AUX_TASK["n_pt"], 2.0 * aux[0].n_mask * wl.dims[1] * wl.dims[5]
+            paper_flops = (3 * U * (fwd_flops(wl, wl.batch + n_pt) + head) + 3 * fwd_flops(wl, wl.meta_batch)
+                           + 2 * (fwd_flops(wl, n_pt) + head))
         ew = [kernels[k] for k in ("adam", "adapt_norm", "perturb_lo", "residual_lo", "nudge") if k in kernels]
         ew_bytes = sum(k["achieved"] * 1e9 * k["ms_per_step"] * 1e-3 for k in ew)
         ew_ms = sum(k["ms_per_step"] for k in ew)
@@ -168,18 +200,29 @@ def main():
         from oracle.reweight import SamaOracle
         cb = {1: wl.batch, 2: wl.batch, 3: 8, 4: 2, 5: 1}[cfg_id]       # samples per batch in the CPU sample
         cm = min(cb, wl.meta_batch)
-        orc = SamaOracle(models.make_model(wl.kind, wl.dims), th0, lam0, base_lr=wl.base_lr, meta_lr=wl.meta_lr,
-                         alpha=wl.alpha, corr_hidden=args.corr_hidden,
-                         n_classes=wl.dims[-1] if args.corr_hidden > 0 else None)
         it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
         x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
-        orc.base_step(x, y)                                               # history (untimed)
         reps = {1: 20, 2: 10}.get(cfg_id, 1)
-        t0 = time.perf_counter()
-        for _ in range(reps):
+        if args.aux:
+            from oracle.auxtask import AuxTaskOracle
+            orc = AuxTaskOracle(models.make_model(wl.kind, wl.dims, mlm=True), th0, lam0, base_lr=wl.base_lr,
+                                meta_lr=wl.meta_lr, alpha=wl.alpha)
+            pt = make_aux_batch(wl, 0, cb)
+            orc.base_step((x, y), pt)                                     # history (untimed)
+            t0 = time.perf_counter()
             for _ in range(args.unroll):
-                orc.base_step(x, y)
-            orc.meta_step(x, y, xm, ym)
+                orc.base_step((x, y), pt)
+            orc.meta_step(pt, (xm, ym))
+        else:
+            orc = SamaOracle(models.make_model(wl.kind, wl.dims), th0, lam0, base_lr=wl.base_lr, meta_lr=wl.meta_lr,
+                             alpha=wl.alpha, corr_hidden=args.corr_hidden,
+                             n_classes=wl.dims[-1] if args.corr_hidden > 0 else None)
+            orc.base_step(x, y)                                           # history (untimed)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                for _ in range(args.unroll):
+                    orc.base_step(x, y)
+                orc.meta_step(x, y, xm, ym)
         tcpu = (time.perf_counter() - t0) / reps
         scale = wl.batch / cb
         try:

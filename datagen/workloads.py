@@ -203,6 +203,18 @@ def _zipf_tokens(rng, stream, n_seq, S, V, a=1.1):
     return ids
 
 
+# Auxiliary-task reweighting (Sec. 4.3 runs it on RoBERTa-base): the encoder of workload 4 with RoBERTa's vocabulary
+# (50265, rounded up to the next multiple of 64 as the masked-token head requires) and that workload's optimiser
+# settings; 16 finetuning + 16 auxiliary sequences per base step, 16 meta sequences.
+AUX_TASK = dict(base=4, dims=(12, 768, 12, 3072, 128, 50304, 6), batch=16, meta_batch=16, n_pt=16)
+
+
+def make_aux_workload(n_train=None, n_meta=None, **override):
+    kw = dict(dims=AUX_TASK["dims"], batch=AUX_TASK["batch"], meta_batch=AUX_TASK["meta_batch"], mlm=True)
+    kw.update(override)
+    return make_workload(AUX_TASK["base"], n_train=n_train, n_meta=n_meta, **kw)
+
+
 def make_aux_batch(wl, step, n_pt, lo=0.10, hi=0.20):
     """Masked-token batch `step` of the auxiliary task of an encoder workload: n_pt sequences of the token recipe
     (own stream), in each a seeded choice of between lo*S and hi*S positions (never position 0) whose ids are replaced

@@ -51,7 +51,7 @@ class EncoderModel : public Model {
     lnpart_[0] = ws.take<float>(nblk * 3 * d_); lnpart_[1] = ws.take<float>(nblk * 3 * d_);
     cspart_[0] = ws.take<float>(nrb * wide); cspart_[1] = ws.take<float>(nrb * wide);
     if (has_mlm()) {   // masked-token head: P_ positions (a multiple of 64, zero rows beyond the batch's), two stacked passes
-      hm_ = ws.take<bf16_t>((size_t)2 * P_ * d_); zt_ = ws.take<float>((size_t)2 * P_ * V_); lse_pos_ = ws.take<float>((size_t)2 * P_);
+      hm_ = ws.take<bf16_t>((size_t)2 * P_ * d_); hm_lo_ = ws.take<bf16_t>((size_t)2 * P_ * d_); zt_ = ws.take<float>((size_t)2 * P_ * V_); lse_pos_ = ws.take<float>((size_t)2 * P_);
       dzt_ = ws.take<bf16_t>((size_t)P_ * V_); dhm_ = ws.take<float>((size_t)GEMM_MAX_BATCH * P_ * d_);
       cs_mlm_ = ws.take<float>((size_t)((P_ + COLSUM_ROWS - 1) / COLSUM_ROWS) * V_);
     }
@@ -130,11 +130,25 @@ class EncoderModel : public Model {
 
   void mlm_forward(hipStream_t st, const PassWeights* w, int nw, int pass_rows, bool kept, const MlmBatch& mb,
                    float* loss_pos) override {
-    const bf16_t* xl = kept ? X_[L_] : X_[L_ & 1];      // bf16 output of the last LayerNorm
-    launch_gather_rows(st, xl, pass_rows, mb.row_base, mb.rows_in_batch, mb.rows, mb.n_mask, P_, d_, nw, hm_);
+    // A kept pass (base step) contracts the bf16 hidden states like every other layer.  The +- passes of Eq. 5 feed
+    // a loss whose difference is the signal: their hidden states enter as the two-term split of the fp32 LayerNorm
+    // output, x_hi (W_hi + W_lo) + x_lo W_hi, so that the rounding of x to bf16 does not bury that difference.
+    if (kept) launch_gather_rows(st, X_[L_], pass_rows, mb.row_base, mb.rows_in_batch, mb.rows, mb.n_mask, P_, d_, nw, hm_);
+    else launch_gather_rows_split(st, res_[0], pass_rows, mb.row_base, mb.rows_in_batch, mb.rows, mb.n_mask, P_, d_, nw, hm_, hm_lo_);
     GemmBf16Args g{};
     g.C32 = zt_;
     fwd_linear(st, w, nw, hm_, d_, wm_, V_, bm_, P_, g);
+    if (!kept) {
+      GemmBf16Args lo[2];
+      for (int k = 0; k < nw; ++k) {
+        lo[k] = GemmBf16Args{};
+        lo[k].A = hm_lo_ + (int64_t)k * P_ * d_; lo[k].lda = d_; lo[k].a_trans = 0;
+        lo[k].B = w[k].hi + wm_; lo[k].ldb = d_; lo[k].b_trans = 1;
+        lo[k].M = P_; lo[k].N = V_; lo[k].K = d_; lo[k].ldc = V_;
+        lo[k].res32 = zt_ + (int64_t)k * P_ * V_; lo[k].C32 = zt_ + (int64_t)k * P_ * V_;   // in place: an element is read and written by the same thread
+      }
+      launch_gemm_bf16_batch(st, lo, nw);
+    }
     launch_mlm_ce(st, zt_, V_, P_, mb.tgt, mb.n_mask, nw, loss_pos, lse_pos_);
   }
 
@@ -250,7 +264,7 @@ class EncoderModel : public Model {
   std::vector<LayerOff> off_;
   int64_t tok_, pos_, eg_, eb_, wc_, bc_, wm_, bm_;
   int P_ = 0;   // masked-token head: padded maximum number of positions
-  bf16_t* hm_ = nullptr; float* zt_ = nullptr; float* lse_pos_ = nullptr; bf16_t* dzt_ = nullptr; float* dhm_ = nullptr;
+  bf16_t* hm_ = nullptr; bf16_t* hm_lo_ = nullptr; float* zt_ = nullptr; float* lse_pos_ = nullptr; bf16_t* dzt_ = nullptr; float* dhm_ = nullptr;
   float* cs_mlm_ = nullptr;
   std::vector<bf16_t*> X_, qkv_, ao_, x1_, fpre_, fact_;
   std::vector<float*> lse_, pre1_, mean1_, rstd1_, pre2_, mean2_, rstd2_;

@@ -198,6 +198,9 @@ void launch_aux_cat(hipStream_t, const int32_t* ids_ft, const int32_t* y_ft, con
 // clamped to [0, rows_in_batch)
 void launch_gather_rows(hipStream_t, const bf16_t* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
                         int n_mask, int P, int d, int nw, bf16_t* out);
+// the same from an fp32 source, as the two-term split hi = bf16(x), lo = bf16(x - hi)
+void launch_gather_rows_split(hipStream_t, const float* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
+                              int n_mask, int P, int d, int nw, bf16_t* hi, bf16_t* lo);
 // loss_pos[k P + j] = logsumexp(Z[k P + j][:V]) - Z[k P + j][tgt[j]], lse_pos likewise (V % 4 == 0)
 void launch_mlm_ce(hipStream_t, const float* Z, int V, int P, const int32_t* tgt, int n_mask, int nw, float* loss_pos,
                    float* lse_pos);

@@ -37,6 +37,27 @@ __global__ __launch_bounds__(128) void k_gather_rows(const bf16_t* X, int pass_r
   }
 }
 
+// The same rows from an fp32 source as a two-term split: hi = bf16(x), lo = bf16(x - hi)  (d % 4 == 0)
+__global__ __launch_bounds__(128) void k_gather_rows_split(const float* X, int pass_rows, int row_base, int rows_in_batch,
+                                                           const int32_t* rows, int n_mask, int P, int d, bf16_t* hi, bf16_t* lo) {
+  const int j = blockIdx.x, k = blockIdx.y;
+  uint2* oh = reinterpret_cast<uint2*>(hi + ((int64_t)k * P + j) * d);
+  uint2* ol = reinterpret_cast<uint2*>(lo + ((int64_t)k * P + j) * d);
+  if (j < n_mask) {
+    const int r = clampi(rows[j], 0, rows_in_batch - 1);
+    const float4* s = reinterpret_cast<const float4*>(X + ((int64_t)k * pass_rows + row_base + r) * d);
+    for (int c = threadIdx.x; c < d / 4; c += 128) {
+      const float4 x = s[c];
+      const uint2 h = make_uint2(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w));
+      oh[c] = h;
+      ol[c] = make_uint2(pack_bf16x2(x.x - bf16_to_f32((bf16_t)h.x), x.y - bf16_to_f32((bf16_t)(h.x >> 16))),
+                         pack_bf16x2(x.z - bf16_to_f32((bf16_t)h.y), x.w - bf16_to_f32((bf16_t)(h.y >> 16))));
+    }
+  } else {
+    for (int c = threadIdx.x; c < d / 4; c += 128) { oh[c] = make_uint2(0u, 0u); ol[c] = make_uint2(0u, 0u); }
+  }
+}
+
 // One workgroup per masked position and pass: a single sweep over the row's V logits keeps a running maximum and
 // the sum of exponentials relative to it in every thread; the 256 pairs are merged in a fixed order.
 __global__ __launch_bounds__(256) void k_mlm_ce(const float* Z, int V, int P, const int32_t* tgt, int n_mask, float* loss_pos,
@@ -110,6 +131,11 @@ void launch_gather_rows(hipStream_t st, const bf16_t* X, int pass_rows, int row_
                         int n_mask, int P, int d, int nw, bf16_t* out) {
   ProfScope ps(st, F_OTHER, 4.0 * nw * P * d);
   k_gather_rows<<<dim3(P, nw), 128, 0, st>>>(X, pass_rows, row_base, rows_in_batch, rows, n_mask, P, d, out);
+}
+void launch_gather_rows_split(hipStream_t st, const float* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
+                              int n_mask, int P, int d, int nw, bf16_t* hi, bf16_t* lo) {
+  ProfScope ps(st, F_OTHER, 8.0 * nw * P * d);
+  k_gather_rows_split<<<dim3(P, nw), 128, 0, st>>>(X, pass_rows, row_base, rows_in_batch, rows, n_mask, P, d, hi, lo);
 }
 void launch_mlm_ce(hipStream_t st, const float* Z, int V, int P, const int32_t* tgt, int n_mask, int nw, float* loss_pos,
                    float* lse_pos) {

@@ -4,7 +4,7 @@ teacher-forced, on a small encoder with a 640-token vocabulary (bf16 GEMM operan
 both sides so that the bar measures the kernels' arithmetic)."""
 import numpy as np
 import pytest
-from datagen import make_workload, make_aux_batch, init_theta, init_lambda, round_to_bf16
+from datagen import make_workload, make_aux_batch, make_aux_workload, AUX_TASK, init_theta, init_lambda, round_to_bf16
 from harness import rel_l2, make_aux_pair, dev_batch, dev_aux_batch, push_state, pull
 
 pytestmark = pytest.mark.gpu
@@ -129,3 +129,40 @@ def test_aux_entry_points_reject_bad_batches():
     with pytest.raises(pkg.SamaError):
         plain.aux_base_step(dev_batch(plain, ft[0], ft[1]), dev_aux_batch(plain, *pt))
     plain.close()
+
+
+def test_aux_full_size_parity():
+    """The configuration `bench.py --aux` times (12 layers, d = 768, 50304-token vocabulary, 16 + 16 sequences): base
+    step 0 from the bf16-representable initial theta at the kernel-arithmetic bar, then one meta step from the oracle's
+    state at the end-to-end bar with nothing snapped."""
+    import time
+    t0 = time.time()
+    n_pt = AUX_TASK["n_pt"]
+    wl = make_aux_workload(n_train=32, n_meta=16)
+    orc, gpu = make_aux_pair(wl, init_theta(wl), init_lambda(wl), max_aux_batch=n_pt, max_aux_masked=n_pt * 26)
+    ft, _ = _ft(wl, 0)
+    pt = make_aux_batch(wl, 0, n_pt)
+    lo = orc.base_step(ft, pt)
+    gpu.aux_base_step(dev_batch(gpu, ft[0], ft[1]), dev_aux_batch(gpu, *pt))
+    g = pull(gpu, "G")
+    errs = _group_errors(orc, g, orc.g)
+    worst = max(errs, key=errs.get)
+    print(f"aux full size: L_base {lo:.3f} rel-L2 g {rel_l2(g, orc.g):.3e}, worst group {worst} {errs[worst]:.1e}, Wmlm "
+          f"{errs['Wmlm']:.1e} bmlm {errs['bmlm']:.1e}  [{time.time() - t0:.0f}s]", flush=True)
+    assert rel_l2(g, orc.g) < KTOL and errs[worst] < 3e-2
+    assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 1e-2 * abs(lo)
+    ft, meta = _ft(wl, 1)
+    pt = make_aux_batch(wl, 1, n_pt)
+    orc.base_step(ft, pt)
+    push_state(orc, gpu)
+    r = orc.meta_step(pt, meta)
+    gpu.aux_meta_step(dev_aux_batch(gpu, *pt), dev_batch(gpu, meta[0], meta[1]))
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+             eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]),
+             theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+    e["fd_signal"] = np.linalg.norm(r["glam_p"] - r["glam_m"]) / np.linalg.norm(r["glam_p"])
+    print("aux full size: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()) + f"  [{time.time() - t0:.0f}s]", flush=True)
+    assert e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL and e["eps"] < TOL and e["gmeta"] < TOL and e["v"] < TOL, e
+    assert int(pull(gpu, "COUNTERS")[2]) == 0
+    gpu.close()
