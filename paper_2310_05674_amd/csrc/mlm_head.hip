@@ -58,52 +58,81 @@ __global__ __launch_bounds__(128) void k_gather_rows_split(const float* X, int p
   }
 }
 
-// One workgroup per masked position and pass: a single sweep over the row's V logits keeps a running maximum and
-// the sum of exponentials relative to it in every thread; the 256 pairs are merged in a fixed order.
-__global__ __launch_bounds__(256) void k_mlm_ce(const float* Z, int V, int P, const int32_t* tgt, int n_mask, float* loss_pos,
-                                                float* lse_pos) {
-  __shared__ float s_m[256];
-  __shared__ float s_s[256];
+// One workgroup of 1024 threads per masked position and pass: a single sweep over the row's V logits, four
+// independent 16-byte loads per thread and trip, keeps a running maximum and the sum of exponentials relative to it in
+// every thread; the 1024 pairs are merged in a fixed order (wave shuffles, then the 16 wave results serially).
+constexpr int CE_THREADS = 1024;
+__device__ __forceinline__ void ce_merge(float& m, float& s, float m2, float s2) {
+  const float mm = fmaxf(m, m2);
+  s = (m == mm ? s : s * __expf(m - mm)) + (m2 == mm ? s2 : s2 * __expf(m2 - mm));   // equal maxima (also -inf) need no scaling
+  m = mm;
+}
+__global__ __launch_bounds__(CE_THREADS) void k_mlm_ce(const float* Z, int V, int P, const int32_t* tgt, int n_mask,
+                                                       float* loss_pos, float* lse_pos) {
+  __shared__ float s_m[CE_THREADS / 64];
+  __shared__ float s_s[CE_THREADS / 64];
   const int j = blockIdx.x, k = blockIdx.y, tid = threadIdx.x;
-  const float* z = Z + ((int64_t)k * P + j) * V;
+  const float4* z4 = reinterpret_cast<const float4*>(Z + ((int64_t)k * P + j) * V);
+  const int n4 = V / 4;                            // V % 4 == 0
   float m = -INFINITY, s = 0.f;
-  for (int c = tid * 4; c < V; c += 1024) {       // V % 4 == 0
-    const float4 q = *reinterpret_cast<const float4*>(z + c);
-    const float qm = fmaxf(fmaxf(q.x, q.y), fmaxf(q.z, q.w));
+  for (int c0 = tid; c0 < n4; c0 += 4 * CE_THREADS) {
+    float4 q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * CE_THREADS;
+      q[u] = c < n4 ? z4[c] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+    float qm = m;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) qm = fmaxf(qm, fmaxf(fmaxf(q[u].x, q[u].y), fmaxf(q[u].z, q[u].w)));
     if (qm > m) { s *= __expf(m - qm); m = qm; }
-    s += __expf(q.x - m) + __expf(q.y - m) + __expf(q.z - m) + __expf(q.w - m);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s += __expf(q[u].x - m) + __expf(q[u].y - m) + __expf(q[u].z - m) + __expf(q[u].w - m);
   }
-  s_m[tid] = m; s_s[tid] = s;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ce_merge(m, s, __shfl_xor(m, o, 64), __shfl_xor(s, o, 64));
+  if ((tid & 63) == 0) { s_m[tid >> 6] = m; s_s[tid >> 6] = s; }
   __syncthreads();
   if (tid == 0) {
     float mm = s_m[0];
-    for (int t = 1; t < 256; ++t) mm = fmaxf(mm, s_m[t]);
+    for (int t = 1; t < CE_THREADS / 64; ++t) mm = fmaxf(mm, s_m[t]);
     double tot = 0.0;
-    for (int t = 0; t < 256; ++t) tot += (double)s_s[t] * exp((double)s_m[t] - (double)mm);
+    for (int t = 0; t < CE_THREADS / 64; ++t) tot += (double)s_s[t] * exp((double)s_m[t] - (double)mm);
     const double lse = log(tot) + (double)mm;
     const int t = clampi(tgt[j], 0, V - 1);
-    loss_pos[k * P + j] = (float)(lse - (double)z[t]);
+    loss_pos[k * P + j] = (float)(lse - (double)Z[((int64_t)k * P + j) * V + t]);
     lse_pos[k * P + j] = (float)lse;
   }
 }
 
 // dZ[j][c] = bf16(coef_j (exp(z_jc - lse_j) - [c == tgt_j])) for j < n_mask, zero rows up to P
-__global__ __launch_bounds__(256) void k_mlm_dz(const float* Z, int V, const int32_t* tgt, const float* coef_pos,
-                                                const float* lse_pos, int n_mask, bf16_t* dZ) {
+__global__ __launch_bounds__(CE_THREADS) void k_mlm_dz(const float* Z, int V, const int32_t* tgt, const float* coef_pos,
+                                                       const float* lse_pos, int n_mask, bf16_t* dZ) {
   const int j = blockIdx.x, tid = threadIdx.x;
   uint2* o = reinterpret_cast<uint2*>(dZ + (int64_t)j * V);
+  const int n4 = V / 4;
   if (j >= n_mask) {
-    for (int c = tid; c < V / 4; c += 256) o[c] = make_uint2(0u, 0u);
+    for (int c = tid; c < n4; c += CE_THREADS) o[c] = make_uint2(0u, 0u);
     return;
   }
-  const float* z = Z + (int64_t)j * V;
+  const float4* z4 = reinterpret_cast<const float4*>(Z + (int64_t)j * V);
   const float coef = coef_pos[j], lse = lse_pos[j];
   const int t = clampi(tgt[j], 0, V - 1);
-  for (int c = tid; c < V / 4; c += 256) {
-    const float4 q = *reinterpret_cast<const float4*>(z + 4 * c);
-    float p[4] = {__expf(q.x - lse), __expf(q.y - lse), __expf(q.z - lse), __expf(q.w - lse)};
-    if ((t >> 2) == c) p[t & 3] -= 1.f;
-    o[c] = make_uint2(pack_bf16x2(coef * p[0], coef * p[1]), pack_bf16x2(coef * p[2], coef * p[3]));
+  for (int c0 = tid; c0 < n4; c0 += 4 * CE_THREADS) {
+    float4 q[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * CE_THREADS;
+      q[u] = c < n4 ? z4[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * CE_THREADS;
+      if (c >= n4) break;
+      float p[4] = {__expf(q[u].x - lse), __expf(q[u].y - lse), __expf(q[u].z - lse), __expf(q[u].w - lse)};
+      if ((t >> 2) == c) p[t & 3] -= 1.f;
+      o[c] = make_uint2(pack_bf16x2(coef * p[0], coef * p[1]), pack_bf16x2(coef * p[2], coef * p[3]));
+    }
   }
 }
 
@@ -140,12 +169,12 @@ void launch_gather_rows_split(hipStream_t st, const float* X, int pass_rows, int
 void launch_mlm_ce(hipStream_t st, const float* Z, int V, int P, const int32_t* tgt, int n_mask, int nw, float* loss_pos,
                    float* lse_pos) {
   ProfScope ps(st, F_MLM_SOFTMAX, 4.0 * nw * n_mask * (double)V);
-  k_mlm_ce<<<dim3(n_mask, nw), 256, 0, st>>>(Z, V, P, tgt, n_mask, loss_pos, lse_pos);
+  k_mlm_ce<<<dim3(n_mask, nw), CE_THREADS, 0, st>>>(Z, V, P, tgt, n_mask, loss_pos, lse_pos);
 }
 void launch_mlm_dz(hipStream_t st, const float* Z, int V, const int32_t* tgt, const float* coef_pos, const float* lse_pos,
                    int n_mask, int P, bf16_t* dZ) {
   ProfScope ps(st, F_MLM_SOFTMAX, 6.0 * n_mask * (double)V + 2.0 * (P - n_mask) * (double)V);
-  k_mlm_dz<<<P, 256, 0, st>>>(Z, V, tgt, coef_pos, lse_pos, n_mask, dZ);
+  k_mlm_dz<<<P, CE_THREADS, 0, st>>>(Z, V, tgt, coef_pos, lse_pos, n_mask, dZ);
 }
 void launch_scatter_add_rows(hipStream_t st, const float* part, int nparts, int64_t part_stride, int row_base, int rows_in_batch,
                              const int32_t* rows, int n_mask, int d, float* dx) {

@@ -52,18 +52,23 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
 
   double lsum = 0.0;
   float* s_cnt = s_lc;                                  // sequence mode: positions per sequence (the corrector is off)
-  for (int i = tid; seq_mode && i < B; i += 256) {
+  // wave w takes sequences w, w + 4, ...: its lanes stride over the positions (coalesced), keep the matching losses,
+  // and a shuffle tree adds the 64 partial sums in a fixed order
+  for (int i = tid >> 6; seq_mode && i < B; i += 4) {
     double acc = 0.0, n_i = 0.0;
-    for (int j = 0; j < a.n_pos; ++j) {
+    for (int j = tid & 63; j < a.n_pos; j += 64) {
       int r = a.pos_row[j];
       r = r < 0 ? 0 : (r >= B * a.S ? B * a.S - 1 : r);
       if (r / a.S == i) { acc += (double)a.pos_loss[j]; n_i += 1.0; }
     }
-    const double l = n_i > 0.0 ? acc / n_i : 0.0;
+    for (int o = 32; o > 0; o >>= 1) { acc += __shfl_xor(acc, o, 64); n_i += __shfl_xor(n_i, o, 64); }
+    if ((tid & 63) == 0) { s_l[i] = n_i > 0.0 ? acc / n_i : 0.0; s_cnt[i] = (float)n_i; }
+  }
+  if (seq_mode) __syncthreads();
+  for (int i = tid; seq_mode && i < B; i += 256) {
+    const double l = s_l[i];
     const double mk = (a.mask == nullptr || a.mask[i] != 0) ? 1.0 : 0.0;
     a.losses[i] = (float)l;
-    s_l[i] = l;
-    s_cnt[i] = (float)n_i;
     double zz = b2;
     for (int h = 0; h < H; ++h) zz += (double)W2[h] * fmax((double)W1[h] * l + (double)b1[h], 0.0);
     const double w = 1.0 / (1.0 + exp(-zz));
