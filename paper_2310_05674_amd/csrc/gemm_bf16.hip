@@ -356,15 +356,16 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
     }
   };
   const bool side = res32 != nullptr || res16 != nullptr || act == GEMM_ACT_GELU_BWD;
+  constexpr bool PREFETCH = NIT <= 8;   // wider wave tiles have no registers to spare for the side inputs of a whole slice
 #pragma unroll
   for (int x = 0; x < XT; ++x) {
     // Side inputs of this 32-row slice (residual, saved pre-activation) are requested before the accumulators go
     // through LDS, so that their latency hides behind the staging.  Launches without side inputs skip this path.
-    float4 r32[NIT];
-    uint2 r16[NIT], ax[NIT];
-    if (side && col_ok) {
+    float4 r32[PREFETCH ? NIT : 1];
+    uint2 r16[PREFETCH ? NIT : 1], ax[PREFETCH ? NIT : 1];
+    if (PREFETCH && side && col_ok) {
 #pragma unroll
-      for (int itr = 0; itr < NIT; ++itr) {
+      for (int itr = 0; itr < (PREFETCH ? NIT : 1); ++itr) {
         const int gi = i0 + wr + x * 32 + rq + RPP * itr;
         r32[itr] = make_float4(0.f, 0.f, 0.f, 0.f); r16[itr] = make_uint2(0u, 0u); ax[itr] = make_uint2(0u, 0u);
         if (gi < Mrows) {
@@ -384,12 +385,25 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
         epi[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * EPI_LD + y * 32 + (lane & 31)] = acc[x][y][r];
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     if (!col_ok) continue;
-    if (side) {
+    if (side && PREFETCH) {
 #pragma unroll
-      for (int itr = 0; itr < NIT; ++itr) {
+      for (int itr = 0; itr < (PREFETCH ? NIT : 1); ++itr) {
         const int row = rq + RPP * itr, gi = i0 + wr + x * 32 + row;
         if (gi >= Mrows) break;
         finish(*reinterpret_cast<const float4*>(epi + row * EPI_LD + 4 * cg), (int64_t)gi * ldc + gj, r32[itr], r16[itr], ax[itr]);
+      }
+    } else if (side) {
+#pragma unroll 4
+      for (int itr = 0; itr < NIT; ++itr) {
+        const int row = rq + RPP * itr, gi = i0 + wr + x * 32 + row;
+        if (gi >= Mrows) break;
+        const int64_t o = (int64_t)gi * ldc + gj;
+        float4 q32 = make_float4(0.f, 0.f, 0.f, 0.f);
+        uint2 q16 = make_uint2(0u, 0u), qa = make_uint2(0u, 0u);
+        if (res32 != nullptr) q32 = *reinterpret_cast<const float4*>(res32 + o);
+        if (res16 != nullptr) q16 = *reinterpret_cast<const uint2*>(res16 + o);
+        if (act == GEMM_ACT_GELU_BWD) qa = *reinterpret_cast<const uint2*>(aux16 + o);
+        finish(*reinterpret_cast<const float4*>(epi + row * EPI_LD + 4 * cg), o, q32, q16, qa);
       }
     } else {
       const float4 z4 = make_float4(0.f, 0.f, 0.f, 0.f);
