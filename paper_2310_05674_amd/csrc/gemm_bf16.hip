@@ -270,26 +270,6 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       for (int y = 0; y < YT; ++y) bw[buf][y] = fetchB(sb + T::B_BYTES, y, ks);
     }
   };
-#ifdef GEMM_SIMPLE_LOOP
-  // experiment: no manual operand double buffer and no scheduling fences; the compiler orders reads and MFMAs
-  for (int i = 0; i < iters; ++i) {
-    arrive(i);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      fetch(i, ks, ks & 1);
-#pragma unroll
-      for (int x = 0; x < XT; ++x)
-#pragma unroll
-        for (int y = 0; y < YT; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks & 1][x], bv[ks & 1][y], acc[x][y], 0, 0, 0);
-      if (DUAL) {
-#pragma unroll
-        for (int x = 0; x < XT; ++x)
-#pragma unroll
-          for (int y = 0; y < YT; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks & 1][x], bw[ks & 1][y], acc[x][y], 0, 0, 0);
-      }
-    }
-  }
-#else
   arrive(0);
   fetch(0, 0, 0);
   auto mfma_step = [&](int cur) {
@@ -325,7 +305,6 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
     if (ks + 1 < KS) fetch(iters - 1, ks + 1, (ks & 1) ^ 1);
     mfma_step(ks & 1);
   }
-#endif
   __syncthreads();
 
   // ---- epilogue: accumulators -> LDS (per wave, 32 x WN fp32 at a time) -> row-contiguous global accesses
