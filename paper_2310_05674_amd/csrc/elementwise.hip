@@ -375,6 +375,18 @@ void launch_adapt_norm(hipStream_t st, const float* g, const float* m, const flo
   k_adapt_norm<<<grid, EW_THREADS, 0, st>>>(g, m, v, gmeta, vdir, partial, n, a);
   k_eps_from_partials<<<1, 256, 0, st>>>(partial, grid, alpha, scalars, status);
 }
+int launch_adapt_slice(hipStream_t st, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
+                       double* partial, int64_t n, const AdaptArgs& a, int max_blocks) {
+  if (n <= 0) return 0;
+  int grid = ew_grid(n);
+  if (grid > max_blocks) grid = max_blocks;
+  ProfScope ps(st, F_ADAPT_NORM, (a.mode == 0 ? 20.0 : 8.0) * n);
+  k_adapt_norm<<<grid, EW_THREADS, 0, st>>>(g, m, v, gmeta, vdir, partial, n, a);
+  return grid;
+}
+void launch_eps_from_partials(hipStream_t st, const double* partial, int count, float alpha, float* scalars, int64_t* status) {
+  k_eps_from_partials<<<1, 256, 0, st>>>(partial, count, alpha, scalars, status);
+}
 void launch_perturb_lo(hipStream_t st, const float* theta, const float* vdir, const float* eps_ptr, bf16_t* lo_p,
                        bf16_t* lo_m, int64_t n16) {
   if (n16 <= 0) return;

@@ -5,7 +5,11 @@
 #include "model.h"
 
 namespace sama {
+static bool g_side_stream = true, g_side_sink = true;
+void encoder_side_stream(bool on) { g_side_stream = on; }
+void encoder_side_sink(bool on) { g_side_sink = on; }
 namespace {
+inline bool side_enabled() { return g_side_stream; }
 
 struct LayerOff { int64_t Wqkv, Wo, W1, W2, bqkv, bo, ln1g, ln1b, b1, b2, ln2g, ln2b; };
 
@@ -44,12 +48,19 @@ class EncoderModel : public Model {
     pre0_ = ws.take<float>(M * d_); mean0_ = ws.take<float>(M); rstd0_ = ws.take<float>(M);
     dX_[0] = ws.take<float>(M * d_); dX_[1] = ws.take<float>(M * d_);
     res_[0] = ws.take<float>(2 * M * d_); res_[1] = ws.take<float>(2 * M * d_);
-    ds32_ = ws.take<float>(M * d_); ds16_[0] = ws.take<bf16_t>(M * d_); ds16_[1] = ws.take<bf16_t>(M * d_);
-    dpre_ = ws.take<bf16_t>(M * ffn_); do_ = ws.take<bf16_t>(M * d_); dqkv_ = ws.take<bf16_t>(M * 3 * d_);
+    ds32_ = ws.take<float>(M * d_); do_ = ws.take<bf16_t>(M * d_);
+    // What a layer's weight-gradient launches read exists twice (layer parity): they run on a second stream while the
+    // next layer's backward chain already writes the other set.
+    for (int p = 0; p < 2; ++p) {
+      ds16_[p][0] = ws.take<bf16_t>(M * d_); ds16_[p][1] = ws.take<bf16_t>(M * d_);
+      dpre_[p] = ws.take<bf16_t>(M * ffn_); dqkv_[p] = ws.take<bf16_t>(M * 3 * d_);
+    }
     const size_t nblk = (M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
     const size_t wide = (size_t)(3 * d_ > ffn_ ? 3 * d_ : ffn_);
-    lnpart_[0] = ws.take<float>(nblk * 3 * d_); lnpart_[1] = ws.take<float>(nblk * 3 * d_);
-    cspart_[0] = ws.take<float>(nrb * wide); cspart_[1] = ws.take<float>(nrb * wide);
+    for (int p = 0; p < 2; ++p) {
+      lnpart_[p][0] = ws.take<float>(nblk * 3 * d_); lnpart_[p][1] = ws.take<float>(nblk * 3 * d_);
+      cspart_[p][0] = ws.take<float>(nrb * wide); cspart_[p][1] = ws.take<float>(nrb * wide);
+    }
     if (has_mlm()) {   // masked-token head: P_ positions (a multiple of 64, zero rows beyond the batch's), two stacked passes
       hm_ = ws.take<bf16_t>((size_t)2 * P_ * d_); hm_lo_ = ws.take<bf16_t>((size_t)2 * P_ * d_); zt_ = ws.take<float>((size_t)2 * P_ * V_); lse_pos_ = ws.take<float>((size_t)2 * P_);
       dzt_ = ws.take<bf16_t>((size_t)P_ * V_); dhm_ = ws.take<float>((size_t)GEMM_MAX_BATCH * P_ * d_);
@@ -211,53 +222,102 @@ class EncoderModel : public Model {
       launch_fill_f32(st, grad + wm_, 0.f, (int64_t)V_ * d_);
       launch_fill_f32(st, grad + bm_, 0.f, V_);
     }
+    // The layer's four weight gradients, its two bias column sums and its four small reductions leave in three
+    // launches at the end of the layer, on a second stream of the same priority: nothing in the backward chain
+    // depends on them, and the chain's launches (small dgrad tiles, LayerNorm, attention) leave room on the CUs.
+    // Their inputs alternate between two buffer sets; the chain waits for the launches of two layers ago before it
+    // overwrites a set, and the pass ends with both streams joined.
+    const bool two = side_enabled() && ensure_side();
+    hipStream_t ss = two ? side_ : st;
+    bool sink_used = false;
     for (int l = L_ - 1; l >= 0; --l) {
       const LayerOff& o = off_[l];
-      // The layer's four weight gradients, its two bias column sums and its four small reductions wait for the
-      // end of the layer and leave in three launches.
+      const int p = l & 1;
+      if (two && side_busy_[p]) { (void)hipStreamWaitEvent(st, ev_side_[p], 0); side_busy_[p] = false; }
+      bf16_t* const ds2 = ds16_[p][0]; bf16_t* const ds1 = ds16_[p][1]; bf16_t* const dpre = dpre_[p]; bf16_t* const dqkv = dqkv_[p];
       GemmBf16Args wg[4];
       // LN2
-      LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds16_[0], lnpart_[0], M, d_};
+      LnBwdArgs n2{dx, pre2_[l], mean2_[l], rstd2_[l], w.theta + o.ln2g, ds32_, ds2, lnpart_[p][0], M, d_};
       launch_ln_bwd(st, n2);
       // FFN
-      wg[0] = wgrad(ds16_[0], d_, fact_[l], ffn_, M, grad + o.W2);
-      GemmBf16Args g = dgrad(w, ds16_[0], d_, o.W2, ffn_, M);
-      g.act = GEMM_ACT_GELU_BWD; g.aux16 = fpre_[l]; g.C16 = dpre_;
+      wg[0] = wgrad(ds2, d_, fact_[l], ffn_, M, grad + o.W2);
+      GemmBf16Args g = dgrad(w, ds2, d_, o.W2, ffn_, M);
+      g.act = GEMM_ACT_GELU_BWD; g.aux16 = fpre_[l]; g.C16 = dpre;
       launch_gemm_bf16(st, g);
-      wg[1] = wgrad(dpre_, ffn_, x1_[l], d_, M, grad + o.W1);
-      g = dgrad(w, dpre_, ffn_, o.W1, d_, M);
+      wg[1] = wgrad(dpre, ffn_, x1_[l], d_, M, grad + o.W1);
+      g = dgrad(w, dpre, ffn_, o.W1, d_, M);
       g.res32 = ds32_; g.C32 = dx_next;                       // + the residual branch
       launch_gemm_bf16(st, g);
       // LN1
-      LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds16_[1], lnpart_[1], M, d_};
+      LnBwdArgs n1{dx_next, pre1_[l], mean1_[l], rstd1_[l], w.theta + o.ln1g, ds32_, ds1, lnpart_[p][1], M, d_};
       launch_ln_bwd(st, n1);
       // attention
-      wg[2] = wgrad(ds16_[1], d_, ao_[l], d_, M, grad + o.Wo);
-      g = dgrad(w, ds16_[1], d_, o.Wo, d_, M);
+      wg[2] = wgrad(ds1, d_, ao_[l], d_, M, grad + o.Wo);
+      g = dgrad(w, ds1, d_, o.Wo, d_, M);
       g.C16 = do_;
       launch_gemm_bf16(st, g);
-      launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv_, B, heads_, d_);
-      wg[3] = wgrad(dqkv_, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
-      g = dgrad(w, dqkv_, 3 * d_, o.Wqkv, d_, M);
+      launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv, B, heads_, d_);
+      wg[3] = wgrad(dqkv, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
+      g = dgrad(w, dqkv, 3 * d_, o.Wqkv, d_, M);
       g.res32 = ds32_; g.C32 = dx;                            // gradient w.r.t. the layer input
+      if (two) {   // everything the side launches read is written by now (the last dgrad only reads dqkv)
+        (void)hipEventRecord(ev_chain_[p], st);
+        (void)hipStreamWaitEvent(side_, ev_chain_[p], 0);
+      }
       launch_gemm_bf16(st, g);
-      launch_gemm_bf16_batch(st, wg, 4);
-      const ColsumJob cj[2] = {{dpre_, M, ffn_, cspart_[0]}, {dqkv_, M, 3 * d_, cspart_[1]}};
-      launch_colsum_partial_multi(st, cj, 2);
+      const bool sink_now = two && g_side_sink && sink_ != nullptr;
+      if (sink_now) (void)hipEventRecord(ev_last_[p], st);   // behind the layer's last read of its own weights
+      launch_gemm_bf16_batch(ss, wg, 4);
+      const ColsumJob cj[2] = {{dpre, M, ffn_, cspart_[p][0]}, {dqkv, M, 3 * d_, cspart_[p][1]}};
+      launch_colsum_partial_multi(ss, cj, 2);
       const int nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
       const ReduceRowsJob rj[4] = {
-          {lnpart_[0], nblk, 3 * d_, d_, d_, {grad + o.ln2g, grad + o.ln2b, grad + o.b2}},
-          {lnpart_[1], nblk, 3 * d_, d_, d_, {grad + o.ln1g, grad + o.ln1b, grad + o.bo}},
-          {cspart_[0], nrb, ffn_, 0, ffn_, {grad + o.b1, nullptr, nullptr}},
-          {cspart_[1], nrb, 3 * d_, 0, 3 * d_, {grad + o.bqkv, nullptr, nullptr}}};
-      launch_reduce_rows_multi(st, rj, 4);
+          {lnpart_[p][0], nblk, 3 * d_, d_, d_, {grad + o.ln2g, grad + o.ln2b, grad + o.b2}},
+          {lnpart_[p][1], nblk, 3 * d_, d_, d_, {grad + o.ln1g, grad + o.ln1b, grad + o.bo}},
+          {cspart_[p][0], nrb, ffn_, 0, ffn_, {grad + o.b1, nullptr, nullptr}},
+          {cspart_[p][1], nrb, 3 * d_, 0, 3 * d_, {grad + o.bqkv, nullptr, nullptr}}};
+      launch_reduce_rows_multi(ss, rj, 4);
+      if (two) { (void)hipEventRecord(ev_side_[p], side_); side_busy_[p] = true; }
+      if (sink_now) {   // this layer's gradients are final (matrices and vectors are one range each); a consumer may
+        (void)hipStreamWaitEvent(side_, ev_last_[p], 0);   // overwrite the layer's weights once its last dgrad has read them
+        sink_->ready(side_, o.Wqkv, (int64_t)4 * d_ * d_ + (int64_t)2 * ffn_ * d_);
+        sink_->ready(side_, o.bqkv, (int64_t)9 * d_ + ffn_);
+        sink_used = true;
+      }
     }
-    LnBwdArgs n0{dx, pre0_, mean0_, rstd0_, w.theta + eg_, ds32_, nullptr, lnpart_[0], M, d_};
+    if (sink_used) { (void)hipEventRecord(ev_side_[0], side_); side_busy_[0] = true; }   // join behind the consumer's work too
+    for (int p = 0; p < 2; ++p)
+      if (two && side_busy_[p]) { (void)hipStreamWaitEvent(st, ev_side_[p], 0); side_busy_[p] = false; }
+    LnBwdArgs n0{dx, pre0_, mean0_, rstd0_, w.theta + eg_, ds32_, nullptr, lnpart_[0][0], M, d_};
     launch_ln_bwd(st, n0);
-    launch_reduce_rows(st, lnpart_[0], nblk, 3 * d_, d_, d_, grad + eg_, grad + eb_, nullptr);
+    launch_reduce_rows(st, lnpart_[0][0], nblk, 3 * d_, d_, d_, grad + eg_, grad + eb_, nullptr);
     launch_fill_f32(st, grad + tok_, 0.f, (int64_t)V_ * d_);
     launch_embedding_bwd(st, ds32_, (const int32_t*)b.x, B, S_, d_, grad + tok_, grad + pos_);
   }
+
+  // second stream (default priority, created at the first backward pass) and the events that order it
+  bool ensure_side() {
+    if (side_ != nullptr) return true;
+    if (side_failed_) return false;
+    bool ok = hipStreamCreateWithFlags(&side_, hipStreamNonBlocking) == hipSuccess;
+    for (int p = 0; p < 2 && ok; ++p)
+      ok = hipEventCreateWithFlags(&ev_chain_[p], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&ev_side_[p], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&ev_last_[p], hipEventDisableTiming) == hipSuccess;
+    if (!ok) { release_side(); side_failed_ = true; (void)hipGetLastError(); }
+    return ok;
+  }
+  void release_side() {
+    for (int p = 0; p < 2; ++p) {
+      if (ev_chain_[p]) (void)hipEventDestroy(ev_chain_[p]);
+      if (ev_side_[p]) (void)hipEventDestroy(ev_side_[p]);
+      if (ev_last_[p]) (void)hipEventDestroy(ev_last_[p]);
+      ev_chain_[p] = ev_side_[p] = ev_last_[p] = nullptr;
+    }
+    if (side_) (void)hipStreamDestroy(side_);
+    side_ = nullptr;
+  }
+  ~EncoderModel() override { release_side(); }
 
  private:
   int L_, d_, heads_, ffn_, S_, V_, C_;
@@ -271,8 +331,11 @@ class EncoderModel : public Model {
   float *pre0_ = nullptr, *mean0_ = nullptr, *rstd0_ = nullptr;
   float* dX_[2] = {nullptr, nullptr};
   float* res_[2] = {nullptr, nullptr};   // fp32 LayerNorm outputs: the residual stream of the current forward pass
-  float* ds32_ = nullptr; bf16_t* ds16_[2] = {nullptr, nullptr}; bf16_t* dpre_ = nullptr; bf16_t* do_ = nullptr; bf16_t* dqkv_ = nullptr;
-  float* lnpart_[2] = {nullptr, nullptr}; float* cspart_[2] = {nullptr, nullptr};
+  float* ds32_ = nullptr; bf16_t* do_ = nullptr;
+  bf16_t* ds16_[2][2] = {}; bf16_t* dpre_[2] = {}; bf16_t* dqkv_[2] = {};   // [layer parity]
+  float* lnpart_[2][2] = {}; float* cspart_[2][2] = {};
+  hipStream_t side_ = nullptr; hipEvent_t ev_chain_[2] = {}, ev_side_[2] = {}, ev_last_[2] = {};
+  bool side_busy_[2] = {false, false}, side_failed_ = false;
 };
 }  // namespace
 

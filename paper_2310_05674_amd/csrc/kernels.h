@@ -49,6 +49,11 @@ void launch_sgd(hipStream_t, const float* g, float* theta, bf16_t* theta16, int6
 void launch_adapt_norm(hipStream_t, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
                        double* partial /*[EW_MAX_BLOCKS]*/, int64_t n, const AdaptArgs&, float alpha, float* scalars,
                        int64_t* status);
+// The same in pieces: v = D . gmeta over one range, its per-block sums of squares into partial[0 .. returned count)
+// (at most max_blocks), and, once every range is done, eps and the status word from all the partials in index order.
+int launch_adapt_slice(hipStream_t, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
+                       double* partial, int64_t n, const AdaptArgs&, int max_blocks);
+void launch_eps_from_partials(hipStream_t, const double* partial, int count, float alpha, float* scalars, int64_t* status);
 void launch_perturb_lo(hipStream_t, const float* theta, const float* vdir, const float* eps_ptr, bf16_t* lo_p,
                        bf16_t* lo_m, int64_t n16);
 // perturb_lo and the nudge of the first n16 elements (n16 % 4 == 0) in one pass: theta, theta16 <- theta - eps v,
@@ -140,6 +145,8 @@ void launch_gemm_bf16(hipStream_t, const GemmBf16Args&);
 constexpr int GEMM_MAX_BATCH = 4;
 const char* check_gemm_bf16_batch(const GemmBf16Args* p, int count);
 void launch_gemm_bf16_batch(hipStream_t, const GemmBf16Args* p, int count);
+void encoder_side_sink(bool on);         // tuning hook: per-layer gradient consumers on that stream (default on)
+void encoder_side_stream(bool on);      // tuning hook: weight-gradient launches on a second stream (default on)
 void gemm_bf16_force_shape(int shape);  // tuning hook: 0 = heuristic, else 100 * tile-order group + tile configuration id
 
 // ------------------------------------------------------------------ encoder ops (encoder_ops.hip)

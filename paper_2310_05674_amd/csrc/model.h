@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string>
+#include <utility>
 #include <vector>
 #include "../../include/sama.h"
 #include "common.h"
@@ -55,9 +56,20 @@ struct MlmBatch {
   int rows_in_batch;    // token rows of the auxiliary sequences (n_pt * S)
 };
 
+// A consumer of finished gradient ranges.  A model that runs part of its backward pass on a stream of its own may
+// call ready() there as soon as grad[off, off + count) is final, so that the consumer's work on that range (the
+// optimizer update of a layer) overlaps with the rest of the pass; the consumer may overwrite the parameters of that
+// range (the pass no longer reads them).  Everything enqueued by ready() is complete, in stream order, when the
+// stream backward() was called with continues after the pass.  Ranges never reported are the caller's to handle.
+struct GradSink {
+  virtual ~GradSink() {}
+  virtual void ready(hipStream_t s, int64_t off, int64_t count) = 0;
+};
+
 class Model {
  public:
   virtual ~Model() {}
+  void set_grad_sink(GradSink* s) { sink_ = s; }   // for the next backward() / backward_mlm(); null = none
   // carve activation buffers for batches up to max_b
   virtual void plan(BumpAlloc& ws, int max_b) = 0;
   // logits[B x C] (fp32, row stride C) for batch `b`; keep = retain what backward needs
@@ -82,6 +94,8 @@ class Model {
   // kept forward and mlm_forward on the same batch
   virtual void backward_mlm(hipStream_t, const PassWeights&, const sama_batch&, const float* /*dlogits*/, float* /*grad*/,
                             const MlmBatch&, const float* /*coef_pos*/) {}
+ protected:
+  GradSink* sink_ = nullptr;
 };
 
 Model* make_mlp(const sama_config& cfg, const std::vector<TensorInfo>& layout);

@@ -9,6 +9,9 @@ extern "C" {
 
 // Tuning hook (not declared in the public headers): block shape of the bf16 GEMM, 0 = heuristic.
 void sama_dev_gemm_shape(int32_t shape) { gemm_bf16_force_shape(shape); }
+// Tuning hook: 0 keeps every launch of the encoder's backward pass on the context's stream.
+void sama_dev_side_stream(int32_t on) { encoder_side_stream(on != 0); }
+void sama_dev_side_sink(int32_t on) { encoder_side_sink(on != 0); }
 
 sama_status sama_op_gemm_bf16(const void* A, int64_t lda, int32_t a_trans, const void* B, const void* B2, int64_t ldb,
                               int32_t b_trans, int32_t M, int32_t N, int32_t K, const float* bias, float* C32, void* C16,

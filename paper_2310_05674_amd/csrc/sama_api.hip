@@ -3,7 +3,10 @@
 #include <math.h>
 #include <stdio.h>
 #include <string.h>
+#include <algorithm>
 #include <memory>
+#include <utility>
+#include <vector>
 #include "kernels.h"
 #include "model.h"
 
@@ -182,6 +185,69 @@ static sama_status check_batch(sama_ctx* c, const sama_batch* b, int maxb, const
   return SAMA_OK;
 }
 
+// The base solver's update (App. C for Adam) of theta[off, off + count) with the gradient in c->g, for step number t.
+static void base_update_range(sama_ctx* c, hipStream_t st, int64_t t, int64_t off, int64_t count) {
+  if (count <= 0) return;
+  const sama_config& f = c->cfg;
+  const int64_t n16 = off < c->n_gemm ? (off + count <= c->n_gemm ? count : c->n_gemm - off) : 0;   // leading part with a bf16 copy
+  bf16_t* t16 = (c->theta16 != nullptr && n16 > 0) ? c->theta16 + off : nullptr;
+  if (f.base_opt == SAMA_OPT_ADAM) {
+    AdamArgs a{};
+    a.beta1 = f.beta1; a.one_m_beta1 = (float)(1.0 - (double)f.beta1);
+    a.beta2 = f.beta2; a.one_m_beta2 = (float)(1.0 - (double)f.beta2);
+    a.lr_c1 = (float)((double)f.base_lr / (1.0 - pow((double)f.beta1, (double)t)));
+    a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)f.beta2, (double)t)));
+    a.eps = f.adam_eps; a.weight_decay = f.weight_decay;
+    launch_adam(st, c->g + off, c->m + off, c->v + off, c->theta + off, t16, count, n16, a);
+  } else {
+    launch_sgd(st, c->g + off, c->theta + off, t16, count, n16, f.base_lr, f.weight_decay);
+  }
+}
+
+// Updates the ranges of theta whose gradients the model reports final while its backward pass still runs.
+struct UpdateSink : GradSink {
+  sama_ctx* c; int64_t t;
+  std::vector<std::pair<int64_t, int64_t>> done;
+  UpdateSink(sama_ctx* c_, int64_t t_) : c(c_), t(t_) {}
+  void ready(hipStream_t s, int64_t off, int64_t count) override {
+    if (off % 4 != 0 || count % 4 != 0 || off < 0 || off + count > c->n) return;   // left to the pass over the rest
+    base_update_range(c, s, t, off, count);
+    done.push_back({off, count});
+  }
+};
+
+// Everything the sink has not updated, on the context's stream; advances the step count.
+static void base_update_rest(sama_ctx* c, UpdateSink& sink) {
+  hipStream_t st = c->stream;
+  std::sort(sink.done.begin(), sink.done.end());
+  int64_t pos = 0;
+  for (auto& r : sink.done) {   // gaps start where a reported range ends (a multiple of 4) or at 0: vector-aligned
+    if (r.first > pos) base_update_range(c, st, sink.t, pos, r.first - pos);
+    pos = r.first + r.second;
+  }
+  if (pos < c->n) base_update_range(c, st, sink.t, pos, c->n - pos);
+  c->t = sink.t;
+  launch_fill_i64x4(st, c->counters, c->t, 0, 0, 0, 1);
+}
+
+// v = D . g_meta and the partial sums of ||v||^2 for the ranges of g_meta the model reports final during its backward
+// pass; the partials of successive ranges follow each other in c->partial.
+struct AdaptSink : GradSink {
+  sama_ctx* c; AdaptArgs ad;
+  std::vector<std::pair<int64_t, int64_t>> done;
+  int used = 0;                                   // partials handed out so far
+  static constexpr int SLICE_BLOCKS = 1024;       // per reported range; leaves most of the EW_MAX_BLOCKS partials to the rest
+  AdaptSink(sama_ctx* c_, const AdaptArgs& a) : c(c_), ad(a) {}
+  void slice(hipStream_t s, int64_t off, int64_t count, int max_blocks) {
+    used += launch_adapt_slice(s, c->g + off, c->m + off, c->v + off, c->gmeta + off, c->vdir + off, c->partial + used, count, ad, max_blocks);
+  }
+  void ready(hipStream_t s, int64_t off, int64_t count) override {
+    if (off % 4 != 0 || count % 4 != 0 || off < 0 || off + count > c->n || used + SLICE_BLOCKS > EW_MAX_BLOCKS / 2) return;
+    slice(s, off, count, SLICE_BLOCKS);
+    done.push_back({off, count});
+  }
+};
+
 extern "C" {
 
 int64_t sama_param_count(const sama_config* cfg) {
@@ -260,8 +326,6 @@ static PassWeights pass_weights(sama_ctx* c, float sign) {
   return w;
 }
 
-static void base_update(sama_ctx* c);
-
 sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out) {
   if (!c) return SAMA_EINVAL;
   sama_status s = check_batch(c, train, c->cfg.max_batch, "train");
@@ -275,28 +339,12 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
   sa.mode = STAGE_BASE; sa.Hc = c->cfg.corr_hidden; sa.kappa = c->cfg.corr_kappa; sa.y = train->y; sa.mask = train->sample_mask; sa.lambda = c->lambda;
   sa.losses = c->losses; sa.dlogits = c->dlogits; sa.loss_scalar = c->scalars + 2; sa.loss_user = loss_out;
   launch_sample_stage(st, sa);
+  UpdateSink sink(c, c->t + 1);
+  c->model->set_grad_sink(&sink);
   c->model->backward(st, w, *train, c->dlogits, c->g);
-  base_update(c);
+  c->model->set_grad_sink(nullptr);
+  base_update_rest(c, sink);
   return check_hip(c, "sama_base_step");
-}
-
-// the base solver's update with the gradient in c->g (App. C for Adam); advances the step count
-static void base_update(sama_ctx* c) {
-  hipStream_t st = c->stream;
-  c->t += 1;
-  const sama_config& f = c->cfg;
-  if (f.base_opt == SAMA_OPT_ADAM) {
-    AdamArgs a{};
-    a.beta1 = f.beta1; a.one_m_beta1 = (float)(1.0 - (double)f.beta1);
-    a.beta2 = f.beta2; a.one_m_beta2 = (float)(1.0 - (double)f.beta2);
-    a.lr_c1 = (float)((double)f.base_lr / (1.0 - pow((double)f.beta1, (double)c->t)));
-    a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t)));
-    a.eps = f.adam_eps; a.weight_decay = f.weight_decay;
-    launch_adam(st, c->g, c->m, c->v, c->theta, c->theta16, c->n, c->n_gemm, a);
-  } else {
-    launch_sgd(st, c->g, c->theta, c->theta16, c->n, c->n_gemm, f.base_lr, f.weight_decay);
-  }
-  launch_fill_i64x4(st, c->counters, c->t, 0, 0, 0, 1);
 }
 
 // First half of a meta gradient: g_meta = dL_meta/dtheta on the clean batch (Eq. 1), v = (du/dg) . g_meta,
@@ -317,7 +365,6 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
   sa.y = meta->y; sa.mask = meta->sample_mask; sa.lambda = c->lambda; sa.losses = c->losses; sa.dlogits = c->dlogits;
   sa.loss_scalar = c->scalars + 3;
   launch_sample_stage(st, sa);
-  c->model->backward(st, w0, *meta, c->dlogits, c->gmeta);
   AdaptArgs ad{};
   if (f.adapt_mode == SAMA_ADAPT_NONE) { ad.mode = 1; ad.scalar = 1.f; }
   else if (f.base_opt == SAMA_OPT_SGD) { ad.mode = 1; ad.scalar = f.base_lr; }
@@ -327,7 +374,21 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
     ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)f.beta1); ad.one_m_beta2 = (float)(1.0 - (double)f.beta2);
     ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
   }
-  launch_adapt_norm(st, c->g, c->m, c->v, c->gmeta, c->vdir, c->partial, c->n, ad, f.alpha, c->scalars, c->counters + 2);
+  // v = D . g_meta layer by layer while the backward pass still runs, the rest after it, then the norm
+  AdaptSink sink(c, ad);
+  c->model->set_grad_sink(&sink);
+  c->model->backward(st, w0, *meta, c->dlogits, c->gmeta);
+  c->model->set_grad_sink(nullptr);
+  std::sort(sink.done.begin(), sink.done.end());
+  {
+    std::vector<std::pair<int64_t, int64_t>> gaps;
+    int64_t pos = 0;
+    for (auto& r : sink.done) { if (r.first > pos) gaps.push_back({pos, r.first - pos}); pos = r.first + r.second; }
+    if (pos < c->n) gaps.push_back({pos, c->n - pos});
+    const int per_gap = gaps.empty() ? 0 : (EW_MAX_BLOCKS - sink.used) / (int)gaps.size();
+    for (auto& r : gaps) sink.slice(st, r.first, r.second, per_gap);
+  }
+  launch_eps_from_partials(st, c->partial, sink.used, f.alpha, c->scalars, c->counters + 2);
   // A step that is applied nudges the GEMM block of theta in the same pass that writes the low halves; the non-GEMM
   // tail is nudged after the two passes, which read it as theta +- eps v.
   const bool fused_nudge = update && c->bf16 && c->n_gemm % 4 == 0;
@@ -421,8 +482,11 @@ sama_status sama_aux_base_step(sama_ctx* c, const sama_batch* ft, const sama_aux
   const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, n_ft * S, n_pt * S};
   c->model->mlm_forward(st, &w, 1, cat.n * S, true, mb, c->loss_pos);
   aux_stage(c, pt, STAGE_BASE, c->loss_pos, c->losses + n_ft, nullptr, loss_out);
+  UpdateSink sink(c, c->t + 1);
+  c->model->set_grad_sink(&sink);
   c->model->backward_mlm(st, w, cat, c->dlogits, c->g, mb, c->coef_pos);
-  base_update(c);
+  c->model->set_grad_sink(nullptr);
+  base_update_rest(c, sink);
   return check_hip(c, "sama_aux_base_step");
 }
 

@@ -179,3 +179,32 @@ def test_workload4_parity():
 
 def test_workload5_parity():
     _full_workload_parity(5, 32, 16)
+
+
+def test_second_stream_changes_no_result():
+    """The backward pass runs its weight-gradient launches, and the per-layer optimizer update / adaptation behind them,
+    on a second stream.  With everything on one stream instead (tuning hooks of the library) a base step must give the
+    same bits, and a meta step the same numbers up to the order in which the partial sums of ||v||^2 are added."""
+    import ctypes
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    res = {}
+    for mode in (0, 1):
+        orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+        gpu.lib.sama_dev_side_stream(ctypes.c_int32(mode)); gpu.lib.sama_dev_side_sink(ctypes.c_int32(mode))
+        try:
+            for s in range(3):
+                (x, y), (xm, ym) = _batches(wl, s)
+                gpu.base_step(dev_batch(gpu, x, y))
+            after_base = {k: pull(gpu, k).copy() for k in ("G", "THETA", "M", "V")}
+            gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
+            res[mode] = (after_base, {k: pull(gpu, k).copy() for k in ("GMETA", "VDIR", "HYPERGRAD", "THETA", "LAMBDA", "SCALARS")})
+        finally:
+            gpu.lib.sama_dev_side_stream(ctypes.c_int32(1)); gpu.lib.sama_dev_side_sink(ctypes.c_int32(1))
+            gpu.close()
+    for k in res[0][0]:
+        assert np.array_equal(res[0][0][k], res[1][0][k]), k
+    assert np.array_equal(res[0][1]["GMETA"], res[1][1]["GMETA"])
+    assert np.array_equal(res[0][1]["VDIR"], res[1][1]["VDIR"])
+    assert abs(res[0][1]["SCALARS"][0] - res[1][1]["SCALARS"][0]) <= 1e-6 * res[0][1]["SCALARS"][0]
+    for k in ("HYPERGRAD", "THETA", "LAMBDA"):
+        assert rel_l2(res[1][1][k], res[0][1][k]) < 1e-4, k
