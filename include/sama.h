@@ -14,7 +14,10 @@
  *    sama_workspace_bytes() bytes (256-byte aligned) and keeps it alive until sama_destroy.
  *  - All work is enqueued on the hipStream_t given to sama_init and returns without waiting for it, except
  *    where a function says it synchronises.  Batches and outputs must stay valid until the stream has passed
- *    the call.  Calls on one context must not overlap from several threads.
+ *    the call.  Calls on one context must not overlap from several threads.  The encoder's backward passes also use
+ *    a second stream of the library's own (default priority, created at the first such pass, destroyed by
+ *    sama_destroy); it forks from and joins the given stream by events inside each call, so the ordering a caller
+ *    sees is that of the given stream alone.
  *  - Return value: SAMA_OK or an error detected on the host (nothing is enqueued after an error).  Conditions
  *    only the device can see (a zero or non-finite ||v||) set a status word readable through
  *    sama_get_state(SAMA_STATE_COUNTERS) and turn that meta step into a no-op with a zero hypergradient.
