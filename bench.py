@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--aux", action="store_true",
                     help="auxiliary-task reweighting (Sec. 4.3) instead of the headline workload: the 12-layer encoder with a "
                          "50304-token masked-token head, 16 finetuning + 16 auxiliary sequences per base step")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each iteration (unroll base steps + meta step) into a HIP graph once per synthetic batch and time "
+                         "replays instead of eager calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -65,6 +68,9 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.graph:                                          # capture needs a stream other than the default one
+        run_stream = torch.cuda.Stream(device=dev)
+        torch.cuda.set_stream(run_stream)
     cfg_id = args.workload
     nb = 4                                                  # distinct synthetic batches cycled through
     if args.aux:
@@ -116,6 +122,19 @@ def main():
         s.aux_base_step(batches[0][0], aux[0])
     else:
         s.base_step(batches[0][0])                          # one step of Adam history before anything is timed
+    step_eager = step
+    if args.graph:
+        step_eager(0)                                       # lazy set-up (second stream, kernel attributes) outside the captures
+        torch.cuda.synchronize(dev)
+        graphs = []
+        for k in range(nb):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=run_stream, capture_error_mode="thread_local"):
+                step_eager(k)
+            graphs.append(g)
+
+        def step(k):                                        # noqa: F811
+            graphs[k % nb].replay()
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize(dev)
@@ -139,7 +158,7 @@ def main():
                    ("MLP " + "-".join(map(str, wl.dims)) if wl.kind == "mlp" else
                     "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
                    "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
-                   "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
+                   "launch": "hip graph replay" if args.graph else "eager", "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
                    "last_step_skipped": bool(skipped),
                    "workspace_bytes": int(s.lib.sama_workspace_bytes(__import__("ctypes").byref(cfg)))},
     }
@@ -154,7 +173,7 @@ def main():
         s.lib.sama_dev_side_stream(ctypes.c_int32(0))
         s.profile(True)
         for k in range(prof_steps):
-            step(k)
+            step_eager(k)
         torch.cuda.synchronize(dev)
         fam = s.profile_read()
         s.profile(False)

@@ -62,6 +62,7 @@ __global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g
                                                      float* __restrict__ v, float* __restrict__ theta,
                                                      bf16_t* __restrict__ theta16, int64_t n, int64_t n16,
                                                      AdamArgs a) {
+  if (a.dev != nullptr) { a.lr_c1 = a.dev[0]; a.c2 = a.dev[1]; }
   const int64_t nv = n / EW_VEC, trip = (int64_t)gridDim.x * EW_TRIP;
   for (int64_t base = (int64_t)blockIdx.x * EW_TRIP + threadIdx.x; base < nv; base += trip) {
     f4 G[EW_U], M[EW_U], V[EW_U], T[EW_U];
@@ -95,6 +96,16 @@ __global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g
   }
 }
 
+__global__ void k_step_scalars(int64_t* counters, int advance, float lr, float beta1, float beta2, float* step) {
+  const int64_t t = counters[0] + advance;
+  if (advance != 0) counters[0] = t;
+  if (t < 1) return;
+  const double c1 = 1.0 / (1.0 - pow((double)beta1, (double)t));
+  const double c2 = 1.0 / sqrt(1.0 - pow((double)beta2, (double)t));
+  step[0] = (float)((double)lr * c1); step[1] = (float)c2;
+  step[2] = (float)((double)lr * c1 * c2); step[3] = (float)c2;
+}
+
 // SGD: theta' = theta - lr (g + wd theta)
 __global__ __launch_bounds__(EW_THREADS) void k_sgd(const float* __restrict__ g, float* __restrict__ theta,
                                                     bf16_t* __restrict__ theta16, int64_t n, int64_t n16, float lr,
@@ -126,6 +137,7 @@ __global__ __launch_bounds__(EW_THREADS) void k_adapt_norm(const float* __restri
                                                            float* __restrict__ vdir, double* __restrict__ partial,
                                                            int64_t n, AdaptArgs a) {
   __shared__ float red[16];
+  if (a.dev != nullptr) { a.lr_c1_c2 = a.dev[2]; a.c2 = a.dev[3]; }
   const int64_t nv = n / EW_VEC, trip = (int64_t)gridDim.x * EW_TRIP;
   float acc = 0.f;
   for (int64_t base = (int64_t)blockIdx.x * EW_TRIP + threadIdx.x; base < nv; base += trip) {
@@ -363,6 +375,9 @@ void launch_adam(hipStream_t st, const float* g, float* m, float* v, float* thet
   if (n <= 0) return;
   ProfScope ps(st, F_ADAM, 28.0 * n + (theta16 ? 2.0 * n16 : 0.0));
   k_adam<<<ew_grid(n), EW_THREADS, 0, st>>>(g, m, v, theta, theta16, n, n16, a);
+}
+void launch_step_scalars(hipStream_t st, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step) {
+  k_step_scalars<<<1, 1, 0, st>>>(counters, advance, lr, beta1, beta2, step);
 }
 void launch_sgd(hipStream_t st, const float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd) {
   if (n <= 0) return;

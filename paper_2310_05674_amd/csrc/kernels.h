@@ -34,6 +34,7 @@ struct AdamArgs {
   float lr_c1;  // lr / (1 - beta1^t)
   float c2;     // 1 / sqrt(1 - beta2^t)
   float eps, weight_decay;
+  const float* dev;  // non-null: lr_c1 = dev[0], c2 = dev[1] read on the device (launch_step_scalars), the two fields above unused
 };
 struct AdaptArgs {
   int mode;  // 0: Adam closed form, 1: scalar
@@ -41,7 +42,12 @@ struct AdaptArgs {
   float one_m_beta1, one_m_beta2;
   float lr_c1_c2;  // lr c1 c2
   float c2, eps;
+  const float* dev;  // non-null: lr_c1_c2 = dev[2], c2 = dev[3] read on the device
 };
+// The step-dependent scalars of Adam and of its adaptation, kept on the device so that a captured sequence of launches
+// stays valid from replay to replay: t = (counters[0] += advance); step[0..3] = {lr / (1 - beta1^t),
+// 1 / sqrt(1 - beta2^t), lr c1 c2, c2} in double arithmetic (left alone while t < 1).
+void launch_step_scalars(hipStream_t, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step);
 void launch_adam(hipStream_t, const float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n, int64_t n16,
                  const AdamArgs&);
 void launch_sgd(hipStream_t, const float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd);

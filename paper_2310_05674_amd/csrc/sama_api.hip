@@ -70,6 +70,7 @@ struct sama_ctx {
   float *lambda, *meta_m, *meta_v, *hyper, *glam_p32, *glam_m32;
   double *glam_p, *glam_m, *partial, *corr_scratch;
   float* scalars;     // {eps, ||v||, L_base, L_meta}
+  float* step;        // step-dependent optimizer scalars (launch_step_scalars)
   int64_t* counters;  // {t (mirror), meta_t, status, 0}
   float *logits, *dlogits, *losses;
   // auxiliary task: concatenated [ft | pt] batch, per-position losses (two stacked passes) and coefficients
@@ -137,6 +138,7 @@ static size_t carve(sama_ctx* c, void* base) {
   c->glam_p = ws.take<double>(nl); c->glam_m = ws.take<double>(nl);
   c->partial = ws.take<double>(EW_MAX_BLOCKS);
   c->scalars = ws.take<float>(4);
+  c->step = ws.take<float>(8);
   c->counters = ws.take<int64_t>(4);
   const int mb = max_rows(c->cfg);
   const int C = c->cfg.dims[c->cfg.n_dims - 1];
@@ -198,6 +200,7 @@ static void base_update_range(sama_ctx* c, hipStream_t st, int64_t t, int64_t of
     a.lr_c1 = (float)((double)f.base_lr / (1.0 - pow((double)f.beta1, (double)t)));
     a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)f.beta2, (double)t)));
     a.eps = f.adam_eps; a.weight_decay = f.weight_decay;
+    a.dev = c->step;   // the device's own step count decides (the host values above are what it holds in eager use)
     launch_adam(st, c->g + off, c->m + off, c->v + off, c->theta + off, t16, count, n16, a);
   } else {
     launch_sgd(st, c->g + off, c->theta + off, t16, count, n16, f.base_lr, f.weight_decay);
@@ -226,8 +229,7 @@ static void base_update_rest(sama_ctx* c, UpdateSink& sink) {
     pos = r.first + r.second;
   }
   if (pos < c->n) base_update_range(c, st, sink.t, pos, c->n - pos);
-  c->t = sink.t;
-  launch_fill_i64x4(st, c->counters, c->t, 0, 0, 0, 1);
+  c->t = sink.t;   // the device's counter was advanced by launch_step_scalars at the start of the step
 }
 
 // v = D . g_meta and the partial sums of ||v||^2 for the ranges of g_meta the model reports final during its backward
@@ -310,6 +312,7 @@ sama_status sama_init(const sama_config* cfg, void* workspace, size_t workspace_
   launch_fill_f32(st, c->meta_m, 0.f, c->nl); launch_fill_f32(st, c->meta_v, 0.f, c->nl);
   launch_fill_f32(st, c->hyper, 0.f, c->nl); launch_fill_f32(st, c->glam_p32, 0.f, c->nl); launch_fill_f32(st, c->glam_m32, 0.f, c->nl);
   launch_fill_f32(st, c->scalars, 0.f, 4);
+  launch_fill_f32(st, c->step, 0.f, 8);
   launch_fill_i64x4(st, c->counters, 0, 0, 0, 0, 15);
   if (c->bf16) launch_to_bf16(st, c->theta16, c->theta, c->n_gemm);
   sama_status s = check_hip(nullptr, "sama_init");
@@ -332,6 +335,7 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
   if (s != SAMA_OK) return s;
   hipStream_t st = c->stream;
   (void)hipGetLastError();
+  launch_step_scalars(st, c->counters, 1, c->cfg.base_lr, c->cfg.beta1, c->cfg.beta2, c->step);
   const PassWeights w = pass_weights(c, 0.f);
   c->model->forward(st, w, *train, true, c->logits);
   SampleStageArgs sa{};
@@ -373,6 +377,7 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
     const double c2 = 1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t));
     ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)f.beta1); ad.one_m_beta2 = (float)(1.0 - (double)f.beta2);
     ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
+    ad.dev = c->step;
   }
   // v = D . g_meta layer by layer while the backward pass still runs, the rest after it, then the norm
   AdaptSink sink(c, ad);
@@ -468,6 +473,7 @@ sama_status sama_aux_base_step(sama_ctx* c, const sama_batch* ft, const sama_aux
   hipStream_t st = c->stream;
   (void)hipGetLastError();
   const int S = c->cfg.dims[4], C = c->model->n_classes(), n_ft = ft->n, n_pt = pt->n_seq;
+  launch_step_scalars(st, c->counters, 1, c->cfg.base_lr, c->cfg.beta1, c->cfg.beta2, c->step);
   launch_aux_cat(st, (const int32_t*)ft->x, ft->y, ft->sample_mask, n_ft, pt->ids, n_pt, S, c->ids_cat, c->y_cat, c->mask_cat);
   const sama_batch cat{c->ids_cat, c->y_cat, c->mask_cat, n_ft + n_pt};
   const PassWeights w = pass_weights(c, 0.f);
@@ -582,6 +588,7 @@ sama_status sama_set_state(sama_ctx* c, int32_t which, const void* src) {
       return fail(c, SAMA_EHIP, "sama_set_state: counter read-back failed");
     if (host[0] < 0 || host[1] < 0) return fail(c, SAMA_EINVAL, "negative counters");
     c->t = host[0];
+    launch_step_scalars(c->stream, c->counters, 0, c->cfg.base_lr, c->cfg.beta1, c->cfg.beta2, c->step);
   }
   return check_hip(c, "sama_set_state");
 }
