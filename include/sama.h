@@ -18,6 +18,12 @@
  *    a second stream of the library's own (default priority, created at the first such pass, destroyed by
  *    sama_destroy); it forks from and joins the given stream by events inside each call, so the ordering a caller
  *    sees is that of the given stream alone.
+ *  - sama_base_step / sama_meta_grad / sama_meta_step (and their sama_aux_* forms) may be captured into a HIP graph on
+ *    the context's stream once each of them has run eagerly (the first calls create the second stream and set
+ *    kernel attributes): step counts and the optimizer's step-dependent scalars live on the device, so a replay
+ *    continues where the last execution stopped.  Batch and output pointers are baked into the capture.  The
+ *    host-side check that a meta gradient follows a base step looks at eager calls only.  sama_set_state(COUNTERS)
+ *    and the profile functions synchronise or record timing events and do not belong into a capture.
  *  - Return value: SAMA_OK or an error detected on the host (nothing is enqueued after an error).  Conditions
  *    only the device can see (a zero or non-finite ||v||) set a status word readable through
  *    sama_get_state(SAMA_STATE_COUNTERS) and turn that meta step into a no-op with a zero hypergradient.
