@@ -41,8 +41,8 @@ def fwd_flops(wl, batch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=5, help="BASELINE.json config number 1..5")
     ap.add_argument("--unroll", type=int, default=1)
     ap.add_argument("--fast-meta-pass", type=int, default=0)
@@ -229,7 +229,7 @@ def main():
         cm = min(cb, wl.meta_batch)
         it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
         x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
-        reps = {1: 20, 2: 10}.get(cfg_id, 1)
+        reps = {1: 20, 2: 10, 3: 3}.get(cfg_id, 1)
         if args.aux:
             from oracle.auxtask import AuxTaskOracle
             orc = AuxTaskOracle(models.make_model(wl.kind, wl.dims, mlm=True), th0, lam0, base_lr=wl.base_lr,
