@@ -208,3 +208,28 @@ def test_second_stream_changes_no_result():
     assert abs(res[0][1]["SCALARS"][0] - res[1][1]["SCALARS"][0]) <= 1e-6 * res[0][1]["SCALARS"][0]
     for k in ("HYPERGRAD", "THETA", "LAMBDA"):
         assert rel_l2(res[1][1][k], res[0][1][k]) < 1e-4, k
+
+
+def test_single_sequence_batches():
+    """One train sequence and one meta sequence (M = 128 token rows: a single partial GEMM tile row)."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    (x, y), (xm, ym) = _batches(wl, 0)
+    x, y, xm, ym = x[:1], y[:1], xm[:1], ym[:1]
+    for _ in range(2):
+        orc.base_step(x, y)
+    _snap(orc)
+    push_state(orc, gpu)
+    orc.base_step(x, y); gpu.base_step(dev_batch(gpu, x, y))
+    assert rel_l2(pull(gpu, "G"), orc.g) < KTOL
+    _snap(orc)
+    push_state(orc, gpu)
+    r = orc.meta_step(x, y, xm, ym)
+    gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+             glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+    print("single sequence: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+    assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["v"] < TOL and e["theta"] < TOL and e["lam"] < TOL
+    assert e["h"] < TOL, e
+    gpu.close()
