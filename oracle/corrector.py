@@ -4,7 +4,7 @@ sample is the cross-entropy against a corrected soft label,
     L_base = (1/B_eff) sum_i mask_i w(l_i; lambda_r) l_i,    l_i = -sum_k c_ik log softmax(z_i)_k,   c_i = c(x_i, y_i; lambda_c).
 
 The paper names the corrector only as a "2-layer MLP" (Table 4) and cites meta label correction; its inputs and
-parametrisation are not given.  reading (builder-defined, stated in the design doc): the corrector sees the given label
+parametrisation are not given.  reading (defined here, where the paper is silent): the corrector sees the given label
 and the base learner's current prediction, both as constants,
 
     u_i = [onehot(y_i), softmax(z_i)]  (2C inputs),   s_i = kappa onehot(y_i) + W2 relu(W1 u_i + b1) + b2,   c_i = softmax(s_i),
