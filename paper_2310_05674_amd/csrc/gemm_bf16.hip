@@ -444,6 +444,8 @@ typedef Tile<256, 128, 64, 4, 2, 3, false> TM;    // 8 waves of 64 x 64, 3 stage
 typedef Tile<128, 128, 64, 2, 2, 2, false> TS;    // 4 waves of 64 x 64, 2 stages of 32 KB: two blocks per CU
 typedef Tile<128, 64, 64, 2, 2, 3, false> TX;     // 4 waves of 64 x 32, 3 stages of 24 KB: two blocks per CU
 typedef Tile<128, 64, 64, 2, 2, 4, false> TX4;    // 4 stages: one block per CU, deeper prefetch
+typedef Tile<128, 64, 64, 4, 2, 4, false> TX8;    // 8 waves of 32 x 32: the small tile when one block per CU is all there is
+typedef Tile<128, 128, 64, 4, 2, 3, false> TS8;   // 8 waves of 32 x 64
 typedef Tile<256, 256, 32, 2, 4, 3, true> DL;     // DUAL: 3 stages of 48 KB
 typedef Tile<256, 128, 64, 4, 2, 2, true> DM;     // 2 stages of 64 KB
 typedef Tile<128, 128, 64, 2, 2, 3, true> DS;     // 3 stages of 48 KB
@@ -454,22 +456,29 @@ int g_force_shape = 0, g_group = 8;
 
 // Which block tile: estimated cycles per 64-deep k-slab on the busiest CU.  A CU ingests ~25 B/clk from L2 (measured),
 // i.e. 5.12 clk per 128-byte operand row, and sustains ~70% of its 4096 flop/clk MFMA rate; rounds = how many tiles
-// the busiest of the 256 CUs works through.  Near-ties go to the larger tile.
+// the busiest of the 256 CUs works through.  The two smaller tiles exist in a form of which two blocks fit a CU side
+// by side (measured: two co-resident blocks take 1.3 times one) and, for single-term problems, in an 8-wave form that
+// is the fastest when one block per CU is all the problem gives.  Near-ties go to the larger tile.
 int pick_tile(const GemmBf16Args* p, int count, bool dual) {
   static const int dims[4][2] = {{256, 256}, {256, 128}, {128, 128}, {128, 64}};
   const double nb = dual ? 2.0 : 1.0;
   int best = 0;
+  int64_t best_tiles = 0;
   double best_cost = 0.0;
   for (int c = 0; c < 4; ++c) {
     const int bm = dims[c][0], bn = dims[c][1];
     int64_t tiles = 0;
     for (int k = 0; k < count; ++k) tiles += (int64_t)((p[k].M + bm - 1) / bm) * ((p[k].N + bn - 1) / bn);
+    const bool pairs = c == 3 || (c == 2 && !dual);   // a form with two blocks per CU exists
+    const double rounds = (pairs && tiles > 256) ? 1.3 * (double)((tiles + 511) / 512) : (double)((tiles + 255) / 256);
     const double ingest = 5.12 * (bm + nb * bn), mfma = bm * bn * nb / 22.0;
-    const double cost = (double)((tiles + 255) / 256) * (ingest > mfma ? ingest : mfma) * (1.0 + 0.05 * c);
-    if (c == 0 || cost < best_cost) { best = c; best_cost = cost; }
-    if (c == 3 && best == 3 && tiles <= 256) best = 4;   // one block per CU is enough: take the deeper pipeline
+    const double cost = rounds * (ingest > mfma ? ingest : mfma) * (1.0 + 0.05 * c);
+    if (c == 0 || cost < best_cost) { best = c; best_cost = cost; best_tiles = tiles; }
   }
-  return (dual ? 11 : 1) + best;
+  if (dual) return best == 3 ? (best_tiles <= 256 ? 15 : 14) : 11 + best;
+  if (best == 2) return best_tiles <= 256 ? 7 : 3;
+  if (best == 3) return best_tiles <= 256 ? 6 : 4;
+  return 1 + best;
 }
 
 template <bool A_KC, bool B_KC>
@@ -483,6 +492,8 @@ void launch_class(hipStream_t st, const GemmBf16Args* p, int count) {
     case 2: launch_tile<TM, A_KC, B_KC>(st, p, count, g_group); break;
     case 4: launch_tile<TX, A_KC, B_KC>(st, p, count, g_group); break;
     case 5: launch_tile<TX4, A_KC, B_KC>(st, p, count, g_group); break;
+    case 6: launch_tile<TX8, A_KC, B_KC>(st, p, count, g_group); break;
+    case 7: launch_tile<TS8, A_KC, B_KC>(st, p, count, g_group); break;
     case 11: launch_tile<DL, A_KC, B_KC>(st, p, count, g_group); break;
     case 12: launch_tile<DM, A_KC, B_KC>(st, p, count, g_group); break;
     case 13: launch_tile<DS, A_KC, B_KC>(st, p, count, g_group); break;

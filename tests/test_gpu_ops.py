@@ -133,7 +133,7 @@ def test_gemm_bf16(M, N, K, a_trans, b_trans, split):
     tbias = _dev(bias)
     L = B.load_library()
     outs = []
-    for shape in (1, 2, 3, 4, 5, 11, 12, 13, 14, 15, 0):
+    for shape in (1, 2, 3, 4, 5, 6, 7, 11, 12, 13, 14, 15, 0):
         L.sama_dev_gemm_shape(ctypes.c_int32(shape))
         o32 = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
         o16 = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
