@@ -25,7 +25,7 @@ PEAK_FP32_MATRIX_TFLOPS = 157.3
 # HBM-side bytes per launch of the dominant kernel family (the hi + lo forward GEMMs) on workload 5, from the two
 # rocprofv3 --pmc runs summarised in profiles/bench_workload5_hbm_traffic.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
 # calibrated on the library's own copy kernel).  Not measured for other workloads / kernels: reported as null there.
-MEASURED_TRAFFIC_BYTES = {(5, "gemm_bf16_nt_hilo"): 94.8e6}
+MEASURED_TRAFFIC_BYTES = {(5, "gemm_bf16_nt_hilo"): 99.5e6}
 
 
 def fwd_flops(wl, batch):
