@@ -144,6 +144,13 @@ def test_gemm_bf16(M, N, K, a_trans, b_trans, split):
         assert rel_l2(got, want) < 1e-5
         assert np.array_equal(_bf16_bits_to_f64(o16), round_to_bf16(got.astype(np.float64)))
         outs.append(got)
+    # every tile of a class (single-term / hi + lo) accumulates an output element in the same order: same bits
+    classes = ((1, 2, 3, 4, 5, 6, 7, 0), ()) if not split else ((11, 12, 13, 14, 15, 0), (1, 2, 3, 4, 5, 6, 7))
+    order = (1, 2, 3, 4, 5, 6, 7, 11, 12, 13, 14, 15, 0)
+    for cls in classes:
+        ref = [outs[order.index(sid)] for sid in cls]
+        for o in ref[1:]:
+            assert np.array_equal(o, ref[0])
     L.sama_dev_gemm_shape(ctypes.c_int32(0))
     o32b = torch.empty((M, N), dtype=torch.float32, device=DEV)
     B.op_gemm_bf16(tA, tB, a_trans=a_trans, b_trans=b_trans, B2=tB2, bias=tbias, out32=o32b)
