@@ -86,7 +86,7 @@ def _torch_encoder_losses(enc, th, ids, y):
     return t, F.cross_entropy(logits, torch.tensor(y, dtype=torch.long), reduction="none")
 
 
-@pytest.mark.parametrize("dims", [(2, 16, 4, 32, 8, 50, 3), (1, 24, 3, 40, 5, 30, 2)])
+@pytest.mark.parametrize("dims", [(2, 16, 4, 32, 8, 50, 3), (1, 24, 3, 40, 5, 30, 2), (2, 128, 2, 256, 128, 300, 3)])   # the last: S = 128, head width 64 as on the GPU
 def test_encoder_vs_torch_autograd(dims):
     enc = models.Encoder(*dims)
     L, d, heads, ffn, S, V, C = dims
