@@ -233,3 +233,22 @@ def test_single_sequence_batches():
     assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["v"] < TOL and e["theta"] < TOL and e["lam"] < TOL
     assert e["h"] < TOL, e
     gpu.close()
+
+
+def test_free_running_trajectory_is_reproducible_bit_for_bit():
+    """No floating-point atomics and a fixed order in every reduction, on two streams: two runs of the same 30
+    iterations (unroll 2) from the same start end in the same bits."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    outs = []
+    for rep in range(2):
+        _, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+        for k in range(30):
+            (x, y), (xm, ym) = _batches(wl, k)
+            tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+            gpu.base_step(tb); gpu.base_step(tb); gpu.meta_step(tb, mb)
+        outs.append({k: pull(gpu, k).copy() for k in ("THETA", "LAMBDA", "M", "V", "HYPERGRAD", "COUNTERS")})
+        gpu.close()
+    assert int(outs[0]["COUNTERS"][0]) == 60 and int(outs[0]["COUNTERS"][1]) == 30 and int(outs[0]["COUNTERS"][2]) == 0
+    assert np.all(np.isfinite(outs[0]["THETA"]))
+    for k in outs[0]:
+        assert np.array_equal(outs[0][k], outs[1][k]), k
