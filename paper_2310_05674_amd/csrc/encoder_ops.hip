@@ -244,10 +244,11 @@ __device__ __forceinline__ s16x4 pack4(float a, float b, float c, float d) {
 // operand: for the 32x32x8 MFMA, lane l gets S[k0 + 4 (l / 32) + 0..3][e32 + l % 32] through ds_read_b64_tr_b16.
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 constexpr int SLD = AD + 32;
+template <int THREADS = 256>
 __device__ __forceinline__ void stage_rows(const bf16_t* __restrict__ src, int64_t ld, bf16_t* __restrict__ S) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + 256 * i, row = c >> 3, ec = c & 7;
+  for (int i = 0; i < 1024 / THREADS; ++i) {
+    const int c = threadIdx.x + THREADS * i, row = c >> 3, ec = c & 7;
     *reinterpret_cast<uint4*>(S + row * SLD + ec * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)row * ld + ec * 8);
   }
 }
@@ -333,24 +334,26 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
 // Phase B (wave owns 32 keys):    P[q][key], dS[q][key] -> dV^T[e][key] = sum_q dO^T[e][q] P[q][key],
 //                                                          dK^T[e][key] = sum_q Q^T[e][q] dS[q][key].
 // dS = P (dP - D) / 8 with D[q] = sum_e dO[q][e] O[q][e].
-__global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ out,
+// The two phases only read what is staged and are independent: waves 0-3 run phase A while waves 4-7 run phase B.
+__global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ out,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ lse,
                                                   bf16_t* __restrict__ dqkv, int heads, int d) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[AS * SLD];
   __shared__ __attribute__((aligned(16))) bf16_t Qs[AS * SLD];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[AS * SLD];
   __shared__ float s_D[AS], s_lse[AS];
-  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3;
+  const bool phase_a = threadIdx.x < 256;
   const int64_t ld = 3 * (int64_t)d;
   const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
   const bf16_t* K = Q + d;
   const bf16_t* V = Q + 2 * d;
   const bf16_t* O = out + (int64_t)b * AS * d + h * AD;
   const bf16_t* dO = dout + (int64_t)b * AS * d + h * AD;
-  stage_rows(K, ld, Ks);
-  stage_rows(Q, ld, Qs);
-  stage_rows(dO, d, dOs);
-  {
+  stage_rows<512>(K, ld, Ks);
+  stage_rows<512>(Q, ld, Qs);
+  stage_rows<512>(dO, d, dOs);
+  if (phase_a) {
     const int q = threadIdx.x >> 1, half = threadIdx.x & 1;
     float acc = 0.f;
 #pragma unroll
@@ -368,7 +371,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
   __syncthreads();
 
   // ---- phase A: dQ
-  {
+  if (phase_a) {
     const int q = 32 * wave + (lane & 31);
     const float lq = s_lse[q], Dq = s_D[q];
     f32x16 dq[2];
@@ -411,7 +414,7 @@ __global__ __launch_bounds__(256) void k_attn_bwd(const bf16_t* __restrict__ qkv
   }
 
   // ---- phase B: dK, dV
-  {
+  if (!phase_a) {
     f32x16 dk[2], dv[2];
 #pragma unroll
     for (int et = 0; et < 2; ++et)
@@ -613,7 +616,7 @@ void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float*
 void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
                           bf16_t* dqkv, int B, int heads, int d) {
   ProfScope ps(st, F_ATTN_BWD, 10.0 * B * heads * 128.0 * 128.0 * 64.0);
-  k_attn_bwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d);
+  k_attn_bwd<<<dim3(heads, B), 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d);
 }
 void launch_head_fwd(hipStream_t st, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits) {
