@@ -83,6 +83,11 @@ __global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g
         }
         st_nt(m, j, M[u]); st_nt(v, j, V[u]); st_nt(theta, j, T[u]);
         st_bf16_prefix(theta16, j, n16, T[u]);
+        if (a.lo != nullptr) {
+          f4 r;
+          r.x = bf16_residual(T[u].x); r.y = bf16_residual(T[u].y); r.z = bf16_residual(T[u].z); r.w = bf16_residual(T[u].w);
+          st_bf16_prefix(a.lo, j, n16, r);
+        }
       }
     }
   }
@@ -93,6 +98,7 @@ __global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g
     adam_one(g[k], mm, vv, tt, a);
     m[k] = mm; v[k] = vv; theta[k] = tt;
     if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(tt);
+    if (a.lo != nullptr && k < n16) a.lo[k] = f32_to_bf16(bf16_residual(tt));
   }
 }
 
@@ -373,7 +379,7 @@ __global__ void k_fill_i64(int64_t* p, int64_t a, int64_t b, int64_t c, int64_t 
 void launch_adam(hipStream_t st, const float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n,
                  int64_t n16, const AdamArgs& a) {
   if (n <= 0) return;
-  ProfScope ps(st, F_ADAM, 28.0 * n + (theta16 ? 2.0 * n16 : 0.0));
+  ProfScope ps(st, F_ADAM, 28.0 * n + (theta16 ? 2.0 * n16 : 0.0) + (a.lo ? 2.0 * n16 : 0.0));
   k_adam<<<ew_grid(n), EW_THREADS, 0, st>>>(g, m, v, theta, theta16, n, n16, a);
 }
 void launch_step_scalars(hipStream_t st, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step) {

@@ -35,6 +35,8 @@ struct AdamArgs {
   float c2;     // 1 / sqrt(1 - beta2^t)
   float eps, weight_decay;
   const float* dev;  // non-null: lr_c1 = dev[0], c2 = dev[1] read on the device (launch_step_scalars), the two fields above unused
+  bf16_t* lo;        // non-null: also lo[k] = bf16(theta'[k] - float(bf16(theta'[k]))) for the first n16 elements (what
+                     // launch_residual_lo would compute afterwards)
 };
 struct AdaptArgs {
   int mode;  // 0: Adam closed form, 1: scalar

@@ -76,6 +76,7 @@ struct sama_ctx {
   // auxiliary task: concatenated [ft | pt] batch, per-position losses (two stacked passes) and coefficients
   int32_t *ids_cat, *y_cat; uint8_t* mask_cat; float *loss_pos, *coef_pos;
   int64_t t;  // base step count (host)
+  bool lo_is_residual = false;   // lo_p holds bf16(theta - bf16(theta)) of the current theta (written by the last Adam step)
   std::string err;
 };
 
@@ -201,6 +202,8 @@ static void base_update_range(sama_ctx* c, hipStream_t st, int64_t t, int64_t of
     a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)f.beta2, (double)t)));
     a.eps = f.adam_eps; a.weight_decay = f.weight_decay;
     a.dev = c->step;   // the device's own step count decides (the host values above are what it holds in eager use)
+    // the residual half the next direct-gradient pass contracts with comes out of the same pass over theta
+    a.lo = (t16 != nullptr && !f.fast_meta_pass) ? c->lo_p + off : nullptr;
     launch_adam(st, c->g + off, c->m + off, c->v + off, c->theta + off, t16, count, n16, a);
   } else {
     launch_sgd(st, c->g + off, c->theta + off, t16, count, n16, f.base_lr, f.weight_decay);
@@ -230,6 +233,7 @@ static void base_update_rest(sama_ctx* c, UpdateSink& sink) {
   }
   if (pos < c->n) base_update_range(c, st, sink.t, pos, c->n - pos);
   c->t = sink.t;   // the device's counter was advanced by launch_step_scalars at the start of the step
+  c->lo_is_residual = c->bf16 && c->cfg.base_opt == SAMA_OPT_ADAM && !c->cfg.fast_meta_pass;
 }
 
 // v = D . g_meta and the partial sums of ||v||^2 for the ranges of g_meta the model reports final during its backward
@@ -360,9 +364,14 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
   const int C = c->model->n_classes();
   PassWeights w0 = pass_weights(c, 0.f);
   if (c->bf16 && !f.fast_meta_pass) {   // hi + lo of the master weights: the gradient is taken at theta, not bf16(theta)
-    launch_residual_lo(st, c->theta, c->lo_p, c->n_gemm);
+    // The last Adam step left the residual half in lo_p unless something changed theta or lo_p since (a meta pass, a
+    // state upload).  A stream capture always takes the pass of its own, so that a captured call stands by itself.
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
+    if (!c->lo_is_residual || capturing) launch_residual_lo(st, c->theta, c->lo_p, c->n_gemm);
     w0.lo = c->lo_p;
   }
+  c->lo_is_residual = false;   // the +- halves overwrite lo_p, an applied step moves theta
   c->model->forward(st, w0, *meta, true, c->logits);
   SampleStageArgs sa{};
   sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = meta->n; sa.H = f.wnet_hidden; sa.mode = STAGE_META;
@@ -581,6 +590,7 @@ sama_status sama_set_state(sama_ctx* c, int32_t which, const void* src) {
   if (hipMemcpyAsync(p, src, bytes, hipMemcpyDeviceToDevice, c->stream) != hipSuccess)
     return fail(c, SAMA_EHIP, "sama_set_state: copy failed");
   if (which == SAMA_STATE_THETA && c->bf16) launch_to_bf16(c->stream, c->theta16, c->theta, c->n_gemm);
+  if (which == SAMA_STATE_THETA) c->lo_is_residual = false;
   if (which == SAMA_STATE_COUNTERS) {
     int64_t host[4];
     if (hipMemcpyAsync(host, c->counters, 32, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||
