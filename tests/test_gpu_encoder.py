@@ -252,3 +252,31 @@ def test_free_running_trajectory_is_reproducible_bit_for_bit():
     assert np.all(np.isfinite(outs[0]["THETA"]))
     for k in outs[0]:
         assert np.array_equal(outs[0][k], outs[1][k]), k
+
+
+@pytest.mark.parametrize("variant", ["sgd", "sama_na"])
+def test_small_encoder_sgd_and_no_adaptation(variant):
+    """The bf16 encoder with an SGD base solver (D = base lr) and with the adaptation switched off (SAMA-NA, D = 1):
+    the per-layer update / adaptation slices of the two-stream backward take their other branches here."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    kw = dict(base_opt="sgd", base_lr=0.05) if variant == "sgd" else dict(adapt_mode=1, base_lr=1e-3)
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), **kw)
+    for s in range(2):
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(x, y)
+    (x, y), (xm, ym) = _batches(wl, 2)
+    _snap(orc)
+    push_state(orc, gpu)
+    orc.base_step(x, y); gpu.base_step(dev_batch(gpu, x, y))
+    assert rel_l2(pull(gpu, "G"), orc.g) < KTOL
+    assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    _snap(orc)
+    push_state(orc, gpu)
+    r = orc.meta_step(x, y, xm, ym)
+    gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+             eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+    print(f"{variant}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+    assert e["gmeta"] < KTOL and e["v"] < KTOL and e["eps"] < KTOL and e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL
+    gpu.close()
