@@ -43,6 +43,7 @@ class AuxTaskOracle(SamaOracle):
         y = np.concatenate([np.asarray(y_ft), np.zeros(n_pt, dtype=np.asarray(y_ft).dtype)])
         coef_pos = (w / (n_pt * np.maximum(cnt, 1.0)))[seq]
         l, l_pos2, g = self.model.loss_grad_mlm(self.theta, ids, y, coef, np.asarray(seq) + n_ft, pos, tgt, coef_pos)
+        g = g + self.weight_decay * self.theta
         self.g = g
         self.t += 1
         if self.base_opt == ADAM:

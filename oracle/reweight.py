@@ -15,7 +15,8 @@ SGD, ADAM = 0, 1
 class SamaOracle:
     def __init__(self, model, theta0, lambda0, *, base_opt=ADAM, base_lr=1e-3, beta1=0.9, beta2=0.999,
                  adam_eps=1e-8, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999, meta_eps=1e-8,
-                 alpha=1.0, adapt_mode=optim.ADAPT_ADAM, corr_hidden=0, corr_kappa=4.0, n_classes=None):
+                 alpha=1.0, adapt_mode=optim.ADAPT_ADAM, corr_hidden=0, corr_kappa=4.0, n_classes=None,
+                 weight_decay=0.0):
         self.model = model
         self.theta = np.array(theta0, dtype=np.float64)
         self.lam = np.array(lambda0, dtype=np.float64)
@@ -27,6 +28,9 @@ class SamaOracle:
         self.base_opt, self.base_lr, self.beta1, self.beta2, self.adam_eps = base_opt, base_lr, beta1, beta2, adam_eps
         self.meta_lr, self.meta_beta1, self.meta_beta2, self.meta_eps = meta_lr, meta_beta1, meta_beta2, meta_eps
         self.alpha, self.adapt_mode = alpha, adapt_mode
+        # reading: the base optimizer's weight decay (the "wdecay" column of the hyperparameter tables of App. B) is an L2
+        # term, weight_decay * theta added to the gradient before the solver; g, as kept for the adaptation, includes it
+        self.weight_decay = float(weight_decay)
         self.status = 0                # 1 after a meta step skipped for ||v|| = 0 / non-finite
         # label correction (Sec. 4.1): lambda = [lambda_r | lambda_c]; corr_hidden = 0 turns it off
         self.Hc, self.kappa, self.C = int(corr_hidden), float(corr_kappa), n_classes
@@ -50,6 +54,7 @@ class SamaOracle:
         w = wnet.weights(l, self.lam[:self.nr])
         coef = mask * w / mask.sum()
         l, g = self.model.loss_grad(self.theta, x, target, coef)
+        g = g + self.weight_decay * self.theta
         self.g = g
         self.t += 1
         if self.base_opt == ADAM:

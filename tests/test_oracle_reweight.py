@@ -177,3 +177,38 @@ def test_workload1_trajectory_runs():
         r = o.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta)
         assert np.all(np.isfinite(r["h"])) and abs(r["eps"] * np.linalg.norm(r["v"]) - wl.alpha) < 1e-12
     assert o.meta_t == wl.steps and np.linalg.norm(o.lam - lam0) > 0
+
+
+def test_weight_decay_is_an_l2_term_in_front_of_the_solver():
+    """wdecay of the base optimizer (App. B tables): with SGD one step is theta - lr (g + wd theta) by hand; with Adam
+    the first step moves every element by lr against the sign of g + wd theta; and the kept gradient, the one the
+    adaptation differentiates the update with respect to, includes the term."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    wd, lr = 0.3, 0.05
+    l = model.losses(th, x, y)
+    w = wnet.weights(l, lam)
+    _, g = model.loss_grad(th, x, y, w / len(y))
+    o = SamaOracle(model, th, lam, base_opt=SGD, base_lr=lr, weight_decay=wd)
+    o.base_step(x, y)
+    assert np.allclose(o.theta, th - lr * (g + wd * th), rtol=0, atol=1e-15)
+    assert np.allclose(o.g, g + wd * th, rtol=0, atol=1e-15)
+    big = 50.0                                    # the decay term decides every sign
+    a = SamaOracle(model, th, lam, base_lr=lr, adam_eps=0.0, weight_decay=big)
+    a.base_step(x, y)
+    assert np.allclose(a.theta, th - lr * np.sign(g + big * th), rtol=1e-12, atol=1e-15)
+    # no decay: the same oracle as before
+    z = SamaOracle(model, th, lam, base_lr=lr); z0 = SamaOracle(model, th, lam, base_lr=lr, weight_decay=0.0)
+    z.base_step(x, y); z0.base_step(x, y)
+    assert np.array_equal(z.theta, z0.theta)
+    # the adaptation is the derivative of the update with respect to the gradient it was given
+    b = SamaOracle(model, th, lam, base_lr=lr, weight_decay=wd)
+    for _ in range(3):
+        b.base_step(x, y)
+    D = b.adaptation()
+    m_prev = (b.m - (1 - b.beta1) * b.g) / b.beta1
+    v_prev = (b.v - (1 - b.beta2) * b.g ** 2) / b.beta2
+    d = 1e-7 * (1 + np.abs(b.g))
+    up = lambda gg: th * 0 - optim.adam_update(th * 0, m_prev, v_prev, gg, b.t, lr, b.beta1, b.beta2, 0.0)[0]
+    fd = (up(b.g + d) - up(b.g - d)) / (2 * d)
+    keep = np.abs(b.v) > 1e-12
+    assert np.allclose(D[keep], fd[keep], rtol=2e-4, atol=1e-10)
