@@ -84,7 +84,8 @@ typedef struct {
   int32_t wnet_hidden; /* H, 1..256 */
   int32_t base_opt;    /* SAMA_OPT_*: the base-level solver u of Sec. 2 */
   float base_lr, beta1, beta2, adam_eps; /* gamma, beta_1, beta_2, epsilon of App. C */
-  float weight_decay;  /* L2 coefficient added to the base gradient before the solver (0 in every paper run with Adam) */
+  float weight_decay;  /* L2 coefficient (the wdecay column of App. B): weight_decay * theta is added to the base gradient
+                        * before the solver; the G state and the adaptation of Eq. 4 use that sum */
   float meta_lr, meta_beta1, meta_beta2, meta_eps; /* Adam on lambda (Table 4) */
   float alpha;         /* eps = alpha / ||v||_2, Sec. 3.2 below Eq. 5 */
   int32_t adapt_mode;  /* SAMA_ADAPT_OPTIMIZER: du/dg of base_opt (App. C for Adam, gamma for SGD);

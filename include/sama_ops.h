@@ -36,8 +36,10 @@ sama_status sama_op_gemm_bf16_batch(int32_t count, const void* const* A, const v
                                     int32_t a_trans, int32_t b_trans, void* hip_stream);
 
 /* Base solver update, Adam form (Sec. 2; Kingma & Ba Alg. 1 with bias correction at step t >= 1), over n fp32
- * elements in place; theta16 (bf16 [n16], n16 <= n) receives the rounded leading part of theta, or NULL. */
-sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16,
+ * elements in place; theta16 (bf16 [n16], n16 <= n) receives the rounded leading part of theta, or NULL.  With
+ * weight_decay != 0 the L2 term is added in front of the solver and g is overwritten with g + weight_decay * theta
+ * (the gradient the solver was given, which the adaptation of Eq. 4 needs); with 0 g is only read. */
+sama_status sama_op_adam(float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16,
                          int64_t t, float lr, float beta1, float beta2, float eps, float weight_decay, void* hip_stream);
 
 /* Adaptation fused with the step size (Eq. 4-5, App. C): vdir = (du_adam/dg) . gmeta from the post-update moments at

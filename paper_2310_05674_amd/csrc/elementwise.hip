@@ -51,14 +51,13 @@ __device__ __forceinline__ float bf16_residual(float t) { return t - bf16_to_f32
 // Adam: m' = b1 m + (1-b1) g ; v' = b2 v + (1-b2) g^2 ; theta' = theta - lr c1 m' / (c2 sqrt(v') + eps)
 // with c1 = 1/(1-b1^t), c2 = 1/sqrt(1-b2^t) computed on the host in double.  Optionally refreshes the bf16
 // working copy of the first n16 elements (the GEMM weight matrices).
-__device__ __forceinline__ void adam_one(float g, float& m, float& v, float& th, const AdamArgs& a) {
-  g = fmaf(a.weight_decay, th, g);
+__device__ __forceinline__ void adam_one(float g, float& m, float& v, float& th, const AdamArgs& a) {   // g includes the L2 term
   m = fmaf(a.beta1, m, a.one_m_beta1 * g);
   v = fmaf(a.beta2, v, a.one_m_beta2 * g * g);
   th = th - a.lr_c1 * m / (fmaf(a.c2, sqrtf(v), a.eps));
 }
 
-__global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g, float* __restrict__ m,
+__global__ __launch_bounds__(EW_THREADS) void k_adam(float* __restrict__ g, float* __restrict__ m,
                                                      float* __restrict__ v, float* __restrict__ theta,
                                                      bf16_t* __restrict__ theta16, int64_t n, int64_t n16,
                                                      AdamArgs a) {
@@ -78,9 +77,11 @@ __global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g
 #pragma unroll
         for (int e = 0; e < EW_VEC; ++e) {
           float mm = M[u][e], vv = V[u][e], tt = T[u][e];
+          G[u][e] = fmaf(a.weight_decay, tt, G[u][e]);
           adam_one(G[u][e], mm, vv, tt, a);
           M[u][e] = mm; V[u][e] = vv; T[u][e] = tt;
         }
+        if (a.weight_decay != 0.f) st_nt(g, j, G[u]);   // the gradient the solver was given, kept for the adaptation
         st_nt(m, j, M[u]); st_nt(v, j, V[u]); st_nt(theta, j, T[u]);
         st_bf16_prefix(theta16, j, n16, T[u]);
         if (a.lo != nullptr) {
@@ -95,7 +96,9 @@ __global__ __launch_bounds__(EW_THREADS) void k_adam(const float* __restrict__ g
   const int64_t k = nv * EW_VEC + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (k < n) {
     float mm = m[k], vv = v[k], tt = theta[k];
-    adam_one(g[k], mm, vv, tt, a);
+    const float ge = fmaf(a.weight_decay, tt, g[k]);
+    adam_one(ge, mm, vv, tt, a);
+    if (a.weight_decay != 0.f) g[k] = ge;
     m[k] = mm; v[k] = vv; theta[k] = tt;
     if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(tt);
     if (a.lo != nullptr && k < n16) a.lo[k] = f32_to_bf16(bf16_residual(tt));
@@ -113,13 +116,15 @@ __global__ void k_step_scalars(int64_t* counters, int advance, float lr, float b
 }
 
 // SGD: theta' = theta - lr (g + wd theta)
-__global__ __launch_bounds__(EW_THREADS) void k_sgd(const float* __restrict__ g, float* __restrict__ theta,
+__global__ __launch_bounds__(EW_THREADS) void k_sgd(float* __restrict__ g, float* __restrict__ theta,
                                                     bf16_t* __restrict__ theta16, int64_t n, int64_t n16, float lr,
                                                     float wd) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride) {
     float t = theta[k];
-    t = t - lr * fmaf(wd, t, g[k]);
+    const float ge = fmaf(wd, t, g[k]);
+    if (wd != 0.f) g[k] = ge;   // the gradient the solver was given
+    t = t - lr * ge;
     theta[k] = t;
     if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(t);
   }
@@ -376,7 +381,7 @@ __global__ void k_fill_i64(int64_t* p, int64_t a, int64_t b, int64_t c, int64_t 
 }
 }  // namespace
 
-void launch_adam(hipStream_t st, const float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n,
+void launch_adam(hipStream_t st, float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n,
                  int64_t n16, const AdamArgs& a) {
   if (n <= 0) return;
   ProfScope ps(st, F_ADAM, 28.0 * n + (theta16 ? 2.0 * n16 : 0.0) + (a.lo ? 2.0 * n16 : 0.0));
@@ -385,7 +390,7 @@ void launch_adam(hipStream_t st, const float* g, float* m, float* v, float* thet
 void launch_step_scalars(hipStream_t st, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step) {
   k_step_scalars<<<1, 1, 0, st>>>(counters, advance, lr, beta1, beta2, step);
 }
-void launch_sgd(hipStream_t st, const float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd) {
+void launch_sgd(hipStream_t st, float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd) {
   if (n <= 0) return;
   k_sgd<<<ew_grid(n), EW_THREADS, 0, st>>>(g, theta, theta16, n, n16, lr, wd);
 }

@@ -50,9 +50,10 @@ struct AdaptArgs {
 // stays valid from replay to replay: t = (counters[0] += advance); step[0..3] = {lr / (1 - beta1^t),
 // 1 / sqrt(1 - beta2^t), lr c1 c2, c2} in double arithmetic (left alone while t < 1).
 void launch_step_scalars(hipStream_t, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step);
-void launch_adam(hipStream_t, const float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n, int64_t n16,
+// With a non-zero weight decay the L2 term is added to g in place (g then is the gradient the solver was given).
+void launch_adam(hipStream_t, float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n, int64_t n16,
                  const AdamArgs&);
-void launch_sgd(hipStream_t, const float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd);
+void launch_sgd(hipStream_t, float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd);
 // v = D . gmeta, then eps = alpha/||v|| -> scalars[0], ||v|| -> scalars[1], status[0] = (norm unusable)
 void launch_adapt_norm(hipStream_t, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
                        double* partial /*[EW_MAX_BLOCKS]*/, int64_t n, const AdaptArgs&, float alpha, float* scalars,

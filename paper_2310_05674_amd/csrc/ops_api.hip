@@ -46,7 +46,7 @@ sama_status sama_op_gemm_bf16_batch(int32_t count, const void* const* A, const v
   return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
 }
 
-sama_status sama_op_adam(const float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16, int64_t t,
+sama_status sama_op_adam(float* g, float* m, float* v, float* theta, void* theta16, int64_t n, int64_t n16, int64_t t,
                          float lr, float beta1, float beta2, float eps, float weight_decay, void* hip_stream) {
   if (!g || !m || !v || !theta || n < 0 || n16 < 0 || n16 > n || t < 1) return SAMA_EINVAL;
   if (((uintptr_t)g | (uintptr_t)m | (uintptr_t)v | (uintptr_t)theta) & 15 || ((uintptr_t)theta16 & 7)) return SAMA_EINVAL;

@@ -17,7 +17,7 @@ def make_pair(wl, theta0, lambda0, **over):
     from oracle.reweight import SamaOracle, ADAM, SGD
     kw = dict(base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
               adam_eps=wl.adam_eps)
-    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps")})
+    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps", "weight_decay")})
     base_opt = over.get("base_opt", "adam")
     adapt = over.get("adapt_mode", 0)
     corr = {k: over[k] for k in ("corr_hidden", "corr_kappa") if k in over}

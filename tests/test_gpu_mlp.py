@@ -142,6 +142,29 @@ def test_sgd_and_no_adaptation_variants(variant):
     gpu.close()
 
 
+@pytest.mark.parametrize("base_opt", ["adam", "sgd"])
+def test_weight_decay_enters_the_kept_gradient(base_opt):
+    """L2 term in front of the solver (the wdecay column of App. B): the G state, and through it the adaptation of
+    Eq. 4, carry g + weight_decay * theta.  The decay is large enough that dropping it anywhere breaks the bars."""
+    wl = make_workload(1)
+    kw = dict(base_opt=base_opt, weight_decay=0.5)
+    if base_opt == "sgd":
+        kw["base_lr"] = 0.05
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl), **kw)
+    ref, _unused = make_pair(wl, init_theta(wl), init_lambda(wl), **dict(kw, weight_decay=0.0))
+    _unused.close()
+    tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
+    for _ in range(3):
+        orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+        ref.base_step(wl.x_train, wl.y_train)
+        assert rel_l2(pull(gpu, "G"), orc.g) < TOL and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    assert rel_l2(ref.g, orc.g) > 0.1          # the term matters at this size
+    r = orc.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta); gpu.meta_step(tb, mb)
+    assert rel_l2(pull(gpu, "VDIR"), r["v"]) < TOL
+    assert rel_l2(pull(gpu, "HYPERGRAD"), r["h"]) < TOL and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    gpu.close()
+
+
 def test_ragged_shapes():
     """Widths and batch sizes that are not multiples of any tile (67-33-5, batches 37 / 19)."""
     from datagen.workloads import Workload
