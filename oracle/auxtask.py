@@ -46,6 +46,7 @@ class AuxTaskOracle(SamaOracle):
         g = g + self.weight_decay * self.theta
         self.g = g
         self.t += 1
+        self.lr_step = self.base_lr          # a scheduler may change base_lr between steps (lr_scheduler column, App. B)
         if self.base_opt == ADAM:
             self.theta, self.m, self.v = optim.adam_update(self.theta, self.m, self.v, g, self.t, self.base_lr,
                                                            self.beta1, self.beta2, self.adam_eps)

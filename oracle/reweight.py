@@ -27,6 +27,7 @@ class SamaOracle:
         self.meta_t = 0
         self.base_opt, self.base_lr, self.beta1, self.beta2, self.adam_eps = base_opt, base_lr, beta1, beta2, adam_eps
         self.meta_lr, self.meta_beta1, self.meta_beta2, self.meta_eps = meta_lr, meta_beta1, meta_beta2, meta_eps
+        self.lr_step = base_lr               # the rate of the last base step
         self.alpha, self.adapt_mode = alpha, adapt_mode
         # reading: the base optimizer's weight decay (the "wdecay" column of the hyperparameter tables of App. B) is an L2
         # term, weight_decay * theta added to the gradient before the solver; g, as kept for the adaptation, includes it
@@ -57,6 +58,7 @@ class SamaOracle:
         g = g + self.weight_decay * self.theta
         self.g = g
         self.t += 1
+        self.lr_step = self.base_lr          # a scheduler may change base_lr between steps (lr_scheduler column, App. B)
         if self.base_opt == ADAM:
             self.theta, self.m, self.v = optim.adam_update(self.theta, self.m, self.v, g, self.t, self.base_lr,
                                                            self.beta1, self.beta2, self.adam_eps)
@@ -68,13 +70,14 @@ class SamaOracle:
     def adaptation(self):
         """du/dg on the diagonal from the LAST base step's gradient and its post-update moments
         (reading: no extra backward pass is spent on re-evaluating g at the updated theta, in
-        keeping with the three-pass count of Sec. 3.3)."""
+        keeping with the three-pass count of Sec. 3.3).  gamma is the rate that step used: under
+        a schedule (lr_scheduler column, App. B) base_lr may have moved on since."""
         if self.adapt_mode == optim.ADAPT_NONE:
             return np.ones_like(self.g)
         if self.base_opt == ADAM:
-            return optim.adam_adaptation(self.g, self.m, self.v, self.t, self.base_lr, self.beta1, self.beta2,
+            return optim.adam_adaptation(self.g, self.m, self.v, self.t, self.lr_step, self.beta1, self.beta2,
                                          self.adam_eps)
-        return optim.sgd_adaptation(self.g, self.base_lr)
+        return optim.sgd_adaptation(self.g, self.lr_step)
 
     def targets(self, theta, x, y):
         """What the base loss compares the prediction with: the labels themselves, or the corrected soft labels

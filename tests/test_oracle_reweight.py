@@ -212,3 +212,40 @@ def test_weight_decay_is_an_l2_term_in_front_of_the_solver():
     fd = (up(b.g + d) - up(b.g - d)) / (2 * d)
     keep = np.abs(b.v) > 1e-12
     assert np.allclose(D[keep], fd[keep], rtol=2e-4, atol=1e-10)
+
+
+def test_scheduled_rate_and_the_adaptation_use_the_rate_of_the_step():
+    """lr_scheduler of the base optimizer (App. B tables): base_lr may change between base steps.  Each step moves by
+    the rate in force when it ran (SGD by hand), and gamma in the adaptation is the rate of the step it differentiates,
+    also after the schedule has moved on; a constant schedule is the unscheduled oracle bit for bit."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    rates = [0.05, 0.02, 0.08]
+    o = SamaOracle(model, th, lam, base_opt=SGD, base_lr=rates[0])
+    cur = th.copy()
+    for lr in rates:
+        o.base_lr = lr
+        l = model.losses(cur, x, y)
+        _, g = model.loss_grad(cur, x, y, wnet.weights(l, lam) / len(y))
+        o.base_step(x, y)
+        cur = cur - lr * g
+        assert np.allclose(o.theta, cur, rtol=0, atol=1e-15)
+    o.base_lr = 123.0                                 # the scheduler's next value: not the last step's
+    assert np.array_equal(o.adaptation(), np.full_like(th, rates[-1]))
+    a = SamaOracle(model, th, lam, base_lr=rates[0])
+    for lr in rates:
+        a.base_lr = lr
+        a.base_step(x, y)
+    a.base_lr = 123.0
+    m_prev = (a.m - (1 - a.beta1) * a.g) / a.beta1
+    v_prev = (a.v - (1 - a.beta2) * a.g ** 2) / a.beta2
+    d = 1e-7 * (1 + np.abs(a.g))
+    up = lambda gg: -optim.adam_update(th * 0, m_prev, v_prev, gg, a.t, rates[-1], a.beta1, a.beta2, 0.0)[0]
+    fd = (up(a.g + d) - up(a.g - d)) / (2 * d)
+    keep = np.abs(a.v) > 1e-12
+    assert np.allclose(a.adaptation()[keep], fd[keep], rtol=2e-4, atol=1e-10)
+    c0 = SamaOracle(model, th, lam, base_lr=0.03); c1 = SamaOracle(model, th, lam, base_lr=0.5)
+    for _ in range(3):
+        c1.base_lr = 0.03
+        c0.base_step(x, y); c1.base_step(x, y)
+    r0 = c0.meta_step(x, y, xm, ym); r1 = c1.meta_step(x, y, xm, ym)
+    assert np.array_equal(r0["h"], r1["h"]) and np.array_equal(c0.theta, c1.theta)
