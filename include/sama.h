@@ -193,6 +193,13 @@ sama_status sama_aux_meta_grad(sama_ctx* ctx, const sama_aux_batch* pt, const sa
                                float* hypergrad_out /*DEVICE*/, float* eps_out /*DEVICE*/);
 sama_status sama_aux_meta_step(sama_ctx* ctx, const sama_aux_batch* pt, const sama_batch* meta);
 
+/* Learning-rate schedule hook (the lr_scheduler column of the App. B tables: cosine, linear decay with warm-up, ...;
+ * the schedule itself is the caller's).  base_lr applies from the next base step, meta_lr from the next meta update;
+ * the adaptation of Eq. 4 keeps using the rate of the base step it differentiates, whenever this is called.  Host
+ * side only, nothing is enqueued; both must be finite and > 0.  Rates are kernel arguments: a captured graph replays
+ * with the rates in force at capture. */
+sama_status sama_set_lr(sama_ctx* ctx, float base_lr, float meta_lr);
+
 /* Copy a state vector out of / into the context (DEVICE pointers; sizes above).  Enqueued on the context's
  * stream.  sama_set_state(COUNTERS) synchronises the stream (the base step count lives on the host);
  * setting THETA also refreshes the bf16 working copy.  SCALARS, LOSSES, HYPERGRAD, GLAM_* are read-only. */

@@ -103,6 +103,7 @@ def load_library():
     L.sama_op_gemm_bf16.argtypes = [vp, i64, i32, vp, vp, i64, i32, i32, i32, i32, vp, vp, vp, i64, vp]
     L.sama_op_gemm_bf16_batch.restype = C.c_int
     L.sama_op_gemm_bf16_batch.argtypes = [i32, vp, vp, vp, vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), i32, i32, vp]
+    L.sama_set_lr.restype = C.c_int; L.sama_set_lr.argtypes = [vp, f32, f32]
     L.sama_op_adam.restype = C.c_int
     L.sama_op_adam.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, f32, f32, f32, f32, vp]
     L.sama_op_adapt_norm.restype = C.c_int
@@ -189,6 +190,9 @@ class Sama:
 
     def meta_step(self, train, meta):
         self._check(self.lib.sama_meta_step(self.h, C.byref(train), C.byref(meta)))
+
+    def set_lr(self, base_lr, meta_lr):
+        self._check(self.lib.sama_set_lr(self.h, base_lr, meta_lr))
 
     def aux_batch(self, ids, mask_row, mask_tgt):
         """Device int32 tensors (ids [n_seq, S], mask_row [n_mask] = sequence * S + position, mask_tgt [n_mask]) ->

@@ -76,6 +76,7 @@ struct sama_ctx {
   // auxiliary task: concatenated [ft | pt] batch, per-position losses (two stacked passes) and coefficients
   int32_t *ids_cat, *y_cat; uint8_t* mask_cat; float *loss_pos, *coef_pos;
   int64_t t;  // base step count (host)
+  float lr_step = 0.f;           // base_lr of the last base step (a schedule may have moved cfg.base_lr since)
   bool lo_is_residual = false;   // lo_p holds bf16(theta - bf16(theta)) of the current theta (written by the last Adam step)
   std::string err;
 };
@@ -233,6 +234,7 @@ static void base_update_rest(sama_ctx* c, UpdateSink& sink) {
   }
   if (pos < c->n) base_update_range(c, st, sink.t, pos, c->n - pos);
   c->t = sink.t;   // the device's counter was advanced by launch_step_scalars at the start of the step
+  c->lr_step = c->cfg.base_lr;
   c->lo_is_residual = c->bf16 && c->cfg.base_opt == SAMA_OPT_ADAM && !c->cfg.fast_meta_pass;
 }
 
@@ -380,12 +382,12 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
   launch_sample_stage(st, sa);
   AdaptArgs ad{};
   if (f.adapt_mode == SAMA_ADAPT_NONE) { ad.mode = 1; ad.scalar = 1.f; }
-  else if (f.base_opt == SAMA_OPT_SGD) { ad.mode = 1; ad.scalar = f.base_lr; }
+  else if (f.base_opt == SAMA_OPT_SGD) { ad.mode = 1; ad.scalar = c->lr_step; }
   else {
     const double c1 = 1.0 / (1.0 - pow((double)f.beta1, (double)c->t));
     const double c2 = 1.0 / sqrt(1.0 - pow((double)f.beta2, (double)c->t));
     ad.mode = 0; ad.one_m_beta1 = (float)(1.0 - (double)f.beta1); ad.one_m_beta2 = (float)(1.0 - (double)f.beta2);
-    ad.lr_c1_c2 = (float)((double)f.base_lr * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
+    ad.lr_c1_c2 = (float)((double)c->lr_step * c1 * c2); ad.c2 = (float)c2; ad.eps = f.adam_eps;
     ad.dev = c->step;
   }
   // v = D . g_meta layer by layer while the backward pass still runs, the rest after it, then the norm
@@ -598,9 +600,18 @@ sama_status sama_set_state(sama_ctx* c, int32_t which, const void* src) {
       return fail(c, SAMA_EHIP, "sama_set_state: counter read-back failed");
     if (host[0] < 0 || host[1] < 0) return fail(c, SAMA_EINVAL, "negative counters");
     c->t = host[0];
+    c->lr_step = c->cfg.base_lr;   // a state put in from outside is taken to have been reached at the rate in force
     launch_step_scalars(c->stream, c->counters, 0, c->cfg.base_lr, c->cfg.beta1, c->cfg.beta2, c->step);
   }
   return check_hip(c, "sama_set_state");
+}
+
+sama_status sama_set_lr(sama_ctx* c, float base_lr, float meta_lr) {
+  if (!c) return SAMA_EINVAL;
+  if (!(base_lr > 0.f) || !(meta_lr > 0.f) || !isfinite(base_lr) || !isfinite(meta_lr))
+    return fail(c, SAMA_EINVAL, "base_lr and meta_lr must be finite and > 0");
+  c->cfg.base_lr = base_lr; c->cfg.meta_lr = meta_lr;
+  return SAMA_OK;
 }
 
 int32_t sama_profile_family_count(void) { return F_COUNT; }

@@ -165,6 +165,39 @@ def test_weight_decay_enters_the_kept_gradient(base_opt):
     gpu.close()
 
 
+@pytest.mark.parametrize("base_opt", ["adam", "sgd"])
+def test_scheduled_rates(base_opt):
+    """lr_scheduler of App. B through sama_set_lr: every base step runs at the rate set before it, the meta update at the
+    meta rate set before it, and the adaptation keeps the rate of the base step it differentiates even when the next
+    value has been set already.  Rates differ by up to 4x, so a stale or early rate breaks the bars."""
+    import paper_2310_05674_amd as pkg
+    wl = make_workload(1)
+    scale = 5.0 if base_opt == "sgd" else 1.0
+    base = [wl.base_lr * scale * f for f in (1.0, 0.25, 0.6, 0.4, 1.0)]
+    meta = [wl.meta_lr * f for f in (1.0, 2.0, 0.5, 1.0, 1.0)]
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl), base_opt=base_opt, base_lr=base[0])
+    tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
+    with pytest.raises(pkg.SamaError):
+        gpu.set_lr(0.0, 1e-3)
+    with pytest.raises(pkg.SamaError):
+        gpu.set_lr(1e-3, float("nan"))
+    for _ in range(2):                                  # history: the adaptation of the very first Adam step is zero
+        orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+    lam0 = orc.lam.copy()
+    for k in range(4):
+        orc.base_lr, orc.meta_lr = base[k], meta[k]
+        gpu.set_lr(base[k], meta[k])
+        orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+        assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+        orc.base_lr = base[k + 1]                       # the scheduler has moved on before the meta step
+        gpu.set_lr(base[k + 1], meta[k])
+        r = orc.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta); gpu.meta_step(tb, mb)
+        assert rel_l2(pull(gpu, "VDIR"), r["v"]) < 1e-3, (k, rel_l2(pull(gpu, "VDIR"), r["v"]))
+        assert rel_l2(pull(gpu, "HYPERGRAD"), r["h"]) < 1e-3      # free running, as in the trajectory test
+        assert rel_l2(pull(gpu, "LAMBDA") - lam0, orc.lam - lam0) < 1e-3 and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    gpu.close()
+
+
 def test_ragged_shapes():
     """Widths and batch sizes that are not multiples of any tile (67-33-5, batches 37 / 19)."""
     from datagen.workloads import Workload
