@@ -192,14 +192,18 @@ __global__ __launch_bounds__(EW_THREADS) void k_adapt_norm(const float* __restri
 // Second stage: fixed-order sum of the per-block partials in double, eps = alpha / ||v||.
 // scalars[0] = eps, scalars[1] = ||v||.  A zero or non-finite norm gives eps = 0 and raises status[0] = 1
 // (status is cleared to 0 otherwise), which turns the rest of the meta step into a no-op.
-__global__ __launch_bounds__(256) void k_eps_from_partials(const double* __restrict__ partial, int nparts, float alpha,
-                                                           float* __restrict__ scalars, int64_t* __restrict__ status) {
-  __shared__ double red[256];
-  double s = 0.0;
-  for (int i = threadIdx.x; i < nparts; i += 256) s += partial[i];
-  red[threadIdx.x] = s;
+__global__ __launch_bounds__(1024) void k_eps_from_partials(const double* __restrict__ partial, int nparts, float alpha,
+                                                            float* __restrict__ scalars, int64_t* __restrict__ status) {
+  __shared__ double red[1024];
+  double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;   // four loads in flight per thread: the sweep is latency-bound
+  int i = threadIdx.x;
+  for (; i + 3072 < nparts; i += 4096) {
+    s0 += partial[i]; s1 += partial[i + 1024]; s2 += partial[i + 2048]; s3 += partial[i + 3072];
+  }
+  for (; i < nparts; i += 1024) s0 += partial[i];
+  red[threadIdx.x] = (s0 + s1) + (s2 + s3);
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (int o = 512; o > 0; o >>= 1) {
     if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
     __syncthreads();
   }
@@ -399,7 +403,7 @@ void launch_adapt_norm(hipStream_t st, const float* g, const float* m, const flo
   const int grid = ew_grid(n);
   ProfScope ps(st, F_ADAPT_NORM, (a.mode == 0 ? 20.0 : 8.0) * n);
   k_adapt_norm<<<grid, EW_THREADS, 0, st>>>(g, m, v, gmeta, vdir, partial, n, a);
-  k_eps_from_partials<<<1, 256, 0, st>>>(partial, grid, alpha, scalars, status);
+  k_eps_from_partials<<<1, 1024, 0, st>>>(partial, grid, alpha, scalars, status);
 }
 int launch_adapt_slice(hipStream_t st, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
                        double* partial, int64_t n, const AdaptArgs& a, int max_blocks) {
@@ -411,7 +415,7 @@ int launch_adapt_slice(hipStream_t st, const float* g, const float* m, const flo
   return grid;
 }
 void launch_eps_from_partials(hipStream_t st, const double* partial, int count, float alpha, float* scalars, int64_t* status) {
-  k_eps_from_partials<<<1, 256, 0, st>>>(partial, count, alpha, scalars, status);
+  k_eps_from_partials<<<1, 1024, 0, st>>>(partial, count, alpha, scalars, status);
 }
 void launch_perturb_lo(hipStream_t st, const float* theta, const float* vdir, const float* eps_ptr, bf16_t* lo_p,
                        bf16_t* lo_m, int64_t n16) {
