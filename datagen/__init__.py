@@ -7,4 +7,4 @@ parameters / batches, and bit-level helpers (bf16 rounding of *inputs*).
 from .rng import CounterRNG, mix64
 from .workloads import (WORKLOADS, Workload, make_workload, param_count,
                         param_layout, init_theta, init_lambda, init_lambda_corr, round_to_bf16,
-                        flip_labels, make_aux_batch, make_aux_workload, AUX_TASK)
+                        flip_labels, make_aux_batch, make_aux_workload, AUX_TASK, seq_lengths)

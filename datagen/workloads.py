@@ -14,6 +14,7 @@ BASE_SEED = 20231005
 S_X, S_TEACHER, S_FLIP_PERM, S_FLIP_LABEL, S_XMETA, S_MEANS, S_CLASS, S_CLASS_META = 1, 2, 3, 4, 5, 6, 7, 8
 S_TOK, S_TOK_META, S_THETA, S_LAMBDA, S_LAMBDA_CORR, S_EPOCH_PERM = 9, 10, 11, 12, 13, 1000
 S_TOK_AUX, S_AUX_COUNT, S_AUX_PERM = 14, 15, 2000000
+S_LENGTHS = 16
 
 
 @dataclass
@@ -232,6 +233,15 @@ def make_aux_batch(wl, step, n_pt, lo=0.10, hi=0.20):
     tgt = ids[seq, pos].astype(np.int32)
     ids[seq, pos] = V - 1
     return ids, seq, pos, tgt
+
+
+def seq_lengths(seed, n, S, lo=0.15):
+    """A length mix for n padded sequences of at most S tokens, as short texts give it: log-uniform between lo*S and
+    2*S, cut at S, so that about a quarter of the sequences fill all S positions (truncated texts) and the rest spread
+    down to a few tokens.  int32 [n], each in [1, S]."""
+    u = CounterRNG(seed).uniform(S_LENGTHS, n)
+    a, b = np.log(max(lo * S, 1.0)), np.log(2.0 * S)
+    return np.clip(np.floor(np.exp(a + (b - a) * u)), 1, S).astype(np.int32)
 
 
 def make_workload(cfg, n_train=None, n_meta=None, **override):

@@ -13,7 +13,7 @@ One base step takes one finetuning batch and one pretraining batch; the theta+- 
 batch only, because the finetuning term of the base loss does not depend on lambda.
 """
 import numpy as np
-from . import optim, sama_core, wnet
+from . import models, optim, sama_core, wnet
 from .reweight import SamaOracle, ADAM
 
 
@@ -29,13 +29,14 @@ def seq_losses(l_pos, seq, n_pt):
 
 class AuxTaskOracle(SamaOracle):
     """Batches: ft = (ids_ft [n_ft, S], y_ft [n_ft]); pt = (ids_pt [n_pt, S], seq, pos, tgt) with masked position j at
-    (seq[j], pos[j]) of ids_pt and target token tgt[j]."""
+    (seq[j], pos[j]) of ids_pt and target token tgt[j].  ids_ft, ids_pt and the meta batch's ids may each be a
+    models.with_lengths(ids, lens) pair (padded sequences)."""
 
     def base_step(self, ft, pt):
         ids_ft, y_ft = ft
         ids_pt, seq, pos, tgt = pt
-        n_ft, n_pt = len(ids_ft), len(ids_pt)
-        ids = np.concatenate([ids_ft, ids_pt], axis=0)
+        n_ft, n_pt = len(models.split_lengths(ids_ft)[0]), len(models.split_lengths(ids_pt)[0])
+        ids = models.cat_inputs(ids_ft, ids_pt)
         l_pos = self.model.mlm_losses(self.theta, ids_pt, seq, pos, tgt)
         l_seq, cnt = seq_losses(l_pos, seq, n_pt)
         w = wnet.weights(l_seq, self.lam)
@@ -58,13 +59,13 @@ class AuxTaskOracle(SamaOracle):
         """The scalar the base step descends (for checks)."""
         ids_ft, y_ft = ft
         ids_pt, seq, pos, tgt = pt
-        l_seq, _ = seq_losses(self.model.mlm_losses(theta, ids_pt, seq, pos, tgt), seq, len(ids_pt))
+        l_seq, _ = seq_losses(self.model.mlm_losses(theta, ids_pt, seq, pos, tgt), seq, len(models.split_lengths(ids_pt)[0]))
         return float(np.mean(self.model.losses(theta, ids_ft, y_ft))) + wnet.base_loss(l_seq, lam)
 
     def glam(self, theta, pt):
         """dL_base/dlambda: only the weighted pretraining term depends on lambda."""
         ids_pt, seq, pos, tgt = pt
-        l_seq, _ = seq_losses(self.model.mlm_losses(theta, ids_pt, seq, pos, tgt), seq, len(ids_pt))
+        l_seq, _ = seq_losses(self.model.mlm_losses(theta, ids_pt, seq, pos, tgt), seq, len(models.split_lengths(ids_pt)[0]))
         return wnet.base_loss_grad_lambda(l_seq, self.lam, None)
 
     def meta_grad(self, pt, meta):

@@ -106,9 +106,38 @@ def _dgelu(a):
     return 0.5 * (1.0 + erf(a / np.sqrt(2.0))) + a * np.exp(-0.5 * a * a) / np.sqrt(2.0 * np.pi)
 
 
+def with_lengths(ids, lens):
+    """An encoder input with padding: ids [B, S] and the number of real tokens of each sequence.  Every method of
+    Encoder that takes `ids` takes this pair as well."""
+    ids, lens = np.asarray(ids), np.asarray(lens)
+    assert ids.ndim == 2 and lens.shape == (ids.shape[0],) and lens.min() >= 1 and lens.max() <= ids.shape[1]
+    return (ids, lens)
+
+
+def split_lengths(x):
+    """(ids, lens or None) of an encoder input."""
+    if isinstance(x, tuple):
+        return np.asarray(x[0]), np.asarray(x[1])
+    return np.asarray(x), None
+
+
+def cat_inputs(a, b):
+    """Two encoder inputs stacked along the batch axis (lengths kept if either has them)."""
+    (ia, la), (ib, lb) = split_lengths(a), split_lengths(b)
+    ids = np.concatenate([ia, ib], axis=0)
+    if la is None and lb is None:
+        return ids
+    S = ids.shape[1]
+    la = np.full(len(ia), S) if la is None else la
+    lb = np.full(len(ib), S) if lb is None else lb
+    return (ids, np.concatenate([la, lb]))
+
+
 class Encoder:
     """Post-LN encoder: x0 = LN(tok[ids] + pos); per layer x <- LN1(x + Attn(x)), x <- LN2(x + FFN(x));
-    logits = x_L[:, 0] Wc^T + bc.  erf-GELU, LN eps 1e-5, softmax(q k^T / sqrt(d_h)), no masks.
+    logits = x_L[:, 0] Wc^T + bc.  erf-GELU, LN eps 1e-5, softmax(q k^T / sqrt(d_h)).  Padding (reading: the usual
+    key-padding mask of text batches, which the paper's language-model workloads imply): with lengths given
+    (with_lengths), keys at positions >= len_b get no attention weight; nothing else changes.
     mlm=True adds the masked-token head of the auxiliary task (Sec. 4.3): token logits x_L[b, s] Wmlm^T + bmlm at the
     masked positions (reading: an untied linear decoder on the last LayerNorm's output)."""
     LN_EPS = 1e-5
@@ -145,8 +174,10 @@ class Encoder:
         return theta[off:off + int(np.prod(shape))].reshape(shape)
 
     def _forward(self, theta, ids, keep):
+        ids, lens = split_lengths(ids)
         P = lambda name: self.get(theta, name)
         B, S = ids.shape
+        pad = None if lens is None else (np.arange(S)[None, :] >= lens[:, None])[:, None, None, :]   # [B,1,1,S] keys
         d, nh = self.d, self.heads
         dh = d // nh
         cache = []
@@ -156,6 +187,8 @@ class Encoder:
             qkv = x @ P(p + "Wqkv").T + P(p + "bqkv")                      # [B,S,3d]
             q, k, v = (qkv[..., i * d:(i + 1) * d].reshape(B, S, nh, dh).transpose(0, 2, 1, 3) for i in range(3))
             s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(dh)               # [B,nh,S,S]
+            if pad is not None:
+                s = np.where(pad, -np.inf, s)
             s = s - s.max(axis=-1, keepdims=True)
             pr = np.exp(s)
             pr /= pr.sum(axis=-1, keepdims=True)
@@ -171,7 +204,7 @@ class Encoder:
         return logits, (c0, cache, x)
 
     def logits(self, theta, ids):
-        return self._forward(theta, np.asarray(ids), False)[0]
+        return self._forward(theta, ids, False)[0]
 
     def losses(self, theta, ids, y):
         return _ce(self.logits(theta, ids), y)
@@ -181,7 +214,7 @@ class Encoder:
 
     def mlm_losses(self, theta, ids, seq, pos, tgt):
         """Cross-entropy over the vocabulary at each masked position (seq[j], pos[j]) against tgt[j]."""
-        xL = self._forward(theta, np.asarray(ids), False)[1][2]
+        xL = self._forward(theta, ids, False)[1][2]
         return _ce(self.mlm_logits(xL, theta, seq, pos), tgt)
 
     def loss_grad(self, theta, ids, y, coef):
@@ -192,14 +225,15 @@ class Encoder:
     def loss_grad_mlm(self, theta, ids, y, coef, seq, pos, tgt, coef_pos):
         """(l, l_pos, g): classification losses l_i, masked-token losses l_pos_j, and
         g = d/dtheta [sum_i coef_i l_i + sum_j coef_pos_j l_pos_j] from ONE forward/backward over `ids`."""
-        ids = np.asarray(ids)
+        x_in = ids
+        ids = split_lengths(ids)[0]
         P = lambda name: self.get(theta, name)
         g = np.zeros(self.n)
         G = lambda name: self.get(g, name)
         B, S = ids.shape
         d, nh = self.d, self.heads
         dh = d // nh
-        logits, (c0, cache, xL) = self._forward(theta, ids, True)
+        logits, (c0, cache, xL) = self._forward(theta, x_in, True)
         l = _ce(logits, y)
         dlog = _dce(logits, y, np.asarray(coef, dtype=np.float64))        # [B,C]
         G("Wc")[...] = dlog.T @ xL[:, 0, :]

@@ -86,3 +86,12 @@ def test_bf16_rounding():
     assert np.all(np.abs(r - x) <= np.abs(x) * 2**-8)
     th = init_theta(make_workload(3, n_train=8, n_meta=8))
     assert np.all(th.astype(np.float32).view(np.uint32) & 0xFFFF == 0)
+
+
+def test_sequence_length_mix():
+    from datagen import seq_lengths
+    l = seq_lengths(77, 4000, 128)
+    assert l.dtype == np.int32 and l.min() >= 1 and l.max() == 128
+    assert 0.2 < np.mean(l == 128) < 0.35 and 40 < np.median(l) < 100       # a quarter truncated, the rest spread out
+    assert np.array_equal(l, seq_lengths(77, 4000, 128)) and not np.array_equal(l, seq_lengths(78, 4000, 128))
+    assert seq_lengths(3, 50, 4).min() >= 1

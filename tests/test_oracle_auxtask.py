@@ -112,6 +112,34 @@ def test_base_gradient_and_glam_are_gradients_of_the_scalar_base_loss():
         assert abs(fd - orc.g[k]) < 2e-7 * (1 + abs(orc.g[k])), (k, fd, orc.g[k])
 
 
+def test_padded_batches_in_the_assembled_base_step():
+    """Sequence lengths on both halves of the stacked batch: the base gradient is still the gradient of the scalar base
+    loss (directional differences), and it differs from the unpadded one."""
+    enc, th, ft, pt, lam = _setup()
+    ids_pt, seq, pos, tgt = pt
+    ftl = (models.with_lengths(ft[0], np.array([8, 3, 6])), ft[1])
+    ptl = (models.with_lengths(ids_pt, np.array([6, 8, 8, 7])), seq, pos, tgt)     # every masked position is a real token
+    orc = AuxTaskOracle(enc, th, lam, base_lr=1e-2)
+    ref = AuxTaskOracle(enc, th, lam, base_lr=1e-2)
+    Lb = orc.base_step(ftl, ptl); ref.base_step(ft, pt)
+    assert abs(Lb - orc.base_loss(th, lam, ftl, ptl)) < 1e-12 * abs(Lb)
+    assert np.linalg.norm(orc.g - ref.g) > 1e-2 * np.linalg.norm(ref.g)
+    l_seq, _ = seq_losses(enc.mlm_losses(th, ptl[0], seq, pos, tgt), seq, 4)
+    w = wnet.weights(l_seq, lam)
+
+    def S(t):
+        ls, _ = seq_losses(enc.mlm_losses(t, ptl[0], seq, pos, tgt), seq, 4)
+        return float(np.mean(enc.losses(t, ftl[0], ftl[1])) + np.mean(w * ls))
+    r = CounterRNG(31)
+    for k in range(4):
+        u = r.normal(k, enc.n); u /= np.linalg.norm(u)
+        fd = (S(th + 1e-6 * u) - S(th - 1e-6 * u)) / 2e-6
+        assert abs(fd - orc.g @ u) < 1e-7 * (1 + abs(fd)), (k, fd, orc.g @ u)
+    # the +- passes see the lengths too
+    r1 = orc.meta_grad(ptl, ftl); r0 = orc.meta_grad(pt, ftl)
+    assert np.linalg.norm(r1["h"] - r0["h"]) > 1e-3 * np.linalg.norm(r0["h"])
+
+
 def test_constant_weights_give_plain_multitask_gradient_and_zero_hypergradient_rows():
     """W2 = 0: w = sigmoid(b2) for every sequence, so the base gradient is that of L_ft + sigmoid(b2) mean L_pt, and only
     the rows of dL_base/dlambda that do not vanish with W2 = 0 (W2 itself and b2) are non-zero."""

@@ -61,9 +61,9 @@ def test_mlp_vs_torch_autograd():
     assert np.allclose(g, t.grad.numpy(), rtol=1e-10, atol=1e-13)
 
 
-def _torch_encoder_losses(enc, th, ids, y):
+def _torch_encoder_losses(enc, th, ids, y, lens=None):
     """The same classifier assembled from torch.nn library layers (post-LN TransformerEncoderLayer,
-    exact GELU), float64, parameters sliced out of one flat leaf tensor."""
+    exact GELU), float64, parameters sliced out of one flat leaf tensor; lens = the library's key_padding_mask."""
     t = torch.tensor(th, dtype=torch.float64, requires_grad=True)
 
     def P(name):
@@ -72,13 +72,15 @@ def _torch_encoder_losses(enc, th, ids, y):
     F = torch.nn.functional
     ids_t = torch.tensor(np.asarray(ids), dtype=torch.long)
     B, S = ids_t.shape
+    kpm = None if lens is None else torch.arange(S)[None, :] >= torch.tensor(np.asarray(lens))[:, None]
     x = F.embedding(ids_t, P("tok_emb")) + P("pos_emb")[:S]
     x = F.layer_norm(x, (enc.d,), P("emb_ln_g"), P("emb_ln_b"), 1e-5)
     for l in range(enc.L):
         p = f"l{l}."
         xs = x.transpose(0, 1)                                    # [S,B,d] for the functional MHA
         a, _ = F.multi_head_attention_forward(xs, xs, xs, enc.d, enc.heads, P(p + "Wqkv"), P(p + "bqkv"), None, None,
-                                              False, 0.0, P(p + "Wo"), P(p + "bo"), training=False, need_weights=False)
+                                              False, 0.0, P(p + "Wo"), P(p + "bo"), training=False, need_weights=False,
+                                              key_padding_mask=kpm)
         x = F.layer_norm(x + a.transpose(0, 1), (enc.d,), P(p + "ln1_g"), P(p + "ln1_b"), 1e-5)
         f = F.linear(F.gelu(F.linear(x, P(p + "W1"), P(p + "b1"))), P(p + "W2"), P(p + "b2"))
         x = F.layer_norm(x + f, (enc.d,), P(p + "ln2_g"), P(p + "ln2_b"), 1e-5)
@@ -107,6 +109,46 @@ def test_encoder_vs_torch_autograd(dims):
     for name, (off, shape) in enc.slices.items():                 # every parameter group on its own scale
         sl = slice(off, off + int(np.prod(shape)))
         assert np.max(np.abs(g[sl] - gt[sl])) <= 1e-9 * (np.max(np.abs(gt[sl])) + 1e-12), name
+
+
+@pytest.mark.parametrize("dims", [(2, 16, 4, 32, 8, 50, 3), (1, 128, 2, 128, 128, 90, 2)])
+def test_encoder_padding_vs_torch_key_padding_mask(dims):
+    """Padded batches: losses and every gradient group against torch's multi-head attention with key_padding_mask;
+    what sits in the padded positions must not matter; ids that occur only as padding get exactly no gradient; full
+    lengths are the unpadded model bit for bit."""
+    enc = models.Encoder(*dims)
+    L, d, heads, ffn, S, V, C = dims
+    th = _theta(enc.n, 15, 0.3)
+    r = CounterRNG(16)
+    B = 5
+    ids = r.integers(1, B * S, V - 1).reshape(B, S); ids[:, 0] = 0
+    lens = np.array([S, 1, S // 2, 3, S - 1])
+    y = r.integers(2, B, C); coef = r.uniform(3, B)
+    t, lt = _torch_encoder_losses(enc, th, ids, y, lens)
+    (lt * torch.tensor(coef)).sum().backward()
+    l, g = enc.loss_grad(th, models.with_lengths(ids, lens), y, coef)
+    assert np.allclose(l, lt.detach().numpy(), rtol=1e-11)
+    gt = t.grad.numpy()
+    for name, (off, shape) in enc.slices.items():
+        sl = slice(off, off + int(np.prod(shape)))
+        assert np.max(np.abs(g[sl] - gt[sl])) <= 1e-9 * (np.max(np.abs(gt[sl])) + 1e-12), name
+    # the mask matters on this input
+    l_nomask = enc.losses(th, ids, y)
+    assert np.max(np.abs(l_nomask - l)) > 1e-3
+    # padded positions: any token there gives the same numbers; the pad token itself gets no gradient
+    ids2 = ids.copy()
+    for b in range(B):
+        ids2[b, lens[b]:] = V - 1
+    l2, g2 = enc.loss_grad(th, models.with_lengths(ids2, lens), y, coef)
+    assert np.allclose(l2, l, rtol=1e-13)
+    tok = enc.slices["tok_emb"][0]
+    others = np.ones(enc.n, dtype=bool); others[tok:tok + V * d] = False
+    assert np.allclose(g2[others], g[others], rtol=1e-11, atol=1e-14)
+    assert np.all(enc.get(g2, "tok_emb")[V - 1] == 0.0)
+    # full lengths = no mask
+    lf, gf = enc.loss_grad(th, models.with_lengths(ids, np.full(B, S)), y, coef)
+    l0, g0 = enc.loss_grad(th, ids, y, coef)
+    assert np.array_equal(lf, l0) and np.array_equal(gf, g0)
 
 
 def test_wnet_vs_torch_and_loops():
