@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--aux", action="store_true",
                     help="auxiliary-task reweighting (Sec. 4.3) instead of the headline workload: the 12-layer encoder with a "
                          "50304-token masked-token head, 16 finetuning + 16 auxiliary sequences per base step")
+    ap.add_argument("--length-mix", action="store_true",
+                    help="encoder workloads: padded batches with a seeded length mix (key-padding mask); padded tokens are "
+                         "still computed, so the rate is that of full sequences")
     ap.add_argument("--graph", action="store_true",
                     help="capture each iteration (unroll base steps + meta step) into a HIP graph once per synthetic batch and time "
                          "replays instead of eager calls")
@@ -92,12 +95,20 @@ def main():
     s = pkg.Sama(cfg, th0, lam0)
     n, n16 = s.n, s.lib.sama_gemm_param_count(__import__("ctypes").byref(cfg))
     batches = []
+    if args.length_mix and (wl.kind != "encoder" or args.aux):
+        raise SystemExit("--length-mix applies to the encoder workloads 3..5 (not to --aux)")
+    from datagen import seq_lengths
+    len_train = seq_lengths(wl.seed + 11, len(wl.y_train), wl.dims[4]) if args.length_mix else None
+    len_meta = seq_lengths(wl.seed + 12, len(wl.y_meta), wl.dims[4]) if args.length_mix else None
+    dl = lambda a: None if a is None else torch.as_tensor(np.ascontiguousarray(a), device=dev)
     for k in range(nb):
         it, im = wl.train_batch(k), wl.meta_batch_idx(k)
         batches.append((s.batch(torch.as_tensor(np.ascontiguousarray(wl.x_train[it]), device=dev),
-                                torch.as_tensor(wl.y_train[it].astype(np.int32), device=dev)),
+                                torch.as_tensor(wl.y_train[it].astype(np.int32), device=dev),
+                                seq_len=dl(None if len_train is None else len_train[it])),
                         s.batch(torch.as_tensor(np.ascontiguousarray(wl.x_meta[im]), device=dev),
-                                torch.as_tensor(wl.y_meta[im].astype(np.int32), device=dev))))
+                                torch.as_tensor(wl.y_meta[im].astype(np.int32), device=dev),
+                                seq_len=dl(None if len_meta is None else len_meta[im]))))
 
     aux = []
     if args.aux:
@@ -158,7 +169,7 @@ def main():
                    ("MLP " + "-".join(map(str, wl.dims)) if wl.kind == "mlp" else
                     "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
                    "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
-                   "launch": "hip graph replay" if args.graph else "eager", "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
+                   "launch": "hip graph replay" if args.graph else "eager", "padding": "length mix" if args.length_mix else "none", "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
                    "last_step_skipped": bool(skipped),
                    "workspace_bytes": int(s.lib.sama_workspace_bytes(__import__("ctypes").byref(cfg)))},
     }
@@ -229,6 +240,8 @@ def main():
         cm = min(cb, wl.meta_batch)
         it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
         x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
+        if args.length_mix:
+            x, xm = models.with_lengths(x, len_train[it]), models.with_lengths(xm, len_meta[im])
         reps = {1: 20, 2: 10, 3: 3}.get(cfg_id, 1)
         if args.aux:
             from oracle.auxtask import AuxTaskOracle

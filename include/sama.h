@@ -33,7 +33,8 @@
  *    MLP  dims = {d0, d1, ..., dL}:    W_0[d1 x d0] ... W_{L-1}[dL x d_{L-1}],  b_0[d1] ... b_{L-1}[dL]
  *         (two dims = multinomial logistic regression; hidden layers use ReLU)
  *    ENCODER dims = {L, d, heads, ffn, S, V, C}  (post-LN, learned positions, erf-GELU, LN eps 1e-5,
- *         softmax(q k^T / sqrt(d/heads)), classifier on the position-0 hidden state):
+ *         softmax(q k^T / sqrt(d/heads)) over the real tokens of a sequence (sama_batch.seq_len), classifier on the
+ *         position-0 hidden state):
  *         per layer l: Wqkv[3d x d] (rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V; head h owns rows h*d/heads..),
  *                      Wo[d x d], W1[ffn x d], W2[d x ffn];
  *         then per layer l: bqkv[3d], bo[d], ln1_g[d], ln1_b[d], b1[ffn], b2[d], ln2_g[d], ln2_b[d];
@@ -108,23 +109,29 @@ typedef struct {
 
 /* One batch.  x: DEVICE, fp32 [n x d0] row-major (MLP) or int32 token ids [n x S] (ENCODER), ids in [0, V).
  * y: DEVICE int32 [n], labels in [0, C).  sample_mask: DEVICE uint8 [n], 1 = use, 0 = ignore, or NULL = use all.
+ * seq_len (ENCODER; ignored by the MLP): DEVICE int32 [n], the number of real tokens of each padded sequence, or NULL =
+ * every sequence fills all S positions.  Keys at positions >= seq_len get no attention weight (key-padding mask);
+ * values are clamped into [1, S]; what sits in the padded positions of x then has no influence on any result.
  * Read-only; owned by the caller. */
 typedef struct {
   const void* x;
   const int32_t* y;
   const uint8_t* sample_mask;
   int32_t n;
+  const int32_t* seq_len;
 } sama_batch;
 
 /* One batch of the auxiliary (masked-token) task.  ids: DEVICE int32 [n_seq x S], the input tokens with the masked
  * positions already replaced by the caller.  mask_row: DEVICE int32 [n_mask], token row sequence * S + position of
  * each masked position, all distinct, every sequence owning at least one; mask_tgt: DEVICE int32 [n_mask], the token
- * to predict there.  Out-of-range rows / targets are clamped into range, not reported.  Read-only; caller-owned. */
+ * to predict there.  Out-of-range rows / targets are clamped into range, not reported.  seq_len: as in sama_batch
+ * ([n_seq] or NULL); masked positions should be real tokens.  Read-only; caller-owned. */
 typedef struct {
   const int32_t* ids;
   const int32_t* mask_row;
   const int32_t* mask_tgt;
   int32_t n_seq, n_mask;
+  const int32_t* seq_len;
 } sama_aux_batch;
 
 /* Selectors of sama_get_state / sama_set_state.  Sizes in elements:

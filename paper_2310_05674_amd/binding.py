@@ -46,7 +46,7 @@ class SamaConfig(C.Structure):
 
 
 class SamaBatch(C.Structure):
-    _fields_ = [("x", C.c_void_p), ("y", C.c_void_p), ("sample_mask", C.c_void_p), ("n", C.c_int32)]
+    _fields_ = [("x", C.c_void_p), ("y", C.c_void_p), ("sample_mask", C.c_void_p), ("n", C.c_int32), ("seq_len", C.c_void_p)]
 
 
 class SamaError(RuntimeError):
@@ -60,7 +60,8 @@ def lib_path():
 
 
 class SamaAuxBatch(C.Structure):
-    _fields_ = [("ids", C.c_void_p), ("mask_row", C.c_void_p), ("mask_tgt", C.c_void_p), ("n_seq", C.c_int32), ("n_mask", C.c_int32)]
+    _fields_ = [("ids", C.c_void_p), ("mask_row", C.c_void_p), ("mask_tgt", C.c_void_p), ("n_seq", C.c_int32), ("n_mask", C.c_int32),
+                ("seq_len", C.c_void_p)]
 
 
 _lib = None
@@ -169,13 +170,17 @@ class Sama:
         if rc != 0:
             raise SamaError(rc, self.lib.sama_last_error(self.h).decode())
 
-    def batch(self, x, y, mask=None):
-        """Device tensors (x fp32 [n, d0] or int32 [n, S]; y int32 [n]; mask uint8 [n] or None) -> sama_batch."""
+    def batch(self, x, y, mask=None, seq_len=None):
+        """Device tensors (x fp32 [n, d0] or int32 [n, S]; y int32 [n]; mask uint8 [n] or None; seq_len int32 [n] or
+        None) -> sama_batch."""
         torch = self.torch
         assert x.is_cuda and y.is_cuda and x.is_contiguous() and y.dtype == torch.int32
         assert x.dtype in (torch.float32, torch.int32)
-        b = SamaBatch(x.data_ptr(), y.data_ptr(), None if mask is None else mask.data_ptr(), int(y.numel()))
-        b._keep = (x, y, mask)
+        if seq_len is not None:
+            assert seq_len.is_cuda and seq_len.is_contiguous() and seq_len.dtype == torch.int32 and seq_len.numel() == y.numel()
+        b = SamaBatch(x.data_ptr(), y.data_ptr(), None if mask is None else mask.data_ptr(), int(y.numel()),
+                      None if seq_len is None else seq_len.data_ptr())
+        b._keep = (x, y, mask, seq_len)
         if mask is not None:
             assert mask.dtype == torch.uint8 and mask.is_cuda and mask.numel() == y.numel()
         return b
@@ -194,15 +199,16 @@ class Sama:
     def set_lr(self, base_lr, meta_lr):
         self._check(self.lib.sama_set_lr(self.h, base_lr, meta_lr))
 
-    def aux_batch(self, ids, mask_row, mask_tgt):
-        """Device int32 tensors (ids [n_seq, S], mask_row [n_mask] = sequence * S + position, mask_tgt [n_mask]) ->
-        sama_aux_batch."""
+    def aux_batch(self, ids, mask_row, mask_tgt, seq_len=None):
+        """Device int32 tensors (ids [n_seq, S], mask_row [n_mask] = sequence * S + position, mask_tgt [n_mask], seq_len
+        [n_seq] or None) -> sama_aux_batch."""
         torch = self.torch
-        for t in (ids, mask_row, mask_tgt):
+        for t in (ids, mask_row, mask_tgt) + (() if seq_len is None else (seq_len,)):
             assert t.is_cuda and t.is_contiguous() and t.dtype == torch.int32
-        assert mask_row.numel() == mask_tgt.numel()
-        b = SamaAuxBatch(ids.data_ptr(), mask_row.data_ptr(), mask_tgt.data_ptr(), int(ids.shape[0]), int(mask_row.numel()))
-        b._keep = (ids, mask_row, mask_tgt)
+        assert mask_row.numel() == mask_tgt.numel() and (seq_len is None or seq_len.numel() == ids.shape[0])
+        b = SamaAuxBatch(ids.data_ptr(), mask_row.data_ptr(), mask_tgt.data_ptr(), int(ids.shape[0]), int(mask_row.numel()),
+                         None if seq_len is None else seq_len.data_ptr())
+        b._keep = (ids, mask_row, mask_tgt, seq_len)
         return b
 
     def aux_base_step(self, ft, pt, loss_out=None):

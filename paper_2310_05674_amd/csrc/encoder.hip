@@ -108,7 +108,7 @@ class EncoderModel : public Model {
       GemmBf16Args g{};
       g.C16 = qkv_[s];
       fwd_linear(st, w, nw, xin, d_, o.Wqkv, 3 * d_, o.bqkv, M, g);
-      launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, nw * B, heads_, d_);
+      launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, nw * B, heads_, d_, b.seq_len, B);
       g = GemmBf16Args{};
       g.res32 = res_[0]; g.C32 = pre1_[s];          // the residual stream stays fp32
       fwd_linear(st, w, nw, ao_[s], d_, o.Wo, d_, o.bo, M, g);
@@ -256,7 +256,7 @@ class EncoderModel : public Model {
       g = dgrad(w, ds1, d_, o.Wo, d_, M);
       g.C16 = do_;
       launch_gemm_bf16(st, g);
-      launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv, B, heads_, d_);
+      launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv, B, heads_, d_, b.seq_len, B);
       wg[3] = wgrad(dqkv, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
       g = dgrad(w, dqkv, 3 * d_, o.Wqkv, d_, M);
       g.res32 = ds32_; g.C32 = dx;                            // gradient w.r.t. the layer input

@@ -276,14 +276,22 @@ __device__ __forceinline__ f32x16 rows_dot_rows(const bf16_t* __restrict__ R, co
 // Forward.  Wave w owns queries 32w..32w+31.  S^T[key][q] tiles leave each lane with one query column, so the
 // softmax over keys is an in-lane reduction plus one cross-half shuffle, and the probability tile is already in
 // the B-operand layout of the 32x32x8 MFMA for O^T[e][q] = sum_key V^T[e][key] P^T[key][q].
+// lens (or null): real tokens of sequence b % lens_period; keys at positions beyond get no weight.
+__device__ __forceinline__ int seq_len_of(const int32_t* __restrict__ lens, int lens_period, int b) {
+  if (lens == nullptr) return AS;
+  const int n = lens[b % lens_period];
+  return n < 1 ? 1 : (n > AS ? AS : n);
+}
+
 __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out, float* __restrict__ lse,
-                                                  int heads, int d) {
+                                                  int heads, int d, const int32_t* __restrict__ lens, int lens_period) {
   __shared__ __attribute__((aligned(16))) bf16_t Vs[AS * SLD];
   const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t ld = 3 * (int64_t)d;
   const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
   const bf16_t* K = Q + d;
   const bf16_t* V = Q + 2 * d;
+  const int len = seq_len_of(lens, lens_period, b);
   stage_rows(V, ld, Vs);
   f32x16 s[4];
 #pragma unroll
@@ -292,7 +300,11 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
 #pragma unroll
   for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[kt][r] *= 0.125f; mx = fmaxf(mx, s[kt][r]); }
+    for (int r = 0; r < 16; ++r) {
+      const int key = 32 * kt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      s[kt][r] = key < len ? s[kt][r] * 0.125f : -3.0e38f;   // exp(-3e38 - mx) = 0: key 0 is always real
+      mx = fmaxf(mx, s[kt][r]);
+    }
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
   float sum = 0.f;
 #pragma unroll
@@ -337,13 +349,15 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
 // The two phases only read what is staged and are independent: waves 0-3 run phase A while waves 4-7 run phase B.
 __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ out,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ lse,
-                                                  bf16_t* __restrict__ dqkv, int heads, int d) {
+                                                  bf16_t* __restrict__ dqkv, int heads, int d, const int32_t* __restrict__ lens,
+                                                  int lens_period) {
   __shared__ __attribute__((aligned(16))) bf16_t Ks[AS * SLD];
   __shared__ __attribute__((aligned(16))) bf16_t Qs[AS * SLD];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[AS * SLD];
   __shared__ float s_D[AS], s_lse[AS];
   const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3;
   const bool phase_a = threadIdx.x < 256;
+  const int len = seq_len_of(lens, lens_period, b);
   const int64_t ld = 3 * (int64_t)d;
   const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
   const bf16_t* K = Q + d;
@@ -390,7 +404,10 @@ __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(vp + 16 * ks), ld_bf16x8(dop + 16 * ks), dp, 0, 0, 0);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) st[r] = __expf(st[r] * 0.125f - lq) * (dp[r] - Dq) * 0.125f;   // dS^T
+      for (int r = 0; r < 16; ++r) {
+        const int key = 32 * kt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        st[r] = key < len ? __expf(st[r] * 0.125f - lq) * (dp[r] - Dq) * 0.125f : 0.f;   // dS^T; a padded key has P = 0
+      }
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const s16x4 dsb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
@@ -434,7 +451,7 @@ __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int q = 32 * qt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const float p = __expf(st[r] * 0.125f - s_lse[q]);
+        const float p = (32 * wave + (lane & 31)) < len ? __expf(st[r] * 0.125f - s_lse[q]) : 0.f;   // this lane's key
         st[r] = p;
         ds[r] = p * (dp[r] - s_D[q]) * 0.125f;
       }
@@ -609,14 +626,15 @@ void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* pa
   launch_colsum_partial_multi(st, &j, 1);
   launch_reduce_rows(st, partial, nrb, N, 0, N, out, nullptr, nullptr);
 }
-void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d) {
+void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d,
+                          const int32_t* lens, int lens_period) {
   ProfScope ps(st, F_ATTN_FWD, 4.0 * B * heads * 128.0 * 128.0 * 64.0);
-  k_attn_fwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, lse, heads, d);
+  k_attn_fwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, lse, heads, d, lens, lens_period > 0 ? lens_period : 1);
 }
 void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
-                          bf16_t* dqkv, int B, int heads, int d) {
+                          bf16_t* dqkv, int B, int heads, int d, const int32_t* lens, int lens_period) {
   ProfScope ps(st, F_ATTN_BWD, 10.0 * B * heads * 128.0 * 128.0 * 64.0);
-  k_attn_bwd<<<dim3(heads, B), 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d);
+  k_attn_bwd<<<dim3(heads, B), 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lens_period > 0 ? lens_period : 1);
 }
 void launch_head_fwd(hipStream_t st, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits) {

@@ -191,10 +191,13 @@ struct ColsumJob { const bf16_t* X; int M, N; float* partial; };
 void launch_colsum_partial_multi(hipStream_t, const ColsumJob* jobs, int count);
 // column sums of a bf16 matrix [M x N] (ld = N) through partial [ceil(M / COLSUM_ROWS)][N]
 void launch_colsum_bf16(hipStream_t, const bf16_t* X, int M, int N, float* partial, float* out);
-// softmax(q k^T / 8) v for S = 128, head width 64; qkv [B*S x 3d] bf16; out [B*S x d] bf16; lse [B][heads][S]
-void launch_attention_fwd(hipStream_t, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d);
+// softmax(q k^T / 8) v for S = 128, head width 64; qkv [B*S x 3d] bf16; out [B*S x d] bf16; lse [B][heads][S].
+// lens (device, or null = all S): sequence b has lens[b % lens_period] real tokens (clamped into [1, S]); keys beyond get
+// no weight.
+void launch_attention_fwd(hipStream_t, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d,
+                          const int32_t* lens, int lens_period);
 void launch_attention_bwd(hipStream_t, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
-                          bf16_t* dqkv, int B, int heads, int d);
+                          bf16_t* dqkv, int B, int heads, int d, const int32_t* lens, int lens_period);
 // classifier on the position-0 hidden state: logits[b][c] = x[b*S] . Wc[c] + bc[c]
 void launch_head_fwd(hipStream_t, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits);
@@ -209,7 +212,8 @@ void launch_embedding_bwd(hipStream_t, const float* demb, const int32_t* ids, in
 // ------------------------------------------------------------------ masked-token head (mlm_head.hip)
 // ids_out = [ids_ft | ids_pt] ([n x S] token rows), y_out = [y_ft | 0], mask_out = [mask_ft (null = ones) | 0]
 void launch_aux_cat(hipStream_t, const int32_t* ids_ft, const int32_t* y_ft, const uint8_t* mask_ft, int n_ft,
-                    const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out, uint8_t* mask_out);
+                    const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out, uint8_t* mask_out,
+                    const int32_t* len_ft, const int32_t* len_pt, int32_t* len_out);
 // out[(k P + j)][:] = X[k pass_rows + row_base + rows[j]][:], j < n_mask, k < nw; rows n_mask..P-1 zero; rows[] is
 // clamped to [0, rows_in_batch)
 void launch_gather_rows(hipStream_t, const bf16_t* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,

@@ -10,16 +10,17 @@ namespace {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// ids_out = [ids_ft | ids_pt], y_out = [y_ft | 0], mask_out = [mask_ft or 1 | 0]
+// ids_out = [ids_ft | ids_pt], y_out = [y_ft | 0], mask_out = [mask_ft or 1 | 0], len_out (if given) = [len_ft or S | len_pt or S]
 __global__ __launch_bounds__(256) void k_aux_cat(const int32_t* ids_ft, const int32_t* y_ft, const uint8_t* mask_ft, int n_ft,
                                                  const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out,
-                                                 uint8_t* mask_out) {
+                                                 uint8_t* mask_out, const int32_t* len_ft, const int32_t* len_pt, int32_t* len_out) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   const int nf = n_ft * S, n = (n_ft + n_pt) * S;
   if (i < n) ids_out[i] = i < nf ? ids_ft[i] : ids_pt[i - nf];
   if (i < n_ft + n_pt) {
     y_out[i] = i < n_ft ? y_ft[i] : 0;
     mask_out[i] = i < n_ft ? (mask_ft ? mask_ft[i] : (uint8_t)1) : (uint8_t)0;
+    if (len_out != nullptr) len_out[i] = i < n_ft ? (len_ft ? len_ft[i] : S) : (len_pt ? len_pt[i - n_ft] : S);
   }
 }
 
@@ -152,9 +153,11 @@ __global__ __launch_bounds__(256) void k_scatter_add_rows(const float* part, int
 }  // namespace
 
 void launch_aux_cat(hipStream_t st, const int32_t* ids_ft, const int32_t* y_ft, const uint8_t* mask_ft, int n_ft,
-                    const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out, uint8_t* mask_out) {
+                    const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out, uint8_t* mask_out,
+                    const int32_t* len_ft, const int32_t* len_pt, int32_t* len_out) {
   ProfScope ps(st, F_OTHER, 8.0 * (n_ft + n_pt) * S);
-  k_aux_cat<<<((n_ft + n_pt) * S + 255) / 256, 256, 0, st>>>(ids_ft, y_ft, mask_ft, n_ft, ids_pt, n_pt, S, ids_out, y_out, mask_out);
+  k_aux_cat<<<((n_ft + n_pt) * S + 255) / 256, 256, 0, st>>>(ids_ft, y_ft, mask_ft, n_ft, ids_pt, n_pt, S, ids_out, y_out, mask_out,
+                                                             len_ft, len_pt, len_out);
 }
 void launch_gather_rows(hipStream_t st, const bf16_t* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
                         int n_mask, int P, int d, int nw, bf16_t* out) {

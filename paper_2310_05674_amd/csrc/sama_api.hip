@@ -74,7 +74,7 @@ struct sama_ctx {
   int64_t* counters;  // {t (mirror), meta_t, status, 0}
   float *logits, *dlogits, *losses;
   // auxiliary task: concatenated [ft | pt] batch, per-position losses (two stacked passes) and coefficients
-  int32_t *ids_cat, *y_cat; uint8_t* mask_cat; float *loss_pos, *coef_pos;
+  int32_t *ids_cat, *y_cat, *len_cat; uint8_t* mask_cat; float *loss_pos, *coef_pos;
   int64_t t;  // base step count (host)
   float lr_step = 0.f;           // base_lr of the last base step (a schedule may have moved cfg.base_lr since)
   bool lo_is_residual = false;   // lo_p holds bf16(theta - bf16(theta)) of the current theta (written by the last Adam step)
@@ -150,10 +150,10 @@ static size_t carve(sama_ctx* c, void* base) {
   c->corr_scratch = c->cfg.corr_hidden > 0 ? ws.take<double>((size_t)c->cfg.max_batch * 2 * C) : nullptr;
   if (c->cfg.aux_mlm) {
     const size_t P = (size_t)(c->cfg.max_aux_masked + 63) / 64 * 64;
-    c->ids_cat = ws.take<int32_t>((size_t)mb * c->cfg.dims[4]); c->y_cat = ws.take<int32_t>(mb); c->mask_cat = ws.take<uint8_t>(mb);
+    c->ids_cat = ws.take<int32_t>((size_t)mb * c->cfg.dims[4]); c->y_cat = ws.take<int32_t>(mb); c->len_cat = ws.take<int32_t>(mb); c->mask_cat = ws.take<uint8_t>(mb);
     c->loss_pos = ws.take<float>(2 * P); c->coef_pos = ws.take<float>(P);
   } else {
-    c->ids_cat = c->y_cat = nullptr; c->mask_cat = nullptr; c->loss_pos = c->coef_pos = nullptr;
+    c->ids_cat = c->y_cat = c->len_cat = nullptr; c->mask_cat = nullptr; c->loss_pos = c->coef_pos = nullptr;
   }
   if (c->model) c->model->plan(ws, mb);
   return ws.used();
@@ -485,8 +485,10 @@ sama_status sama_aux_base_step(sama_ctx* c, const sama_batch* ft, const sama_aux
   (void)hipGetLastError();
   const int S = c->cfg.dims[4], C = c->model->n_classes(), n_ft = ft->n, n_pt = pt->n_seq;
   launch_step_scalars(st, c->counters, 1, c->cfg.base_lr, c->cfg.beta1, c->cfg.beta2, c->step);
-  launch_aux_cat(st, (const int32_t*)ft->x, ft->y, ft->sample_mask, n_ft, pt->ids, n_pt, S, c->ids_cat, c->y_cat, c->mask_cat);
-  const sama_batch cat{c->ids_cat, c->y_cat, c->mask_cat, n_ft + n_pt};
+  const bool padded = ft->seq_len != nullptr || pt->seq_len != nullptr;
+  launch_aux_cat(st, (const int32_t*)ft->x, ft->y, ft->sample_mask, n_ft, pt->ids, n_pt, S, c->ids_cat, c->y_cat, c->mask_cat,
+                 ft->seq_len, pt->seq_len, padded ? c->len_cat : nullptr);
+  const sama_batch cat{c->ids_cat, c->y_cat, c->mask_cat, n_ft + n_pt, padded ? c->len_cat : nullptr};
   const PassWeights w = pass_weights(c, 0.f);
   c->model->forward(st, w, cat, true, c->logits);
   // finetuning term: mean cross-entropy over the ft rows (the auxiliary rows are masked out of the classifier loss)
@@ -520,7 +522,7 @@ static sama_status aux_meta_common(sama_ctx* c, const sama_aux_batch* pt, const 
   const int S = c->cfg.dims[4];
   const bool fused_nudge = meta_direction(c, meta, update);
   // passes 2 and 3 on the auxiliary sequences alone: the finetuning term of L_base does not depend on lambda
-  const sama_batch ptb{pt->ids, nullptr, nullptr, pt->n_seq};
+  const sama_batch ptb{pt->ids, nullptr, nullptr, pt->n_seq, pt->seq_len};
   const PassWeights w[2] = {pass_weights(c, 1.f), pass_weights(c, -1.f)};
   c->model->forward_pair(st, w[0], w[1], ptb, c->logits);
   const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, 0, pt->n_seq * S};

@@ -37,26 +37,27 @@ def make_aux_pair(wl, theta0, lambda0, max_aux_batch, max_aux_masked, **over):
     from oracle.auxtask import AuxTaskOracle
     kw = dict(base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
               adam_eps=wl.adam_eps)
-    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps")})
+    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps", "weight_decay")})
     orc = AuxTaskOracle(models.make_model(wl.kind, wl.dims, mlm=True), theta0, lambda0, **kw)
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch, aux_mlm=1,
                               max_aux_batch=max_aux_batch, max_aux_masked=max_aux_masked, **kw)
     return orc, pkg.Sama(cfg, theta0, lambda0)
 
 
-def dev_aux_batch(gpu, ids, seq, pos, tgt):
+def dev_aux_batch(gpu, ids, seq, pos, tgt, lens=None):
     import torch
     S = ids.shape[1]
     t = lambda a: torch.as_tensor(np.ascontiguousarray(a).astype(np.int32), device=gpu.dev)
-    return gpu.aux_batch(t(ids), t(seq.astype(np.int64) * S + pos), t(tgt))
+    return gpu.aux_batch(t(ids), t(seq.astype(np.int64) * S + pos), t(tgt), None if lens is None else t(lens))
 
 
-def dev_batch(gpu, x, y, mask=None):
+def dev_batch(gpu, x, y, mask=None, lens=None):
     import torch
     xt = torch.as_tensor(np.ascontiguousarray(x), device=gpu.dev)
     yt = torch.as_tensor(np.ascontiguousarray(y).astype(np.int32), device=gpu.dev)
     mt = None if mask is None else torch.as_tensor(np.ascontiguousarray(mask).astype(np.uint8), device=gpu.dev)
-    return gpu.batch(xt, yt, mt)
+    lt = None if lens is None else torch.as_tensor(np.ascontiguousarray(lens).astype(np.int32), device=gpu.dev)
+    return gpu.batch(xt, yt, mt, lt)
 
 
 def push_state(orc, gpu):

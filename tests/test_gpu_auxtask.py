@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 from datagen import make_workload, make_aux_batch, make_aux_workload, AUX_TASK, init_theta, init_lambda, round_to_bf16
 from harness import rel_l2, make_aux_pair, dev_batch, dev_aux_batch, push_state, pull
+from oracle.models import with_lengths
 
 pytestmark = pytest.mark.gpu
 KTOL, TOL = 1e-2, 2e-2
@@ -102,6 +103,50 @@ def test_aux_meta_step_parity():
         assert e["h"] < TOL, e
         assert e["theta"] < TOL and e["lam"] < TOL
         assert int(pull(gpu, "COUNTERS")[2]) == 0 and int(pull(gpu, "COUNTERS")[1]) == orc.meta_t
+    gpu.close()
+
+
+def test_aux_padded_batches():
+    """Sequence lengths on the finetuning, the auxiliary and the meta batch (key-padding mask): one base step and one
+    meta step against the oracle; each auxiliary sequence is as long as its last masked position at least."""
+    wl, orc, gpu = _setup()
+    S = wl.dims[4]
+    for s in range(3):
+        ft, _ = _ft(wl, s)
+        orc.base_step(ft, make_aux_batch(wl, s, 4))
+    ft, meta = _ft(wl, 3)
+    ids_pt, seq, pos, tgt = make_aux_batch(wl, 3, 4)
+    last = np.array([pos[seq == i].max() for i in range(4)])
+    l_pt = np.minimum(last + np.array([1, 9, 40, S]), S).astype(np.int32)
+    l_ft = np.array([S, 1, 30, 77, 5], dtype=np.int32); l_m = np.array([12, S, 3], dtype=np.int32)
+    ftl, ptl, metal = (with_lengths(ft[0], l_ft), ft[1]), (with_lengths(ids_pt, l_pt), seq, pos, tgt), (with_lengths(meta[0], l_m), meta[1])
+    _snap(orc)
+    push_state(orc, gpu)
+    ref_l = orc.model.mlm_losses(orc.theta, ids_pt, seq, pos, tgt)
+    assert np.max(np.abs(ref_l - orc.model.mlm_losses(orc.theta, ptl[0], seq, pos, tgt))) > 1e-3      # the mask matters
+    lo = orc.base_step(ftl, ptl)
+    ftb, ptb = dev_batch(gpu, ft[0], ft[1], lens=l_ft), dev_aux_batch(gpu, ids_pt, seq, pos, tgt, lens=l_pt)
+    gpu.aux_base_step(ftb, ptb)
+    g = pull(gpu, "G")
+    errs = _group_errors(orc, g, orc.g)
+    print(f"padded aux base step: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
+    assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
+    assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 1e-2 * abs(lo)
+    _snap(orc)
+    push_state(orc, gpu)
+    r = orc.meta_step(ptl, metal)
+    gpu.aux_meta_step(ptb, dev_batch(gpu, meta[0], meta[1], lens=l_m))
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), theta=rel_l2(pull(gpu, "THETA"), orc.theta))
+    print("padded aux meta step: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+    assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["h"] < TOL and e["theta"] < TOL
+    # lengths on one half only: the other half counts as full
+    push_state(orc, gpu)
+    gpu.aux_base_step(dev_batch(gpu, ft[0], ft[1]), dev_aux_batch(gpu, ids_pt, seq, pos, tgt, lens=np.full(4, S, dtype=np.int32)))
+    g_half = pull(gpu, "G").copy()
+    push_state(orc, gpu)
+    gpu.aux_base_step(dev_batch(gpu, ft[0], ft[1]), dev_aux_batch(gpu, ids_pt, seq, pos, tgt))
+    assert np.array_equal(g_half, pull(gpu, "G"))
     gpu.close()
 
 

@@ -3,7 +3,8 @@ seeded inputs, teacher-forced from the oracle's state.  Bar: relative L2 <= 2e-2
 updated theta / lambda (bf16 GEMM operands, fp32 accumulation and state)."""
 import numpy as np
 import pytest
-from datagen import make_workload, init_theta, init_lambda, round_to_bf16
+from datagen import make_workload, init_theta, init_lambda, round_to_bf16, seq_lengths
+from oracle.models import with_lengths
 from harness import rel_l2, make_pair, dev_batch, push_state, pull
 
 pytestmark = pytest.mark.gpu
@@ -279,4 +280,69 @@ def test_small_encoder_sgd_and_no_adaptation(variant):
              theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
     print(f"{variant}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
     assert e["gmeta"] < KTOL and e["v"] < KTOL and e["eps"] < KTOL and e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL
+    gpu.close()
+
+
+def test_padded_batches_small_encoder():
+    """Sequence lengths (key-padding mask): base step and meta step against the oracle on a length mix that includes a
+    one-token and a full sequence; then the invariants of padding on the GPU alone: full lengths give the bits of no
+    lengths, and other tokens in the padded positions change no bit of the gradient."""
+    import torch
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    S, V = wl.dims[4], wl.dims[5]
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    lens_all = seq_lengths(wl.seed + 1, 64, S)
+    for s in range(3):
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(with_lengths(x, lens_all[5 * s:5 * s + 5]), y)
+    for s in range(3, 5):
+        (x, y), (xm, ym) = _batches(wl, s)
+        lt = lens_all[5 * s:5 * s + 5].copy(); lm = lens_all[40 + 3 * s:43 + 3 * s].copy()
+        lt[0], lt[1], lm[0] = 1, S, 2
+        _snap(orc)
+        push_state(orc, gpu)
+        tb, mb = dev_batch(gpu, x, y, lens=lt), dev_batch(gpu, xm, ym, lens=lm)
+        # the mask matters on these batches
+        assert np.max(np.abs(orc.model.losses(orc.theta, x, y) - orc.model.losses(orc.theta, with_lengths(x, lt), y))) > 1e-3
+        lo = orc.base_step(with_lengths(x, lt), y)
+        gpu.base_step(tb)
+        g = pull(gpu, "G")
+        errs = _group_errors(orc, g, orc.g)
+        print(f"padded base step {s}: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
+        assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
+        assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 2e-2 * abs(lo)
+        _snap(orc)
+        push_state(orc, gpu)
+        r = orc.meta_step(with_lengths(x, lt), y, with_lengths(xm, lm), ym)
+        gpu.meta_step(tb, mb)
+        e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+                 glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), theta=rel_l2(pull(gpu, "THETA"), orc.theta))
+        print(f"padded meta step {s}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+        assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["h"] < TOL and e["theta"] < TOL
+    # ---- invariants, GPU against itself
+    (x, y), _ = _batches(wl, 5)
+    lens = np.array([S, 7, 64, 1, 100], dtype=np.int32)
+
+    def grad_of(xx, ll):
+        push_state(orc, gpu)
+        gpu.base_step(dev_batch(gpu, xx, y, lens=ll))
+        return pull(gpu, "G").copy(), pull(gpu, "LOSSES")[:5].copy()
+    g_none, l_none = grad_of(x, None)
+    g_full, l_full = grad_of(x, np.full(5, S, dtype=np.int32))
+    assert np.array_equal(g_none, g_full) and np.array_equal(l_none, l_full)
+    g_a, l_a = grad_of(x, lens)
+    x2 = x.copy()
+    for b in range(5):
+        x2[b, lens[b]:] = V - 1 - b
+    g_b, l_b = grad_of(x2, lens)
+    tok = orc.model.slices["tok_emb"][0]
+    keep = np.ones(g_a.size, dtype=bool); keep[tok:tok + V * wl.dims[1]] = False
+    assert np.array_equal(l_a, l_b) and np.array_equal(g_a[keep], g_b[keep])
+    tg_a, tg_b = g_a[tok:tok + V * wl.dims[1]].reshape(V, -1), g_b[tok:tok + V * wl.dims[1]].reshape(V, -1)
+    real = np.unique(np.concatenate([x[b, :lens[b]] for b in range(5)]))
+    assert np.array_equal(tg_a[real], tg_b[real])
+    assert np.all(tg_b[[V - 1 - b for b in range(1, 5) if (V - 1 - b) not in real]] == 0.0)      # pad-only tokens: no gradient
+    # out-of-range lengths are clamped, not an error
+    g_c, _ = grad_of(x, np.array([S + 50, 7, 64, 0, 100], dtype=np.int32))
+    assert np.array_equal(g_c, g_a)
     gpu.close()
