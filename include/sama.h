@@ -34,7 +34,8 @@
  *         (two dims = multinomial logistic regression; hidden layers use ReLU)
  *    ENCODER dims = {L, d, heads, ffn, S, V, C}  (post-LN, learned positions, erf-GELU, LN eps 1e-5,
  *         softmax(q k^T / sqrt(d/heads)) over the real tokens of a sequence (sama_batch.seq_len), classifier on the
- *         position-0 hidden state):
+ *         position-0 hidden state; supported shapes: S = 64, 128 or 256, d / heads = 64, d <= 1024, ffn % 64 = 0,
+ *         at most 8192 token rows per batch):
  *         per layer l: Wqkv[3d x d] (rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V; head h owns rows h*d/heads..),
  *                      Wo[d x d], W1[ffn x d], W2[d x ffn];
  *         then per layer l: bqkv[3d], bo[d], ln1_g[d], ln1_b[d], b1[ffn], b2[d], ln2_g[d], ln2_b[d];
@@ -103,7 +104,7 @@ typedef struct {
                              (Wmlm [V x d] after the layers' matrices, bmlm [V] before Wc); V must be a multiple of 64;
                              cannot be combined with corr_hidden > 0.  The sama_aux_* entry points need it. */
   int32_t max_aux_batch;  /* aux_mlm: largest number of auxiliary sequences per batch; (max_batch + max_aux_batch) * S
-                             and max_meta_batch * S must stay within the encoder's 4096-token limit */
+                             and max_meta_batch * S must stay within the encoder's 8192-token limit */
   int32_t max_aux_masked; /* aux_mlm: largest number of masked positions per auxiliary batch, 1..max_aux_batch * S */
 } sama_config;
 

@@ -108,7 +108,7 @@ class EncoderModel : public Model {
       GemmBf16Args g{};
       g.C16 = qkv_[s];
       fwd_linear(st, w, nw, xin, d_, o.Wqkv, 3 * d_, o.bqkv, M, g);
-      launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, nw * B, heads_, d_, b.seq_len, B);
+      launch_attention_fwd(st, qkv_[s], ao_[s], keep ? lse_[s] : nullptr, nw * B, S_, heads_, d_, b.seq_len, B);
       g = GemmBf16Args{};
       g.res32 = res_[0]; g.C32 = pre1_[s];          // the residual stream stays fp32
       fwd_linear(st, w, nw, ao_[s], d_, o.Wo, d_, o.bo, M, g);
@@ -256,7 +256,7 @@ class EncoderModel : public Model {
       g = dgrad(w, ds1, d_, o.Wo, d_, M);
       g.C16 = do_;
       launch_gemm_bf16(st, g);
-      launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv, B, heads_, d_, b.seq_len, B);
+      launch_attention_bwd(st, qkv_[l], ao_[l], do_, lse_[l], dqkv, B, S_, heads_, d_, b.seq_len, B);
       wg[3] = wgrad(dqkv, 3 * d_, X_[l], d_, M, grad + o.Wqkv);
       g = dgrad(w, dqkv, 3 * d_, o.Wqkv, d_, M);
       g.res32 = ds32_; g.C32 = dx;                            // gradient w.r.t. the layer input
@@ -341,13 +341,13 @@ class EncoderModel : public Model {
 
 Model* make_encoder(const sama_config& c, const std::vector<TensorInfo>& layout, std::string& err) {
   const int d = c.dims[1], heads = c.dims[2], ffn = c.dims[3], S = c.dims[4];
-  if (S != 128) { err = "the attention kernels are built for S = 128"; return nullptr; }
+  if (!attention_supports(S)) { err = "the encoder kernels are built for S = 64, 128 or 256"; return nullptr; }
   if (d / heads != 64 || d % heads != 0) { err = "the attention kernels are built for head width d/heads = 64"; return nullptr; }
   if (d > LN_MAX_D) { err = "d must be <= 1024"; return nullptr; }
   if (ffn % 64 != 0) { err = "ffn must be a multiple of 64"; return nullptr; }
   const int tb = c.max_batch + (c.aux_mlm ? c.max_aux_batch : 0);
   const int mb = tb > c.max_meta_batch ? tb : c.max_meta_batch;
-  if ((int64_t)mb * S > 4096) { err = "max batch (+ max auxiliary batch) * S must be <= 4096 tokens"; return nullptr; }
+  if ((int64_t)mb * S > MAX_TOKENS) { err = "max batch (+ max auxiliary batch) * S must be <= 8192 tokens"; return nullptr; }
   if (c.aux_mlm && c.dims[5] % 64 != 0) { err = "the masked-token head needs a vocabulary size that is a multiple of 64"; return nullptr; }
   return new EncoderModel(c, layout);
 }

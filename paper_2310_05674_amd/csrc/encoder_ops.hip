@@ -229,7 +229,8 @@ __global__ __launch_bounds__(256) void k_colsum_partial_bf16(ColsumMulti m) {
 }
 
 // =========================================================================================== attention
-constexpr int AS = 128, AD = 64;  // sequence length, head width
+// Sequence length S = 32 NT (NT = 2, 4 or 8 tiles of 32 positions), head width 64.
+constexpr int AD = 64;  // head width
 
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ s16x4 ld_s16x4(const bf16_t* p) { return *reinterpret_cast<const s16x4*>(p); }
@@ -239,17 +240,18 @@ __device__ __forceinline__ s16x4 pack4(float a, float b, float c, float d) {
   return r;
 }
 
-// A [128 x 64] bf16 tile (row stride ld) staged in LDS as it lies in memory, S[row][e] with row stride SLD (192 bytes:
+// A [ROWS x 64] bf16 tile (row stride ld) staged in LDS as it lies in memory, S[row][e] with row stride SLD (192 bytes:
 // the four rows one transposing read touches fall into four different 64-byte bank windows), and its transposed MFMA
 // operand: for the 32x32x8 MFMA, lane l gets S[k0 + 4 (l / 32) + 0..3][e32 + l % 32] through ds_read_b64_tr_b16.
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 constexpr int SLD = AD + 32;
-template <int THREADS = 256>
+template <int THREADS, int ROWS>
 __device__ __forceinline__ void stage_rows(const bf16_t* __restrict__ src, int64_t ld, bf16_t* __restrict__ S) {
 #pragma unroll
-  for (int i = 0; i < 1024 / THREADS; ++i) {
-    const int c = threadIdx.x + THREADS * i, row = c >> 3, ec = c & 7;
-    *reinterpret_cast<uint4*>(S + row * SLD + ec * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)row * ld + ec * 8);
+  for (int c0 = 0; c0 < ROWS * 8; c0 += THREADS) {
+    const int c = c0 + threadIdx.x, row = c >> 3, ec = c & 7;
+    if (ROWS * 8 % THREADS == 0 || c < ROWS * 8)
+      *reinterpret_cast<uint4*>(S + row * SLD + ec * 8) = *reinterpret_cast<const uint4*>(src + (int64_t)row * ld + ec * 8);
   }
 }
 __device__ __forceinline__ s16x4 ld_transposed(const bf16_t* __restrict__ S, int e32, int k0, int lane) {
@@ -273,32 +275,24 @@ __device__ __forceinline__ f32x16 rows_dot_rows(const bf16_t* __restrict__ R, co
   return acc;
 }
 
-// Forward.  Wave w owns queries 32w..32w+31.  S^T[key][q] tiles leave each lane with one query column, so the
-// softmax over keys is an in-lane reduction plus one cross-half shuffle, and the probability tile is already in
-// the B-operand layout of the 32x32x8 MFMA for O^T[e][q] = sum_key V^T[e][key] P^T[key][q].
-// lens (or null): real tokens of sequence b % lens_period; keys at positions beyond get no weight.
-__device__ __forceinline__ int seq_len_of(const int32_t* __restrict__ lens, int lens_period, int b) {
-  if (lens == nullptr) return AS;
+// lens (or null): real tokens of sequence b % lens_period, clamped into [1, S]; keys at positions beyond get no weight.
+__device__ __forceinline__ int seq_len_of(const int32_t* __restrict__ lens, int lens_period, int b, int S) {
+  if (lens == nullptr) return S;
   const int n = lens[b % lens_period];
-  return n < 1 ? 1 : (n > AS ? AS : n);
+  return n < 1 ? 1 : (n > S ? S : n);
 }
 
-__global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out, float* __restrict__ lse,
-                                                  int heads, int d, const int32_t* __restrict__ lens, int lens_period) {
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[AS * SLD];
-  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t ld = 3 * (int64_t)d;
-  const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
-  const bf16_t* K = Q + d;
-  const bf16_t* V = Q + 2 * d;
-  const int len = seq_len_of(lens, lens_period, b);
-  stage_rows(V, ld, Vs);
-  f32x16 s[4];
+// Forward.  Four waves; wave w owns the query tiles w, w + 4, ... (32 queries each).  S^T[key][q] tiles leave each lane
+// with one query column, so the softmax over keys is an in-lane reduction plus one cross-half shuffle, and the
+// probability tile is already in the B-operand layout of the 32x32x8 MFMA for O^T[e][q] = sum_key V^T[e][key] P^T[key][q].
+template <int NT>
+__device__ __forceinline__ void attn_scores(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, int64_t ld, int qt, int len,
+                                            int lane, f32x16 (&s)[NT], float& inv, float* __restrict__ lse_row) {
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt) s[kt] = rows_dot_rows(K, Q, ld, 32 * kt, 32 * wave, lane);
+  for (int kt = 0; kt < NT; ++kt) s[kt] = rows_dot_rows(K, Q, ld, 32 * kt, 32 * qt, lane);
   float mx = -3.0e38f;
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
+  for (int kt = 0; kt < NT; ++kt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int key = 32 * kt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -308,178 +302,212 @@ __global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
   float sum = 0.f;
 #pragma unroll
-  for (int kt = 0; kt < 4; ++kt)
+  for (int kt = 0; kt < NT; ++kt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[kt][r] = __expf(s[kt][r] - mx); sum += s[kt][r]; }
   sum += __shfl_xor(sum, 32, 64);
-  const float inv = 1.f / sum;
-  if (lane < 32 && lse != nullptr) lse[((int64_t)b * heads + h) * AS + 32 * wave + lane] = mx + __logf(sum);
-  __syncthreads();
-  f32x16 o[2];
+  inv = 1.f / sum;
+  if (lane < 32 && lse_row != nullptr) lse_row[32 * qt + lane] = mx + __logf(sum);
+}
+
+template <int NT, bool PADDED>   // PADDED = false: no lengths given, the comparisons against len fold away
+__global__ __launch_bounds__(256) void k_attn_fwd(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out, float* __restrict__ lse,
+                                                  int heads, int d, const int32_t* __restrict__ lens, int lens_period) {
+  constexpr int S = 32 * NT;
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[S * SLD];
+  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t ld = 3 * (int64_t)d;
+  const bf16_t* Q = qkv + (int64_t)b * S * ld + h * AD;
+  const bf16_t* K = Q + d;
+  const bf16_t* V = Q + 2 * d;
+  const int len = PADDED ? seq_len_of(lens, lens_period, b, S) : S;
+  float* lse_row = lse != nullptr ? lse + ((int64_t)b * heads + h) * S : nullptr;
+  stage_rows<256, S>(V, ld, Vs);
+  f32x16 s[NT];
+  float inv = 0.f;
+  int qt = wave;
+  if (qt < NT) attn_scores<NT>(Q, K, ld, qt, len, lane, s, inv, lse_row);   // overlaps the staging of V
+  __syncthreads();                                                          // reached once by every wave
+  while (qt < NT) {
+    f32x16 o[2];
 #pragma unroll
-  for (int et = 0; et < 2; ++et) {
+    for (int et = 0; et < 2; ++et) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[et][r] = 0.f;
+      for (int r = 0; r < 16; ++r) o[et][r] = 0.f;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+      for (int kt = 0; kt < NT; ++kt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const s16x4 pb = pack4(s[kt][4 * c] * inv, s[kt][4 * c + 1] * inv, s[kt][4 * c + 2] * inv, s[kt][4 * c + 3] * inv);
+          const s16x4 va = ld_transposed(Vs, 32 * et, 32 * kt + 8 * c, lane);
+          o[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(va, pb, o[et], 0, 0, 0);
+        }
+    }
+    bf16_t* orow = out + ((int64_t)b * S + 32 * qt + (lane & 31)) * d + h * AD;
+#pragma unroll
+    for (int et = 0; et < 2; ++et)
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const s16x4 pb = pack4(s[kt][4 * c] * inv, s[kt][4 * c + 1] * inv, s[kt][4 * c + 2] * inv, s[kt][4 * c + 3] * inv);
-        const s16x4 va = ld_transposed(Vs, 32 * et, 32 * kt + 8 * c, lane);
-        o[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(va, pb, o[et], 0, 0, 0);
+        uint2 pk;
+        pk.x = pack_bf16x2(o[et][4 * c], o[et][4 * c + 1]);
+        pk.y = pack_bf16x2(o[et][4 * c + 2], o[et][4 * c + 3]);
+        *reinterpret_cast<uint2*>(orow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
       }
+    qt += 4;
+    if (qt < NT) attn_scores<NT>(Q, K, ld, qt, len, lane, s, inv, lse_row);
   }
-  bf16_t* orow = out + ((int64_t)b * AS + 32 * wave + (lane & 31)) * d + h * AD;
-#pragma unroll
-  for (int et = 0; et < 2; ++et)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      uint2 pk;
-      pk.x = pack_bf16x2(o[et][4 * c], o[et][4 * c + 1]);
-      pk.y = pack_bf16x2(o[et][4 * c + 2], o[et][4 * c + 3]);
-      *reinterpret_cast<uint2*>(orow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
-    }
 }
 
 // Backward.  Probabilities are recomputed from q, k and the saved log-sum-exp.
-// Phase A (wave owns 32 queries): dS^T[key][q] -> dQ^T[e][q] = sum_key K^T[e][key] dS^T[key][q].
-// Phase B (wave owns 32 keys):    P[q][key], dS[q][key] -> dV^T[e][key] = sum_q dO^T[e][q] P[q][key],
-//                                                          dK^T[e][key] = sum_q Q^T[e][q] dS[q][key].
+// Phase A (a wave owns 32 queries at a time): dS^T[key][q] -> dQ^T[e][q] = sum_key K^T[e][key] dS^T[key][q].
+// Phase B (a wave owns 32 keys at a time):    P[q][key], dS[q][key] -> dV^T[e][key] = sum_q dO^T[e][q] P[q][key],
+//                                                                      dK^T[e][key] = sum_q Q^T[e][q] dS[q][key].
 // dS = P (dP - D) / 8 with D[q] = sum_e dO[q][e] O[q][e].
-// The two phases only read what is staged and are independent: waves 0-3 run phase A while waves 4-7 run phase B.
+// The two phases only read what is staged and are independent: waves 0-3 run phase A while waves 4-7 run phase B, each
+// over the tiles w, w + 4, ... of its phase.
+template <int NT, bool PADDED>
 __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ out,
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ lse,
                                                   bf16_t* __restrict__ dqkv, int heads, int d, const int32_t* __restrict__ lens,
                                                   int lens_period) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[AS * SLD];
-  __shared__ __attribute__((aligned(16))) bf16_t Qs[AS * SLD];
-  __shared__ __attribute__((aligned(16))) bf16_t dOs[AS * SLD];
-  __shared__ float s_D[AS], s_lse[AS];
+  constexpr int S = 32 * NT;
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[S * SLD];
+  __shared__ __attribute__((aligned(16))) bf16_t Qs[S * SLD];
+  __shared__ __attribute__((aligned(16))) bf16_t dOs[S * SLD];
+  __shared__ float s_D[S], s_lse[S];
   const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3;
   const bool phase_a = threadIdx.x < 256;
-  const int len = seq_len_of(lens, lens_period, b);
+  const int len = PADDED ? seq_len_of(lens, lens_period, b, S) : S;
   const int64_t ld = 3 * (int64_t)d;
-  const bf16_t* Q = qkv + (int64_t)b * AS * ld + h * AD;
+  const bf16_t* Q = qkv + (int64_t)b * S * ld + h * AD;
   const bf16_t* K = Q + d;
   const bf16_t* V = Q + 2 * d;
-  const bf16_t* O = out + (int64_t)b * AS * d + h * AD;
-  const bf16_t* dO = dout + (int64_t)b * AS * d + h * AD;
-  stage_rows<512>(K, ld, Ks);
-  stage_rows<512>(Q, ld, Qs);
-  stage_rows<512>(dO, d, dOs);
+  const bf16_t* O = out + (int64_t)b * S * d + h * AD;
+  const bf16_t* dO = dout + (int64_t)b * S * d + h * AD;
+  stage_rows<512, S>(K, ld, Ks);
+  stage_rows<512, S>(Q, ld, Qs);
+  stage_rows<512, S>(dO, d, dOs);
   if (phase_a) {
-    const int q = threadIdx.x >> 1, half = threadIdx.x & 1;
-    float acc = 0.f;
+    // two threads per query; 2 S and 256 are multiples of the wave size, so a wave is in or out of a trip as a whole
+    for (int t = threadIdx.x; t < 2 * S; t += 256) {
+      const int q = t >> 1, half = t & 1;
+      float acc = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint4 o4 = *reinterpret_cast<const uint4*>(O + (int64_t)q * d + half * 32 + 8 * i);
-      const uint4 d4 = *reinterpret_cast<const uint4*>(dO + (int64_t)q * d + half * 32 + 8 * i);
-      const uint32_t ow[4] = {o4.x, o4.y, o4.z, o4.w}, dw[4] = {d4.x, d4.y, d4.z, d4.w};
+      for (int i = 0; i < 4; ++i) {
+        const uint4 o4 = *reinterpret_cast<const uint4*>(O + (int64_t)q * d + half * 32 + 8 * i);
+        const uint4 d4 = *reinterpret_cast<const uint4*>(dO + (int64_t)q * d + half * 32 + 8 * i);
+        const uint32_t ow[4] = {o4.x, o4.y, o4.z, o4.w}, dw[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        acc = fmaf(bf16_to_f32((bf16_t)(ow[e >> 1] >> ((e & 1) * 16))), bf16_to_f32((bf16_t)(dw[e >> 1] >> ((e & 1) * 16))), acc);
+        for (int e = 0; e < 8; ++e)
+          acc = fmaf(bf16_to_f32((bf16_t)(ow[e >> 1] >> ((e & 1) * 16))), bf16_to_f32((bf16_t)(dw[e >> 1] >> ((e & 1) * 16))), acc);
+      }
+      acc += __shfl_xor(acc, 1, 64);
+      if (half == 0) { s_D[q] = acc; s_lse[q] = lse[((int64_t)b * heads + h) * S + q]; }
     }
-    acc += __shfl_xor(acc, 1, 64);
-    if (half == 0) { s_D[q] = acc; s_lse[q] = lse[((int64_t)b * heads + h) * AS + q]; }
   }
   __syncthreads();
 
   // ---- phase A: dQ
   if (phase_a) {
-    const int q = 32 * wave + (lane & 31);
-    const float lq = s_lse[q], Dq = s_D[q];
-    f32x16 dq[2];
+    for (int qt = wave; qt < NT; qt += 4) {
+      const int q = 32 * qt + (lane & 31);
+      const float lq = s_lse[q], Dq = s_D[q];
+      f32x16 dq[2];
 #pragma unroll
-    for (int et = 0; et < 2; ++et)
+      for (int et = 0; et < 2; ++et)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dq[et][r] = 0.f;
+        for (int r = 0; r < 16; ++r) dq[et][r] = 0.f;
+#pragma unroll(NT <= 4 ? NT : 1)   // the long sequences keep one tile's operands in flight: unrolled they spill
+      for (int kt = 0; kt < NT; ++kt) {
+        f32x16 st = rows_dot_rows(K, Q, ld, 32 * kt, 32 * qt, lane);     // S^T[key][q]
+        const bf16_t* vp = V + (int64_t)(32 * kt + (lane & 31)) * ld + 8 * (lane >> 5);
+        const bf16_t* dop = dO + (int64_t)(32 * qt + (lane & 31)) * d + 8 * (lane >> 5);
+        f32x16 dp;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-      f32x16 st = rows_dot_rows(K, Q, ld, 32 * kt, 32 * wave, lane);     // S^T[key][q]
-      const bf16_t* vp = V + (int64_t)(32 * kt + (lane & 31)) * ld + 8 * (lane >> 5);
-      const bf16_t* dop = dO + (int64_t)(32 * wave + (lane & 31)) * d + 8 * (lane >> 5);
-      f32x16 dp;
+        for (int r = 0; r < 16; ++r) dp[r] = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+        for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(vp + 16 * ks), ld_bf16x8(dop + 16 * ks), dp, 0, 0, 0);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(vp + 16 * ks), ld_bf16x8(dop + 16 * ks), dp, 0, 0, 0);
+        for (int r = 0; r < 16; ++r) {
+          const int key = 32 * kt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          st[r] = key < len ? __expf(st[r] * 0.125f - lq) * (dp[r] - Dq) * 0.125f : 0.f;   // dS^T; a padded key has P = 0
+        }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = 32 * kt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        st[r] = key < len ? __expf(st[r] * 0.125f - lq) * (dp[r] - Dq) * 0.125f : 0.f;   // dS^T; a padded key has P = 0
-      }
+        for (int c = 0; c < 4; ++c) {
+          const s16x4 dsb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const s16x4 dsb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
-#pragma unroll
-        for (int et = 0; et < 2; ++et) {
-          const s16x4 ka = ld_transposed(Ks, 32 * et, 32 * kt + 8 * c, lane);
-          dq[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ka, dsb, dq[et], 0, 0, 0);
+          for (int et = 0; et < 2; ++et) {
+            const s16x4 ka = ld_transposed(Ks, 32 * et, 32 * kt + 8 * c, lane);
+            dq[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ka, dsb, dq[et], 0, 0, 0);
+          }
         }
       }
+      bf16_t* dqrow = dqkv + ((int64_t)b * S + q) * ld + h * AD;
+#pragma unroll
+      for (int et = 0; et < 2; ++et)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          uint2 pk;
+          pk.x = pack_bf16x2(dq[et][4 * c], dq[et][4 * c + 1]);
+          pk.y = pack_bf16x2(dq[et][4 * c + 2], dq[et][4 * c + 3]);
+          *reinterpret_cast<uint2*>(dqrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+        }
     }
-    bf16_t* dqrow = dqkv + ((int64_t)b * AS + q) * ld + h * AD;
-#pragma unroll
-    for (int et = 0; et < 2; ++et)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        uint2 pk;
-        pk.x = pack_bf16x2(dq[et][4 * c], dq[et][4 * c + 1]);
-        pk.y = pack_bf16x2(dq[et][4 * c + 2], dq[et][4 * c + 3]);
-        *reinterpret_cast<uint2*>(dqrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
-      }
   }
 
   // ---- phase B: dK, dV
   if (!phase_a) {
-    f32x16 dk[2], dv[2];
+    for (int kt = wave; kt < NT; kt += 4) {
+      const bool real_key = (32 * kt + (lane & 31)) < len;              // this lane's key
+      f32x16 dk[2], dv[2];
 #pragma unroll
-    for (int et = 0; et < 2; ++et)
+      for (int et = 0; et < 2; ++et)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { dk[et][r] = 0.f; dv[et][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) { dk[et][r] = 0.f; dv[et][r] = 0.f; }
+#pragma unroll(NT <= 4 ? NT : 1)
+      for (int qt = 0; qt < NT; ++qt) {
+        f32x16 st = rows_dot_rows(Q, K, ld, 32 * qt, 32 * kt, lane);     // S[q][key]
+        const bf16_t* dop = dO + (int64_t)(32 * qt + (lane & 31)) * d + 8 * (lane >> 5);
+        const bf16_t* vp = V + (int64_t)(32 * kt + (lane & 31)) * ld + 8 * (lane >> 5);
+        f32x16 dp;
 #pragma unroll
-    for (int qt = 0; qt < 4; ++qt) {
-      f32x16 st = rows_dot_rows(Q, K, ld, 32 * qt, 32 * wave, lane);     // S[q][key]
-      const bf16_t* dop = dO + (int64_t)(32 * qt + (lane & 31)) * d + 8 * (lane >> 5);
-      const bf16_t* vp = V + (int64_t)(32 * wave + (lane & 31)) * ld + 8 * (lane >> 5);
-      f32x16 dp;
+        for (int r = 0; r < 16; ++r) dp[r] = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+        for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(dop + 16 * ks), ld_bf16x8(vp + 16 * ks), dp, 0, 0, 0);
+        f32x16 ds;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ld_bf16x8(dop + 16 * ks), ld_bf16x8(vp + 16 * ks), dp, 0, 0, 0);
-      f32x16 ds;
+        for (int r = 0; r < 16; ++r) {
+          const int q = 32 * qt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const float p = real_key ? __expf(st[r] * 0.125f - s_lse[q]) : 0.f;
+          st[r] = p;
+          ds[r] = p * (dp[r] - s_D[q]) * 0.125f;
+        }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int q = 32 * qt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const float p = (32 * wave + (lane & 31)) < len ? __expf(st[r] * 0.125f - s_lse[q]) : 0.f;   // this lane's key
-        st[r] = p;
-        ds[r] = p * (dp[r] - s_D[q]) * 0.125f;
-      }
+        for (int c = 0; c < 4; ++c) {
+          const s16x4 pb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
+          const s16x4 dsb = pack4(ds[4 * c], ds[4 * c + 1], ds[4 * c + 2], ds[4 * c + 3]);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const s16x4 pb = pack4(st[4 * c], st[4 * c + 1], st[4 * c + 2], st[4 * c + 3]);
-        const s16x4 dsb = pack4(ds[4 * c], ds[4 * c + 1], ds[4 * c + 2], ds[4 * c + 3]);
-#pragma unroll
-        for (int et = 0; et < 2; ++et) {
-          dv[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_transposed(dOs, 32 * et, 32 * qt + 8 * c, lane), pb, dv[et], 0, 0, 0);
-          dk[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_transposed(Qs, 32 * et, 32 * qt + 8 * c, lane), dsb, dk[et], 0, 0, 0);
+          for (int et = 0; et < 2; ++et) {
+            dv[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_transposed(dOs, 32 * et, 32 * qt + 8 * c, lane), pb, dv[et], 0, 0, 0);
+            dk[et] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ld_transposed(Qs, 32 * et, 32 * qt + 8 * c, lane), dsb, dk[et], 0, 0, 0);
+          }
         }
       }
+      bf16_t* krow = dqkv + ((int64_t)b * S + 32 * kt + (lane & 31)) * ld + d + h * AD;
+      bf16_t* vrow = krow + d;
+#pragma unroll
+      for (int et = 0; et < 2; ++et)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          uint2 pk;
+          pk.x = pack_bf16x2(dk[et][4 * c], dk[et][4 * c + 1]);
+          pk.y = pack_bf16x2(dk[et][4 * c + 2], dk[et][4 * c + 3]);
+          *reinterpret_cast<uint2*>(krow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+          pk.x = pack_bf16x2(dv[et][4 * c], dv[et][4 * c + 1]);
+          pk.y = pack_bf16x2(dv[et][4 * c + 2], dv[et][4 * c + 3]);
+          *reinterpret_cast<uint2*>(vrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
+        }
     }
-    bf16_t* krow = dqkv + ((int64_t)b * AS + 32 * wave + (lane & 31)) * ld + d + h * AD;
-    bf16_t* vrow = krow + d;
-#pragma unroll
-    for (int et = 0; et < 2; ++et)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        uint2 pk;
-        pk.x = pack_bf16x2(dk[et][4 * c], dk[et][4 * c + 1]);
-        pk.y = pack_bf16x2(dk[et][4 * c + 2], dk[et][4 * c + 3]);
-        *reinterpret_cast<uint2*>(krow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
-        pk.x = pack_bf16x2(dv[et][4 * c], dv[et][4 * c + 1]);
-        pk.y = pack_bf16x2(dv[et][4 * c + 2], dv[et][4 * c + 3]);
-        *reinterpret_cast<uint2*>(vrow + 32 * et + 8 * c + 4 * (lane >> 5)) = pk;
-      }
   }
 }
 
@@ -535,7 +563,7 @@ __global__ __launch_bounds__(256) void k_pos_grad(const float* __restrict__ demb
 // only the block of the first occurrence goes on, and writes the ordered sum of those rows.
 __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb, const int32_t* __restrict__ ids, int M, int d,
                                                   float* __restrict__ g_tok) {
-  __shared__ int s_list[MAX_BATCH > 4096 ? MAX_BATCH : 4096];
+  __shared__ int s_list[MAX_TOKENS];
   __shared__ int s_cnt, s_wave[4];
   const int m = blockIdx.x, id = ids[m], lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x == 0) s_cnt = 0;
@@ -550,14 +578,14 @@ __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb
     for (int w = 0; w < wave; ++w) off += s_wave[w];
     if (hit) {
       const int pos = off + __popcll(bal & ((1ull << lane) - 1ull));
-      if (pos < 4096) s_list[pos] = mm;
+      if (pos < MAX_TOKENS) s_list[pos] = mm;
     }
     __syncthreads();
     if (threadIdx.x == 0) s_cnt += s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
     __syncthreads();
     if (s_cnt > 0 && s_list[0] != m) return;   // an earlier position holds this id (the list is ascending)
   }
-  const int cnt = s_cnt < 4096 ? s_cnt : 4096;
+  const int cnt = s_cnt < MAX_TOKENS ? s_cnt : MAX_TOKENS;
   // a frequent id (position 0 of every sequence, the head of the Zipf law) has hundreds of rows: fetch them sixteen at
   // a time so that their latencies overlap, add them in list order
   for (int c = threadIdx.x; c < d; c += 256) {
@@ -626,15 +654,49 @@ void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* pa
   launch_colsum_partial_multi(st, &j, 1);
   launch_reduce_rows(st, partial, nrb, N, 0, N, out, nullptr, nullptr);
 }
-void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d,
+// (S = 32 would fit the kernels, but the weight-gradient GEMMs contract over batch * S token rows in slabs of 64)
+bool attention_supports(int S) { return S == 64 || S == 128 || S == 256; }
+void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float* lse, int B, int S, int heads, int d,
                           const int32_t* lens, int lens_period) {
-  ProfScope ps(st, F_ATTN_FWD, 4.0 * B * heads * 128.0 * 128.0 * 64.0);
-  k_attn_fwd<<<dim3(heads, B), 256, 0, st>>>(qkv, out, lse, heads, d, lens, lens_period > 0 ? lens_period : 1);
+  ProfScope ps(st, F_ATTN_FWD, 4.0 * B * heads * (double)S * S * 64.0);
+  const dim3 grid(heads, B);
+  const int lp = lens_period > 0 ? lens_period : 1;
+  switch (S) {
+    case 64:
+      if (lens) k_attn_fwd<2, true><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      else k_attn_fwd<2, false><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      break;
+    case 128:
+      if (lens) k_attn_fwd<4, true><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      else k_attn_fwd<4, false><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      break;
+    case 256:
+      if (lens) k_attn_fwd<8, true><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      else k_attn_fwd<8, false><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      break;
+    default: break;   // make_encoder admits no other length
+  }
 }
 void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
-                          bf16_t* dqkv, int B, int heads, int d, const int32_t* lens, int lens_period) {
-  ProfScope ps(st, F_ATTN_BWD, 10.0 * B * heads * 128.0 * 128.0 * 64.0);
-  k_attn_bwd<<<dim3(heads, B), 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lens_period > 0 ? lens_period : 1);
+                          bf16_t* dqkv, int B, int S, int heads, int d, const int32_t* lens, int lens_period) {
+  ProfScope ps(st, F_ATTN_BWD, 10.0 * B * heads * (double)S * S * 64.0);
+  const dim3 grid(heads, B);
+  const int lp = lens_period > 0 ? lens_period : 1;
+  switch (S) {
+    case 64:
+      if (lens) k_attn_bwd<2, true><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      else k_attn_bwd<2, false><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      break;
+    case 128:
+      if (lens) k_attn_bwd<4, true><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      else k_attn_bwd<4, false><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      break;
+    case 256:
+      if (lens) k_attn_bwd<8, true><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      else k_attn_bwd<8, false><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      break;
+    default: break;
+  }
 }
 void launch_head_fwd(hipStream_t st, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits) {

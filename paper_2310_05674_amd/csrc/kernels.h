@@ -24,6 +24,7 @@ bool prof_read(int family, const char** name, int64_t* launches, double* total_m
 
 constexpr int EW_MAX_BLOCKS = 65536;  // grid cap of the elementwise kernels (also the size of the norm partials)
 constexpr int MAX_BATCH = 2048;
+constexpr int MAX_TOKENS = 8192;   // encoder: token rows of one batch (the token-gradient kernel lists them in LDS)
 constexpr int MAX_WNET_HIDDEN = 256;
 constexpr int MAX_CORR_HIDDEN = 128;   // label corrector: hidden width and number of classes it supports
 constexpr int MAX_CORR_CLASSES = 16;
@@ -191,13 +192,14 @@ struct ColsumJob { const bf16_t* X; int M, N; float* partial; };
 void launch_colsum_partial_multi(hipStream_t, const ColsumJob* jobs, int count);
 // column sums of a bf16 matrix [M x N] (ld = N) through partial [ceil(M / COLSUM_ROWS)][N]
 void launch_colsum_bf16(hipStream_t, const bf16_t* X, int M, int N, float* partial, float* out);
-// softmax(q k^T / 8) v for S = 128, head width 64; qkv [B*S x 3d] bf16; out [B*S x d] bf16; lse [B][heads][S].
-// lens (device, or null = all S): sequence b has lens[b % lens_period] real tokens (clamped into [1, S]); keys beyond get
-// no weight.
-void launch_attention_fwd(hipStream_t, const bf16_t* qkv, bf16_t* out, float* lse, int B, int heads, int d,
+// softmax(q k^T / 8) v for S in {64, 128, 256} (attention_supports), head width 64; qkv [B*S x 3d] bf16; out [B*S x d]
+// bf16; lse [B][heads][S].  lens (device, or null = all S): sequence b has lens[b % lens_period] real tokens (clamped into
+// [1, S]); keys beyond get no weight.
+bool attention_supports(int S);
+void launch_attention_fwd(hipStream_t, const bf16_t* qkv, bf16_t* out, float* lse, int B, int S, int heads, int d,
                           const int32_t* lens, int lens_period);
 void launch_attention_bwd(hipStream_t, const bf16_t* qkv, const bf16_t* out, const bf16_t* dout, const float* lse,
-                          bf16_t* dqkv, int B, int heads, int d, const int32_t* lens, int lens_period);
+                          bf16_t* dqkv, int B, int S, int heads, int d, const int32_t* lens, int lens_period);
 // classifier on the position-0 hidden state: logits[b][c] = x[b*S] . Wc[c] + bc[c]
 void launch_head_fwd(hipStream_t, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits);

@@ -65,7 +65,7 @@ def test_masked_token_head_layout_and_limits(lib):
                 pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=0, max_aux_masked=100, **good),
                 pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=0, **good),
                 pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=4 * 128 + 1, **good),
-                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=30, max_aux_masked=100, **good),   # 34 * 128 tokens
+                pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=61, max_aux_masked=100, **good),   # 65 * 128 tokens > 8192
                 pkg.SamaConfig.make("encoder", dims, aux_mlm=2, max_aux_batch=4, max_aux_masked=100, **good),
                 pkg.SamaConfig.make("encoder", dims, aux_mlm=1, max_aux_batch=4, max_aux_masked=100, corr_hidden=4, **good),
                 pkg.SamaConfig.make("mlp", (4, 3), aux_mlm=1, max_aux_batch=4, max_aux_masked=100, **good)):
@@ -83,9 +83,17 @@ def test_bad_configs_rejected(lib):
                 pkg.SamaConfig.make("mlp", (4, 3), H=16, max_batch=0, max_meta_batch=8),
                 pkg.SamaConfig.make("mlp", (4, 3), H=16, max_batch=8, max_meta_batch=8, alpha=0.0),
                 pkg.SamaConfig.make("mlp", (4, 3), H=16, max_batch=8, max_meta_batch=8, bf16=True),
-                pkg.SamaConfig.make("encoder", (2, 30, 4, 64, 128, 100, 3), **good)):
+                pkg.SamaConfig.make("encoder", (2, 30, 4, 64, 128, 100, 3), **good),
+                pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 96, 100, 3), **good),            # S not 64 / 128 / 256
+                pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 512, 100, 3), **good),
+                pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 32, 100, 3), **good),
+                pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 256, 100, 3), H=16, max_batch=33, max_meta_batch=8)):   # 8448 tokens
         assert lib.sama_workspace_bytes(C.byref(bad)) == 0
         assert lib.sama_last_error(None) != b""
+    for S in (64, 128, 256):
+        assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("encoder", (2, 128, 2, 256, S, 100, 3), **good))) > 0
+    assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 256, 100, 3), H=16, max_batch=32,
+                                                                max_meta_batch=8))) > 0
     # label correction: lambda grows by the corrector [Hc x 2C, Hc, C x Hc, C]; limits on Hc, C and kappa
     cc = pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=5, corr_kappa=2.0, **good)
     assert lib.sama_lambda_count(C.byref(cc)) == 3 * 16 + 1 + 5 * 6 + 5 + 3 * 5 + 3

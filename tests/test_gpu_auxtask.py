@@ -150,6 +150,38 @@ def test_aux_padded_batches():
     gpu.close()
 
 
+def test_aux_sequence_length_256():
+    """The auxiliary task at the sequence length of the paper's continued-pretraining runs (256): one base step and one
+    meta step against the oracle."""
+    wl = make_workload(3, n_train=40, n_meta=12, **dict(SMALL, dims=(2, 192, 3, 320, 256, 640, 3)))
+    n_pt = 3
+    orc, gpu = make_aux_pair(wl, init_theta(wl, 0.02), init_lambda(wl), max_aux_batch=n_pt, max_aux_masked=n_pt * 52, base_lr=1e-3)
+    for s in range(2):
+        ft, _ = _ft(wl, s)
+        orc.base_step(ft, make_aux_batch(wl, s, n_pt))
+    ft, meta = _ft(wl, 2)
+    pt = make_aux_batch(wl, 2, n_pt)
+    _snap(orc)
+    push_state(orc, gpu)
+    lo = orc.base_step(ft, pt)
+    ftb, ptb = dev_batch(gpu, ft[0], ft[1]), dev_aux_batch(gpu, *pt)
+    gpu.aux_base_step(ftb, ptb)
+    g = pull(gpu, "G")
+    errs = _group_errors(orc, g, orc.g)
+    print(f"S=256 aux base step: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
+    assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
+    assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 1e-2 * abs(lo)
+    _snap(orc)
+    push_state(orc, gpu)
+    r = orc.meta_step(pt, meta)
+    gpu.aux_meta_step(ptb, dev_batch(gpu, meta[0], meta[1]))
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), theta=rel_l2(pull(gpu, "THETA"), orc.theta))
+    print("S=256 aux meta step: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+    assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["h"] < TOL and e["theta"] < TOL
+    gpu.close()
+
+
 def test_aux_entry_points_reject_bad_batches():
     import torch
     import paper_2310_05674_amd as pkg

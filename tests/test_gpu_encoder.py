@@ -346,3 +346,41 @@ def test_padded_batches_small_encoder():
     g_c, _ = grad_of(x, np.array([S + 50, 7, 64, 0, 100], dtype=np.int32))
     assert np.array_equal(g_c, g_a)
     gpu.close()
+
+
+@pytest.mark.parametrize("S,padded,B", [(64, False, 3), (64, True, 5), (256, False, 3), (256, True, 3), (256, True, 32)])
+def test_other_sequence_lengths(S, padded, B):
+    """Sequence lengths 64 and 256 (the attention kernels are instantiated per length; 256 walks two tiles per wave):
+    one base step and one meta step against the oracle, with and without padding.  The last case fills the 8192-token
+    limit of a batch (32 sequences of 256)."""
+    Bm = max(2, B // 2)
+    wl = make_workload(3, n_train=8 * B, n_meta=8 * Bm, dims=(2, 128, 2, 256, S, 600, 3), batch=B, meta_batch=Bm)
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    lens = seq_lengths(wl.seed + S, 6 * B, S)
+    lens[0], lens[1] = 1, S
+    inp = (lambda x, l: with_lengths(x, l)) if padded else (lambda x, l: x)
+    for s in range(3):
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(inp(x, lens[B * (s + 1):B * (s + 2)]), y)
+    (x, y), (xm, ym) = _batches(wl, 3)
+    lt, lm = lens[:B], lens[5 * B:5 * B + Bm]
+    _snap(orc)
+    push_state(orc, gpu)
+    tb = dev_batch(gpu, x, y, lens=lt if padded else None)
+    mb = dev_batch(gpu, xm, ym, lens=lm if padded else None)
+    lo = orc.base_step(inp(x, lt), y)
+    gpu.base_step(tb)
+    g = pull(gpu, "G")
+    errs = _group_errors(orc, g, orc.g)
+    print(f"S={S} padded={padded} base: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
+    assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
+    assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 2e-2 * abs(lo)
+    _snap(orc)
+    push_state(orc, gpu)
+    r = orc.meta_step(inp(x, lt), y, inp(xm, lm), ym)
+    gpu.meta_step(tb, mb)
+    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+             glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), theta=rel_l2(pull(gpu, "THETA"), orc.theta))
+    print(f"S={S} padded={padded} meta: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
+    assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["h"] < TOL and e["theta"] < TOL
+    gpu.close()
