@@ -91,7 +91,7 @@ def main():
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch,
                               base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
                               adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass, corr_hidden=args.corr_hidden,
-                              **(dict(aux_mlm=1, max_aux_batch=AUX_TASK["n_pt"], max_aux_masked=AUX_TASK["n_pt"] * 26) if args.aux else {}))
+                              **(dict(aux_mlm=1, max_aux_batch=AUX_TASK["n_pt"], max_aux_masked=AUX_TASK["n_pt"] * (AUX_TASK["dims"][4] // 5 + 1)) if args.aux else {}))
     s = pkg.Sama(cfg, th0, lam0)
     n, n16 = s.n, s.lib.sama_gemm_param_count(__import__("ctypes").byref(cfg))
     batches = []

@@ -206,8 +206,9 @@ def _zipf_tokens(rng, stream, n_seq, S, V, a=1.1):
 
 # Auxiliary-task reweighting (Sec. 4.3 runs it on RoBERTa-base): the encoder of workload 4 with RoBERTa's vocabulary
 # (50265, rounded up to the next multiple of 64 as the masked-token head requires) and that workload's optimiser
-# settings; 16 finetuning + 16 auxiliary sequences per base step, 16 meta sequences.
-AUX_TASK = dict(base=4, dims=(12, 768, 12, 3072, 128, 50304, 6), batch=16, meta_batch=16, n_pt=16)
+# settings; 16 finetuning + 16 auxiliary sequences per base step, 16 meta sequences, 256 tokens each (the batch size and the
+# maximum sequence length App. B gives for those runs).
+AUX_TASK = dict(base=4, dims=(12, 768, 12, 3072, 256, 50304, 6), batch=16, meta_batch=16, n_pt=16)
 
 
 def make_aux_workload(n_train=None, n_meta=None, **override):

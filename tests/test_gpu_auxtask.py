@@ -209,14 +209,14 @@ def test_aux_entry_points_reject_bad_batches():
 
 
 def test_aux_full_size_parity():
-    """The configuration `bench.py --aux` times (12 layers, d = 768, 50304-token vocabulary, 16 + 16 sequences): base
+    """The configuration `bench.py --aux` times (12 layers, d = 768, 50304-token vocabulary, 16 + 16 sequences of 256 tokens): base
     step 0 from the bf16-representable initial theta at the kernel-arithmetic bar, then one meta step from the oracle's
     state at the end-to-end bar with nothing snapped."""
     import time
     t0 = time.time()
     n_pt = AUX_TASK["n_pt"]
     wl = make_aux_workload(n_train=32, n_meta=16)
-    orc, gpu = make_aux_pair(wl, init_theta(wl), init_lambda(wl), max_aux_batch=n_pt, max_aux_masked=n_pt * 26)
+    orc, gpu = make_aux_pair(wl, init_theta(wl), init_lambda(wl), max_aux_batch=n_pt, max_aux_masked=n_pt * (wl.dims[4] // 5 + 1))
     ft, _ = _ft(wl, 0)
     pt = make_aux_batch(wl, 0, n_pt)
     lo = orc.base_step(ft, pt)
