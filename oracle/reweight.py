@@ -66,6 +66,13 @@ class SamaOracle:
             self.theta = optim.sgd_update(self.theta, g, self.base_lr)
         return float(np.sum(coef * l))
 
+    def evaluate(self, x, y):
+        """What the base step sees of a batch, forward only: (logits, l, w) with l_i the per-sample loss (against the
+        corrected label when label correction is on) and w_i = w(l_i; lambda), the learned importance of sample i."""
+        target = self.targets(self.theta, x, y)
+        l = self.model.losses(self.theta, x, target)
+        return self.model.logits(self.theta, x), l, wnet.weights(l, self.lam[:self.nr])
+
     # ------------------------------------------------------------------ meta level
     def adaptation(self):
         """du/dg on the diagonal from the LAST base step's gradient and its post-update moments

@@ -249,3 +249,20 @@ def test_scheduled_rate_and_the_adaptation_use_the_rate_of_the_step():
         c0.base_step(x, y); c1.base_step(x, y)
     r0 = c0.meta_step(x, y, xm, ym); r1 = c1.meta_step(x, y, xm, ym)
     assert np.array_equal(r0["h"], r1["h"]) and np.array_equal(c0.theta, c1.theta)
+
+
+def test_evaluate_is_the_forward_half_of_the_base_step():
+    """evaluate() against the base step's own return value (L_base = sum_i mask_i w_i l_i / B_eff) and against the
+    model's plain cross-entropy; it changes nothing."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    o = SamaOracle(model, th, lam, base_lr=0.05)
+    o.base_step(x, y)
+    th1 = o.theta.copy()
+    z, l, w = o.evaluate(x, y)
+    assert np.array_equal(o.theta, th1) and o.t == 1
+    mask = np.ones(len(y)); mask[1] = 0
+    ref = SamaOracle(model, th1, lam, base_lr=0.05)
+    assert abs(ref.base_step(x, y, mask) - np.sum(mask * w * l) / mask.sum()) < 1e-14
+    assert np.allclose(l, model.losses(th1, x, y), rtol=0, atol=1e-15)
+    assert np.allclose(l, np.log(np.exp(z).sum(axis=1)) - z[np.arange(len(y)), y], rtol=1e-12)
+    assert np.all((w > 0) & (w < 1))
