@@ -201,6 +201,15 @@ sama_status sama_aux_meta_grad(sama_ctx* ctx, const sama_aux_batch* pt, const sa
                                float* hypergrad_out /*DEVICE*/, float* eps_out /*DEVICE*/);
 sama_status sama_aux_meta_step(sama_ctx* ctx, const sama_aux_batch* pt, const sama_batch* meta);
 
+/* A forward-only look at a batch through the current theta and lambda, as the base step of Sec. 4.1 sees it:
+ * logits_out [n x C] (row-major), losses_out [n] = l_i (against the corrected soft label when label correction is on),
+ * weights_out [n] = w(l_i; lambda) -- the per-sample importance the meta learner has learned (what the reweighting and
+ * pruning applications of Sec. 4 read off it).  DEVICE pointers, each may be NULL.  n up to max(max_batch,
+ * max_meta_batch); sample_mask is ignored, seq_len honoured.  bf16 models evaluate at the bf16 working copy, as the base
+ * step's forward does.  Changes no state (LOSSES and SCALARS keep what the last step left). */
+sama_status sama_eval(sama_ctx* ctx, const sama_batch* batch, float* logits_out /*DEVICE*/, float* losses_out /*DEVICE*/,
+                      float* weights_out /*DEVICE*/);
+
 /* Learning-rate schedule hook (the lr_scheduler column of the App. B tables: cosine, linear decay with warm-up, ...;
  * the schedule itself is the caller's).  base_lr applies from the next base step, meta_lr from the next meta update;
  * the adaptation of Eq. 4 keeps using the rate of the base step it differentiates, whenever this is called.  Host

@@ -80,7 +80,7 @@ void launch_to_bf16(hipStream_t, bf16_t* dst, const float* src, int64_t n);
 void launch_fill_i64x4(hipStream_t, int64_t* p, int64_t a, int64_t b, int64_t c, int64_t d, int mask);
 
 // ------------------------------------------------------------------ per-sample stage (sample_stage.hip)
-enum { STAGE_BASE = 0, STAGE_META = 1, STAGE_GLAM = 2 };
+enum { STAGE_BASE = 0, STAGE_META = 1, STAGE_GLAM = 2, STAGE_EVAL = 3 };   // EVAL: BASE's losses and weights only
 struct SampleStageArgs {
   const float* logits;  // [B x C], row stride ld
   int ld, C, B, H, mode;
@@ -89,7 +89,8 @@ struct SampleStageArgs {
   const float* lambda;  // [3H+1] weighting net, then the corrector [Hc*2C + Hc + C*Hc + C] when Hc > 0
   int Hc; float kappa;  // label corrector (BASE and GLAM): Hc = 0 turns it off
   double* corr_scratch; // [B x 2C] device scratch of the corrector's backward (GLAM with Hc > 0)
-  float* losses;        // [B] out
+  float* losses;        // [B] out (may be null in EVAL)
+  float* weights;       // [B] out, w(l_i; lambda), or null (not in sequence mode)
   float* dlogits;       // [B x C] out, row stride C (BASE, META)
   float* loss_scalar;   // out: sum_i coef_i l_i
   float* loss_user;     // optional second destination

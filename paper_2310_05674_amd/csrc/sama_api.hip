@@ -357,6 +357,26 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
   return check_hip(c, "sama_base_step");
 }
 
+sama_status sama_eval(sama_ctx* c, const sama_batch* batch, float* logits_out, float* losses_out, float* weights_out) {
+  if (!c) return SAMA_EINVAL;
+  const int maxb = c->cfg.max_batch > c->cfg.max_meta_batch ? c->cfg.max_batch : c->cfg.max_meta_batch;
+  sama_status s = check_batch(c, batch, maxb, "eval");
+  if (s != SAMA_OK) return s;
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  const PassWeights w = pass_weights(c, 0.f);
+  float* logits = logits_out != nullptr ? logits_out : c->logits;
+  c->model->forward(st, w, *batch, false, logits);
+  if (losses_out != nullptr || weights_out != nullptr) {
+    SampleStageArgs sa{};
+    sa.logits = logits; sa.ld = c->model->n_classes(); sa.C = sa.ld; sa.B = batch->n; sa.H = c->cfg.wnet_hidden;
+    sa.mode = STAGE_EVAL; sa.Hc = c->cfg.corr_hidden; sa.kappa = c->cfg.corr_kappa; sa.y = batch->y; sa.mask = nullptr;
+    sa.lambda = c->lambda; sa.losses = losses_out; sa.weights = weights_out;
+    launch_sample_stage(st, sa);
+  }
+  return check_hip(c, "sama_eval");
+}
+
 // First half of a meta gradient: g_meta = dL_meta/dtheta on the clean batch (Eq. 1), v = (du/dg) . g_meta,
 // eps = alpha / ||v|| (Eq. 4-5, App. C), and the low halves of theta +- eps v.  Returns whether the GEMM block of
 // theta was nudged already (sama_meta_step on bf16 models: one pass over theta and v instead of two).

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
     } else {
       l = lse - (double)z[yi];
     }
-    a.losses[i] = (float)l;
+    if (a.losses != nullptr) a.losses[i] = (float)l;
     s_l[i] = l;
     double w = 1.0;
     if (a.mode != STAGE_META) {
@@ -125,6 +125,8 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
       for (int h = 0; h < H; ++h) zz += (double)W2[h] * fmax((double)W1[h] * l + (double)b1[h], 0.0);
       w = 1.0 / (1.0 + exp(-zz));
     }
+    if (a.weights != nullptr) a.weights[i] = (float)w;
+    if (a.mode == STAGE_EVAL) continue;
     if (a.mode == STAGE_GLAM) {
       s_dz[i] = w * (1.0 - w) * l * mk * inv_beff;
       if (Hc > 0) {

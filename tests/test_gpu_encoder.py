@@ -384,3 +384,23 @@ def test_other_sequence_lengths(S, padded, B):
     print(f"S={S} padded={padded} meta: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
     assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["h"] < TOL and e["theta"] < TOL
     gpu.close()
+
+
+def test_eval_small_encoder_with_padding():
+    """sama_eval on the bf16 encoder, padded batch: logits, losses and weights against the oracle at the bf16 working
+    weights (what the base step's forward sees)."""
+    import torch
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    S = wl.dims[4]
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    (x, y), (xm, ym) = _batches(wl, 0)
+    _snap(orc)
+    push_state(orc, gpu)
+    orc.t = 1                                            # evaluate needs no history; keep the oracle's guard quiet
+    lens = np.array([S, 9, 1, 77, 40], dtype=np.int32)
+    zo = torch.zeros((5, wl.dims[-1]), device=gpu.dev); lo = torch.zeros(5, device=gpu.dev); wo = torch.zeros(5, device=gpu.dev)
+    gpu.eval(dev_batch(gpu, x, y, lens=lens), zo, lo, wo)
+    z, l, w = orc.evaluate(with_lengths(x, lens), y)
+    print(f"eval: logits {rel_l2(zo.cpu().numpy(), z):.2e} losses {rel_l2(lo.cpu().numpy(), l):.2e} weights {rel_l2(wo.cpu().numpy(), w):.2e}")
+    assert rel_l2(zo.cpu().numpy(), z) < KTOL and rel_l2(lo.cpu().numpy(), l) < KTOL and rel_l2(wo.cpu().numpy(), w) < KTOL
+    gpu.close()

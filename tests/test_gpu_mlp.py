@@ -198,6 +198,36 @@ def test_scheduled_rates(base_opt):
     gpu.close()
 
 
+@pytest.mark.parametrize("corr", [0, 6])
+def test_eval_returns_logits_losses_and_weights(corr):
+    """sama_eval against the oracle's forward half of the base step, with and without label correction; it leaves every
+    state vector alone, also the losses of the last step."""
+    import torch
+    from datagen import init_lambda_corr
+    wl = make_workload(2)
+    lam0 = np.concatenate([init_lambda(wl), init_lambda_corr(wl, corr)]) if corr else init_lambda(wl)
+    kw = dict(corr_hidden=corr, corr_kappa=1.5) if corr else {}
+    orc, gpu = make_pair(wl, init_theta(wl), lam0, **kw)
+    (x, y), (xm, ym) = _batches(wl, 0)
+    tb = dev_batch(gpu, x, y)
+    for _ in range(2):
+        orc.base_step(x, y); gpu.base_step(tb)
+    before = {k: pull(gpu, k).copy() for k in ("THETA", "LAMBDA", "M", "V", "G", "LOSSES", "SCALARS", "COUNTERS")}
+    n, C = len(ym), wl.dims[-1]
+    zo = torch.full((n, C), -7.0, device=gpu.dev); lo = torch.full((n,), -7.0, device=gpu.dev); wo = torch.full((n,), -7.0, device=gpu.dev)
+    gpu.eval(dev_batch(gpu, xm, ym), zo, lo, wo)
+    z, l, w = orc.evaluate(xm, ym)
+    assert rel_l2(zo.cpu().numpy(), z) < TOL and rel_l2(lo.cpu().numpy(), l) < TOL and rel_l2(wo.cpu().numpy(), w) < TOL
+    for k, v in before.items():
+        assert np.array_equal(pull(gpu, k), v), k
+    # any subset of the outputs
+    w2 = torch.zeros(n, device=gpu.dev)
+    gpu.eval(dev_batch(gpu, xm, ym), weights_out=w2)
+    assert torch.equal(w2, wo)
+    gpu.eval(dev_batch(gpu, xm, ym))
+    gpu.close()
+
+
 def test_ragged_shapes():
     """Widths and batch sizes that are not multiples of any tile (67-33-5, batches 37 / 19)."""
     from datagen.workloads import Workload
