@@ -266,3 +266,27 @@ def test_evaluate_is_the_forward_half_of_the_base_step():
     assert np.allclose(l, model.losses(th1, x, y), rtol=0, atol=1e-15)
     assert np.allclose(l, np.log(np.exp(z).sum(axis=1)) - z[np.arange(len(y)), y], rtol=1e-12)
     assert np.all((w > 0) & (w < 1))
+
+
+def test_frozen_trajectories():
+    """Short runs of every oracle variant against tests/golden/oracle_trajectories.json (written by
+    tests/golden/make_oracle_golden.py from oracle/ alone): a change to the oracle's arithmetic has to show up here.
+    Tolerances leave room for another BLAS summation order, amplified by the difference of Eq. 5, and nothing more."""
+    import importlib.util
+    import json
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_oracle_golden", os.path.join(here, "golden", "make_oracle_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = json.load(open(os.path.join(here, "golden", "oracle_trajectories.json")))
+    got = mod.build()
+    assert set(got) == set(want)
+    for name in want:
+        assert len(got[name]) == len(want[name])
+        for g, w in zip(got[name], want[name]):
+            for key in ("loss", "theta_norm", "lam_norm"):
+                assert abs(g[key] - w[key]) <= 1e-10 * abs(w[key]), (name, key)
+            for key in ("eps", "v_norm", "h_norm"):
+                assert abs(g[key] - w[key]) <= 1e-6 * abs(w[key]), (name, key, g[key], w[key])
+            assert np.allclose(g["h_head"], w["h_head"], rtol=0, atol=1e-6 * w["h_norm"]), name
