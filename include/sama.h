@@ -210,6 +210,11 @@ sama_status sama_aux_meta_step(sama_ctx* ctx, const sama_aux_batch* pt, const sa
 sama_status sama_eval(sama_ctx* ctx, const sama_batch* batch, float* logits_out /*DEVICE*/, float* losses_out /*DEVICE*/,
                       float* weights_out /*DEVICE*/);
 
+/* The same look at an auxiliary batch (Sec. 4.3): losses_out [n_seq] = L_pt(x), the mean masked-token loss of each
+ * sequence, and weights_out [n_seq] = w(L_pt(x); lambda), how much the meta learner lets each auxiliary sequence count.
+ * DEVICE pointers, each may be NULL; changes no state. */
+sama_status sama_aux_eval(sama_ctx* ctx, const sama_aux_batch* pt, float* losses_out /*DEVICE*/, float* weights_out /*DEVICE*/);
+
 /* Learning-rate schedule hook (the lr_scheduler column of the App. B tables: cosine, linear decay with warm-up, ...;
  * the schedule itself is the caller's).  base_lr applies from the next base step, meta_lr from the next meta update;
  * the adaptation of Eq. 4 keeps using the rate of the base step it differentiates, whenever this is called.  Host

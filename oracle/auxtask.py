@@ -62,6 +62,12 @@ class AuxTaskOracle(SamaOracle):
         l_seq, _ = seq_losses(self.model.mlm_losses(theta, ids_pt, seq, pos, tgt), seq, len(models.split_lengths(ids_pt)[0]))
         return float(np.mean(self.model.losses(theta, ids_ft, y_ft))) + wnet.base_loss(l_seq, lam)
 
+    def evaluate_aux(self, pt):
+        """(L_pt(x), w(L_pt(x); lambda)) of each auxiliary sequence at the current state, forward only."""
+        ids_pt, seq, pos, tgt = pt
+        l_seq, _ = seq_losses(self.model.mlm_losses(self.theta, ids_pt, seq, pos, tgt), seq, len(models.split_lengths(ids_pt)[0]))
+        return l_seq, wnet.weights(l_seq, self.lam)
+
     def glam(self, theta, pt):
         """dL_base/dlambda: only the weighted pretraining term depends on lambda."""
         ids_pt, seq, pos, tgt = pt

@@ -106,6 +106,7 @@ def load_library():
     L.sama_op_gemm_bf16_batch.argtypes = [i32, vp, vp, vp, vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), i32, i32, vp]
     L.sama_set_lr.restype = C.c_int; L.sama_set_lr.argtypes = [vp, f32, f32]
     L.sama_eval.restype = C.c_int; L.sama_eval.argtypes = [vp, vp, vp, vp, vp]
+    L.sama_aux_eval.restype = C.c_int; L.sama_aux_eval.argtypes = [vp, vp, vp, vp]
     L.sama_op_adam.restype = C.c_int
     L.sama_op_adam.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, f32, f32, f32, f32, vp]
     L.sama_op_adapt_norm.restype = C.c_int
@@ -203,6 +204,12 @@ class Sama:
         for t in (logits_out, losses_out, weights_out):
             assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == self.torch.float32)
         self._check(self.lib.sama_eval(self.h, C.byref(batch), p(logits_out), p(losses_out), p(weights_out)))
+
+    def aux_eval(self, pt, losses_out=None, weights_out=None):
+        p = lambda t: None if t is None else t.data_ptr()
+        for t in (losses_out, weights_out):
+            assert t is None or (t.is_cuda and t.is_contiguous() and t.dtype == self.torch.float32)
+        self._check(self.lib.sama_aux_eval(self.h, C.byref(pt), p(losses_out), p(weights_out)))
 
     def set_lr(self, base_lr, meta_lr):
         self._check(self.lib.sama_set_lr(self.h, base_lr, meta_lr))

@@ -90,7 +90,7 @@ struct SampleStageArgs {
   int Hc; float kappa;  // label corrector (BASE and GLAM): Hc = 0 turns it off
   double* corr_scratch; // [B x 2C] device scratch of the corrector's backward (GLAM with Hc > 0)
   float* losses;        // [B] out (may be null in EVAL)
-  float* weights;       // [B] out, w(l_i; lambda), or null (not in sequence mode)
+  float* weights;       // [B] out, w(l_i; lambda), or null
   float* dlogits;       // [B x C] out, row stride C (BASE, META)
   float* loss_scalar;   // out: sum_i coef_i l_i
   float* loss_user;     // optional second destination

@@ -529,6 +529,26 @@ sama_status sama_aux_base_step(sama_ctx* c, const sama_batch* ft, const sama_aux
   return check_hip(c, "sama_aux_base_step");
 }
 
+sama_status sama_aux_eval(sama_ctx* c, const sama_aux_batch* pt, float* losses_out, float* weights_out) {
+  if (!c) return SAMA_EINVAL;
+  sama_status s = check_aux(c, pt);
+  if (s != SAMA_OK) return s;
+  hipStream_t st = c->stream;
+  (void)hipGetLastError();
+  const int S = c->cfg.dims[4];
+  const sama_batch ptb{pt->ids, nullptr, nullptr, pt->n_seq, pt->seq_len};
+  const PassWeights w = pass_weights(c, 0.f);
+  c->model->forward(st, w, ptb, true, c->logits);        // the head reads the kept last hidden state
+  const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, 0, pt->n_seq * S};
+  c->model->mlm_forward(st, &w, 1, pt->n_seq * S, true, mb, c->loss_pos);
+  SampleStageArgs sa{};
+  sa.B = pt->n_seq; sa.H = c->cfg.wnet_hidden; sa.mode = STAGE_EVAL; sa.lambda = c->lambda;
+  sa.losses = losses_out; sa.weights = weights_out;
+  sa.pos_loss = c->loss_pos; sa.pos_row = pt->mask_row; sa.n_pos = pt->n_mask; sa.S = S;
+  launch_sample_stage(st, sa);
+  return check_hip(c, "sama_aux_eval");
+}
+
 static sama_status aux_meta_common(sama_ctx* c, const sama_aux_batch* pt, const sama_batch* meta, float* hyper_out,
                                    float* eps_out, bool update) {
   if (!c) return SAMA_EINVAL;

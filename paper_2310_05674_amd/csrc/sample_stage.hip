@@ -68,10 +68,12 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   for (int i = tid; seq_mode && i < B; i += 256) {
     const double l = s_l[i];
     const double mk = (a.mask == nullptr || a.mask[i] != 0) ? 1.0 : 0.0;
-    a.losses[i] = (float)l;
+    if (a.losses != nullptr) a.losses[i] = (float)l;
     double zz = b2;
     for (int h = 0; h < H; ++h) zz += (double)W2[h] * fmax((double)W1[h] * l + (double)b1[h], 0.0);
     const double w = 1.0 / (1.0 + exp(-zz));
+    if (a.weights != nullptr) a.weights[i] = (float)w;
+    if (a.mode == STAGE_EVAL) continue;
     if (a.mode == STAGE_GLAM) {
       s_dz[i] = w * (1.0 - w) * l * mk * inv_beff;
     } else {
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
       lsum += s_dz[i] * l;
     }
   }
-  if (seq_mode && a.mode != STAGE_GLAM) {
+  if (seq_mode && a.mode != STAGE_GLAM && a.mode != STAGE_EVAL) {   // uniform over the block
     __syncthreads();
     for (int j = tid; j < a.n_pos; j += 256) {
       int r = a.pos_row[j];

@@ -182,6 +182,28 @@ def test_aux_sequence_length_256():
     gpu.close()
 
 
+def test_aux_eval_returns_sequence_losses_and_weights():
+    import torch
+    wl, orc, gpu = _setup()
+    for s in range(2):
+        ft, _ = _ft(wl, s)
+        orc.base_step(ft, make_aux_batch(wl, s, 4))
+    _snap(orc)
+    push_state(orc, gpu)
+    ids_pt, seq, pos, tgt = make_aux_batch(wl, 2, 3)
+    lens = np.array([128, max(pos[seq == 1]) + 1, 128], dtype=np.int32)
+    before = {k: pull(gpu, k).copy() for k in ("THETA", "LAMBDA", "M", "V", "G", "SCALARS", "COUNTERS")}
+    lo = torch.full((3,), -1.0, device=gpu.dev); wo = torch.full((3,), -1.0, device=gpu.dev)
+    gpu.aux_eval(dev_aux_batch(gpu, ids_pt, seq, pos, tgt, lens=lens), lo, wo)
+    l, w = orc.evaluate_aux((with_lengths(ids_pt, lens), seq, pos, tgt))
+    print(f"aux eval: losses {rel_l2(lo.cpu().numpy(), l):.2e} weights {rel_l2(wo.cpu().numpy(), w):.2e}")
+    assert rel_l2(lo.cpu().numpy(), l) < KTOL and rel_l2(wo.cpu().numpy(), w) < KTOL
+    for k, v in before.items():
+        assert np.array_equal(pull(gpu, k), v), k
+    gpu.aux_eval(dev_aux_batch(gpu, ids_pt, seq, pos, tgt, lens=lens), weights_out=wo)
+    gpu.close()
+
+
 def test_aux_entry_points_reject_bad_batches():
     import torch
     import paper_2310_05674_amd as pkg

@@ -140,6 +140,17 @@ def test_padded_batches_in_the_assembled_base_step():
     assert np.linalg.norm(r1["h"] - r0["h"]) > 1e-3 * np.linalg.norm(r0["h"])
 
 
+def test_evaluate_aux_is_the_weighted_term_of_the_base_loss():
+    enc, th, ft, pt, lam = _setup()
+    orc = AuxTaskOracle(enc, th, lam, base_lr=1e-2)
+    l_seq, w = orc.evaluate_aux(pt)
+    assert abs(orc.base_loss(th, lam, ft, pt) - (np.mean(enc.losses(th, ft[0], ft[1])) + np.mean(w * l_seq))) < 1e-13
+    ids_pt, seq, pos, tgt = pt
+    l_pos = enc.mlm_losses(th, ids_pt, seq, pos, tgt)
+    assert np.allclose(l_seq, [l_pos[seq == i].mean() for i in range(len(ids_pt))], rtol=1e-13)
+    assert np.all((w > 0) & (w < 1))
+
+
 def test_constant_weights_give_plain_multitask_gradient_and_zero_hypergradient_rows():
     """W2 = 0: w = sigmoid(b2) for every sequence, so the base gradient is that of L_ft + sigmoid(b2) mean L_pt, and only
     the rows of dL_base/dlambda that do not vanish with W2 = 0 (W2 itself and b2) are non-zero."""
