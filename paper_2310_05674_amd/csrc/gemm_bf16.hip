@@ -530,7 +530,12 @@ const char* check_gemm_bf16_batch(const GemmBf16Args* p, int count) {
   return nullptr;
 }
 
+static const char* g_launch_error = nullptr;
+void note_launch_error(const char* what) { if (g_launch_error == nullptr) g_launch_error = what; }
+const char* take_launch_error() { const char* e = g_launch_error; g_launch_error = nullptr; return e; }
+
 void launch_gemm_bf16_batch(hipStream_t st, const GemmBf16Args* p, int count) {
+  if (const char* e = check_gemm_bf16_batch(p, count)) { note_launch_error(e); return; }   // never run a shape the tiles cannot cover
   double flops = 0.0;
   for (int k = 0; k < count; ++k) flops += 2.0 * p[k].M * p[k].N * p[k].K * (p[k].B2 ? 2.0 : 1.0);   // hi + lo contracts over 2K
   const bool hilo = p[0].B2 != nullptr;

@@ -23,6 +23,11 @@ void prof_enable(bool on);
 bool prof_read(int family, const char** name, int64_t* launches, double* total_ms, double* units);
 
 constexpr int EW_MAX_BLOCKS = 65536;  // grid cap of the elementwise kernels (also the size of the norm partials)
+// A launcher that is handed a shape its kernel cannot run records the reason here and launches nothing; the C entry
+// points report it as an error (take_launch_error returns and clears it, null = none).
+void note_launch_error(const char* what);
+const char* take_launch_error();
+
 constexpr int MAX_BATCH = 2048;
 constexpr int MAX_TOKENS = 8192;   // encoder: token rows of one batch (the token-gradient kernel lists them in LDS)
 constexpr int MAX_WNET_HIDDEN = 256;

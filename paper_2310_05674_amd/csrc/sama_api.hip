@@ -179,6 +179,7 @@ static sama_status fail(sama_ctx* c, sama_status s, const std::string& msg) {
   return s;
 }
 static sama_status check_hip(sama_ctx* c, const char* what) {
+  if (const char* le = take_launch_error()) return fail(c, SAMA_EINVAL, std::string(what) + ": a kernel was not launched: " + le);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(c, SAMA_EHIP, std::string(what) + ": " + hipGetErrorString(e));
   return SAMA_OK;
