@@ -58,6 +58,21 @@ sama_status sama_op_perturb_lo(const float* theta, const float* vdir, const floa
 sama_status sama_op_nudge(float* theta, const float* vdir, const float* eps_ptr, void* theta16, int64_t n, int64_t n16,
                           void* hip_stream);
 
+/* Diagnostic switches, process-wide, for tests and profiling.  They take effect from the next launch and are not
+ * thread-safe.
+ *  - sama_dev_gemm_shape(id): every bf16 GEMM launch uses block tile `id`: 1..7 are the single-term tiles (a hi+lo
+ *    problem then runs as one contraction over the concatenated operands, which rounds differently from the hi+lo
+ *    tiles), 11..15 the hi+lo tiles (single-term problems ignore them); 0 = the heuristic (default).  Within a class
+ *    every tile gives the same bits.
+ *  - sama_dev_side_stream(0): the encoder's backward passes keep every launch on the context's stream instead of
+ *    running weight gradients and optimizer slices on the library's second stream (a per-kernel profile wants one
+ *    stream); 1 = default.  Changes no result bit.
+ *  - sama_dev_side_sink(0): the optimizer and adaptation slices wait for the end of the backward pass instead of
+ *    following each layer's gradients; 1 = default.  Changes no result bit. */
+void sama_dev_gemm_shape(int32_t id);
+void sama_dev_side_stream(int32_t on);
+void sama_dev_side_sink(int32_t on);
+
 #ifdef __cplusplus
 }
 #endif

@@ -7,9 +7,9 @@ using namespace sama;
 
 extern "C" {
 
-// Tuning hook (not declared in the public headers): block shape of the bf16 GEMM, 0 = heuristic.
+// Diagnostic switches (include/sama_ops.h): block shape of the bf16 GEMM, 0 = heuristic.
 void sama_dev_gemm_shape(int32_t shape) { gemm_bf16_force_shape(shape); }
-// Tuning hook: 0 keeps every launch of the encoder's backward pass on the context's stream.
+// 0 keeps every launch of the encoder's backward pass on the context's stream / makes the optimizer slices wait for its end.
 void sama_dev_side_stream(int32_t on) { encoder_side_stream(on != 0); }
 void sama_dev_side_sink(int32_t on) { encoder_side_sink(on != 0); }
 
