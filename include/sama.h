@@ -224,7 +224,10 @@ sama_status sama_set_lr(sama_ctx* ctx, float base_lr, float meta_lr);
 
 /* Copy a state vector out of / into the context (DEVICE pointers; sizes above).  Enqueued on the context's
  * stream.  sama_set_state(COUNTERS) synchronises the stream (the base step count lives on the host);
- * setting THETA also refreshes the bf16 working copy.  SCALARS, LOSSES, HYPERGRAD, GLAM_* are read-only. */
+ * setting THETA also refreshes the bf16 working copy.  SCALARS, LOSSES, HYPERGRAD, GLAM_* are read-only.
+ * The settable selectors (THETA, M, V, G, LAMBDA, META_M, META_V, COUNTERS) are a complete checkpoint: a fresh context
+ * of the same configuration that is handed them continues a run with the same bits (set the learning rates in force
+ * with sama_set_lr before COUNTERS). */
 sama_status sama_get_state(sama_ctx* ctx, int32_t which, void* dst /*DEVICE*/);
 sama_status sama_set_state(sama_ctx* ctx, int32_t which, const void* src /*DEVICE*/);
 

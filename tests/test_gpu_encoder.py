@@ -404,3 +404,35 @@ def test_eval_small_encoder_with_padding():
     print(f"eval: logits {rel_l2(zo.cpu().numpy(), z):.2e} losses {rel_l2(lo.cpu().numpy(), l):.2e} weights {rel_l2(wo.cpu().numpy(), w):.2e}")
     assert rel_l2(zo.cpu().numpy(), z) < KTOL and rel_l2(lo.cpu().numpy(), l) < KTOL and rel_l2(wo.cpu().numpy(), w) < KTOL
     gpu.close()
+
+
+def test_checkpoint_and_resume_continue_bit_for_bit():
+    """The settable state (theta, the moments, the kept gradient, lambda and its moments, the counters) is everything a
+    run needs: a fresh context that is handed the state of a run after 6 iterations continues with the bits of the
+    uninterrupted run (bf16 encoder, two streams, scheduled rates)."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    names = ("THETA", "M", "V", "G", "LAMBDA", "META_M", "META_V")
+    rate = lambda k: 1e-3 * (1.0 - 0.05 * k)
+
+    def run(gpu, k0, k1):
+        for k in range(k0, k1):
+            (x, y), (xm, ym) = _batches(wl, k)
+            tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+            gpu.set_lr(rate(k), 1e-3)
+            gpu.base_step(tb); gpu.meta_step(tb, mb)
+
+    _, a = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    run(a, 0, 6)
+    saved = {n: pull(a, n).copy() for n in names}
+    counters = pull(a, "COUNTERS").copy()
+    run(a, 6, 10)
+    want = {n: pull(a, n).copy() for n in names + ("HYPERGRAD", "COUNTERS")}
+    a.close()
+    _, b = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    for n in names:
+        b.set_state(n, saved[n])
+    b.set_state("COUNTERS", counters)
+    run(b, 6, 10)
+    for n in want:
+        assert np.array_equal(pull(b, n), want[n]), n
+    b.close()
