@@ -34,7 +34,7 @@
  *         (two dims = multinomial logistic regression; hidden layers use ReLU)
  *    ENCODER dims = {L, d, heads, ffn, S, V, C}  (post-LN, learned positions, erf-GELU, LN eps 1e-5,
  *         softmax(q k^T / sqrt(d/heads)) over the real tokens of a sequence (sama_batch.seq_len), classifier on the
- *         position-0 hidden state; supported shapes: S = 64, 128 or 256, d / heads = 64, d <= 1024, ffn % 64 = 0,
+ *         position-0 hidden state; supported shapes: S = 64, 128 or 256, d / heads = 64, d <= 2048, ffn % 64 = 0,
  *         at most 8192 token rows per batch):
  *         per layer l: Wqkv[3d x d] (rows 0..d-1 = Q, d..2d-1 = K, 2d..3d-1 = V; head h owns rows h*d/heads..),
  *                      Wo[d x d], W1[ffn x d], W2[d x ffn];

@@ -343,7 +343,7 @@ Model* make_encoder(const sama_config& c, const std::vector<TensorInfo>& layout,
   const int d = c.dims[1], heads = c.dims[2], ffn = c.dims[3], S = c.dims[4];
   if (!attention_supports(S)) { err = "the encoder kernels are built for S = 64, 128 or 256"; return nullptr; }
   if (d / heads != 64 || d % heads != 0) { err = "the attention kernels are built for head width d/heads = 64"; return nullptr; }
-  if (d > LN_MAX_D) { err = "d must be <= 1024"; return nullptr; }
+  if (d > LN_MAX_D) { err = "d must be <= 2048"; return nullptr; }
   if (ffn % 64 != 0) { err = "ffn must be a multiple of 64"; return nullptr; }
   const int tb = c.max_batch + (c.aux_mlm ? c.max_aux_batch : 0);
   const int mb = tb > c.max_meta_batch ? tb : c.max_meta_batch;

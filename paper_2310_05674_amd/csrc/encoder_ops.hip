@@ -14,16 +14,18 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr float LN_EPS = 1e-5f;
 
 // =========================================================================================== LayerNorm forward
-// One wave per row; the row lives in registers (d <= 1024).  Statistics in fp32 with a centred second pass.
+// One wave per row; the row lives in registers, NV 16-byte pieces per lane (d <= 256 NV).  Statistics in fp32 with a centred
+// second pass.
+template <int NV>
 __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= a.M) return;
   const int nq = a.d >> 2;  // float4 chunks per row
   const float sc = a.pv.scale_row(row);
-  float4 xr[4];
+  float4 xr[NV];
   float sum = 0.f;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NV; ++j) {
     const int q = lane + 64 * j;
     xr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (q < nq) {
@@ -46,7 +48,7 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
   const float mu = wave_sum(sum) / (float)a.d;
   float sq = 0.f;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NV; ++j) {
     if (lane + 64 * j < nq) {
       const float e0 = xr[j].x - mu, e1 = xr[j].y - mu, e2 = xr[j].z - mu, e3 = xr[j].w - mu;
       sq += (e0 * e0 + e1 * e1) + (e2 * e2 + e3 * e3);
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
     if (a.rstd != nullptr) a.rstd[row] = rstd;
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NV; ++j) {
     const int q = lane + 64 * j;
     if (q < nq) {
       float4 g = *reinterpret_cast<const float4*>(a.pv.theta + a.g_off + 4 * q), b = *reinterpret_cast<const float4*>(a.pv.theta + a.b_off + 4 * q);
@@ -82,19 +84,20 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
 // dx = rstd (dy g - mean(dy g) - xh mean(dy g xh)); per-block partial sums of dgamma = dy xh, dbeta = dy and of
 // dx itself (the bias gradient of the linear layer feeding this LayerNorm).  A block owns LN_BWD_ROWS rows,
 // each wave walks its rows in order, lanes keep per-column accumulators, the four waves are added in order.
+template <int NV>
 __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
-  __shared__ float s_acc[4][3][LN_MAX_D];
+  __shared__ float s_acc[4][3][256 * NV];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nq = a.d >> 2;
-  float4 dg[4], db[4], dc[4], gam[4];
+  float4 dg[NV], db[NV], dc[NV], gam[NV];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NV; ++j) {
     dg[j] = db[j] = dc[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     gam[j] = (lane + 64 * j < nq) ? reinterpret_cast<const float4*>(a.gamma)[lane + 64 * j] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const int r0 = blockIdx.x * LN_BWD_ROWS + wave * (LN_BWD_ROWS / 4);
   constexpr int RW = LN_BWD_ROWS / 4;   // rows per wave: all of their loads are issued before the first row is reduced
-  float4 xin[RW][4], dyin[RW][4];
+  float4 xin[RW][NV], dyin[RW][NV];
   float mus[RW], rstds[RW];
 #pragma unroll
   for (int rr = 0; rr < RW; ++rr) {
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
     mus[rr] = rstds[rr] = 0.f;
     if (row < a.M) { mus[rr] = a.mean[row]; rstds[rr] = a.rstd[row]; }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NV; ++j) {
       const int q = lane + 64 * j;
       xin[rr][j] = dyin[rr][j] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (row < a.M && q < nq) {
@@ -116,10 +119,10 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
     const int row = r0 + rr;
     if (row >= a.M) break;
     const float mu = mus[rr], rstd = rstds[rr];
-    float4 xh[4], dyg[4];
+    float4 xh[NV], dyg[NV];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NV; ++j) {
       const int q = lane + 64 * j;
       xh[j] = dyg[j] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (q < nq) {
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
     }
     const float m1 = wave_sum(s1) / (float)a.d, m2 = wave_sum(s2) / (float)a.d;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NV; ++j) {
       const int q = lane + 64 * j;
       if (q < nq) {
         float4 dx;
@@ -154,7 +157,7 @@ __global__ __launch_bounds__(256) void k_ln_bwd(LnBwdArgs a) {
     }
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < NV; ++j) {
     const int q = lane + 64 * j;
     if (q < nq) {
       reinterpret_cast<float4*>(s_acc[wave][0])[q] = dg[j];
@@ -606,11 +609,13 @@ __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb
 
 void launch_ln_fwd(hipStream_t st, const LnFwdArgs& a) {
   ProfScope ps(st, F_LN_FWD, 6.0 * a.M * a.d);
-  k_ln_fwd<<<(a.M + 3) / 4, 256, 0, st>>>(a);
+  if (a.d <= 1024) k_ln_fwd<4><<<(a.M + 3) / 4, 256, 0, st>>>(a);
+  else k_ln_fwd<8><<<(a.M + 3) / 4, 256, 0, st>>>(a);
 }
 void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) {
   ProfScope ps(st, F_LN_BWD, 14.0 * a.M * a.d);
-  k_ln_bwd<<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
+  if (a.d <= 1024) k_ln_bwd<4><<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
+  else k_ln_bwd<8><<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
 }
 void launch_reduce_rows_multi(hipStream_t st, const ReduceRowsJob* jobs, int count) {
   ReduceRowsMulti m{};

@@ -90,6 +90,8 @@ def test_bad_configs_rejected(lib):
                 pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 256, 100, 3), H=16, max_batch=33, max_meta_batch=8)):   # 8448 tokens
         assert lib.sama_workspace_bytes(C.byref(bad)) == 0
         assert lib.sama_last_error(None) != b""
+    assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("encoder", (1, 2048, 32, 2048, 64, 100, 3), **good))) > 0
+    assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("encoder", (1, 2112, 33, 2048, 64, 100, 3), **good))) == 0   # d > 2048
     for S in (64, 128, 256):
         assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("encoder", (2, 128, 2, 256, S, 100, 3), **good))) > 0
     assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("encoder", (2, 128, 2, 256, 256, 100, 3), H=16, max_batch=32,
