@@ -93,8 +93,7 @@ class EncoderModel : public Model {
   // batch, stacked along the row dimension (forward only, keep must be false); logits [nw B x C].
   void run_forward(hipStream_t st, const PassWeights* w, int nw, const sama_batch& b, bool keep, float* logits) {
     const int B = b.n, M = B * S_, R = nw * M;
-    ParamView pv{w[0].theta, w[0].vdir, w[0].eps_ptr, w[0].sign};
-    pv.flip_row = nw == 2 ? M : 0;
+    ParamView pv{w[0].theta, w[0].vdir, w[0].eps_ptr, w[0].sign, nw == 2 ? M : 0};
     LnFwdArgs e{};
     e.x = nullptr; e.ids = (const int32_t*)b.x; e.ids_rows = M; e.S = S_; e.tok_off = tok_; e.pos_off = pos_; e.x_out = keep ? pre0_ : nullptr;
     e.pv = pv; e.g_off = eg_; e.b_off = eb_; e.y = X_[0]; e.y32 = res_[0]; e.mean = keep ? mean0_ : nullptr; e.rstd = keep ? rstd0_ : nullptr;

@@ -236,7 +236,6 @@ __global__ __launch_bounds__(256) void k_colsum_partial_bf16(ColsumMulti m) {
 constexpr int AD = 64;  // head width
 
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16_t* p) { return *reinterpret_cast<const bf16x8*>(p); }
-__device__ __forceinline__ s16x4 ld_s16x4(const bf16_t* p) { return *reinterpret_cast<const s16x4*>(p); }
 __device__ __forceinline__ s16x4 pack4(float a, float b, float c, float d) {
   s16x4 r;
   r[0] = (short)f32_to_bf16(a); r[1] = (short)f32_to_bf16(b); r[2] = (short)f32_to_bf16(c); r[3] = (short)f32_to_bf16(d);
@@ -373,7 +372,7 @@ __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv
                                                   const bf16_t* __restrict__ dout, const float* __restrict__ lse,
                                                   bf16_t* __restrict__ dqkv, int heads, int d, const int32_t* __restrict__ lens,
                                                   int lens_period) {
-  constexpr int S = 32 * NT;
+  constexpr int S = 32 * NT, TILE_UNROLL = NT <= 4 ? NT : 1;
   __shared__ __attribute__((aligned(16))) bf16_t Ks[S * SLD];
   __shared__ __attribute__((aligned(16))) bf16_t Qs[S * SLD];
   __shared__ __attribute__((aligned(16))) bf16_t dOs[S * SLD];
@@ -420,7 +419,7 @@ __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv
       for (int et = 0; et < 2; ++et)
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[et][r] = 0.f;
-#pragma unroll(NT <= 4 ? NT : 1)   // the long sequences keep one tile's operands in flight: unrolled they spill
+#pragma unroll TILE_UNROLL   // the long sequences keep one tile's operands in flight: unrolled they spill
       for (int kt = 0; kt < NT; ++kt) {
         f32x16 st = rows_dot_rows(K, Q, ld, 32 * kt, 32 * qt, lane);     // S^T[key][q]
         const bf16_t* vp = V + (int64_t)(32 * kt + (lane & 31)) * ld + 8 * (lane >> 5);
@@ -467,7 +466,7 @@ __global__ __launch_bounds__(512) void k_attn_bwd(const bf16_t* __restrict__ qkv
       for (int et = 0; et < 2; ++et)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dk[et][r] = 0.f; dv[et][r] = 0.f; }
-#pragma unroll(NT <= 4 ? NT : 1)
+#pragma unroll TILE_UNROLL
       for (int qt = 0; qt < NT; ++qt) {
         f32x16 st = rows_dot_rows(Q, K, ld, 32 * qt, 32 * kt, lane);     // S[q][key]
         const bf16_t* dop = dO + (int64_t)(32 * qt + (lane & 31)) * d + 8 * (lane >> 5);
