@@ -49,6 +49,22 @@ sama_status sama_op_adapt_norm(const float* g, const float* m, const float* v, c
                                double* partial, int64_t n, int64_t t, float lr, float beta1, float beta2, float eps,
                                float alpha, float* scalars, int64_t* status, void* hip_stream);
 
+/* sama_op_adapt_norm for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments without `partial`, same results bit for bit: the
+ * partial sums live in a 512 KB array inside the library's device image (one copy per GPU, held until the process
+ * ends) whose address is resolved once per device at the first call there.  The call allocates nothing.  n must not
+ * exceed SAMA_OP_STATIC_MAX_N; a larger n returns SAMA_EINVAL, launches nothing, and sama_op_last_error() says why.
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different streams or threads)
+ * race on it -- serialise them, or use sama_op_adapt_norm with separate scratch buffers.  Nothing in the array needs
+ * clearing between calls (each call overwrites the entries it reads). */
+#define SAMA_OP_STATIC_MAX_N ((int64_t)1 << 29)
+sama_status sama_op_adapt_norm_static(const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
+                                      int64_t n, int64_t t, float lr, float beta1, float beta2, float eps, float alpha,
+                                      float* scalars, int64_t* status, void* hip_stream);
+/* Text of the last error of an op-level call on this thread (HOST string owned by the library, "" if none); set by
+ * sama_op_adapt_norm_static. */
+const char* sama_op_last_error(void);
+
 /* Low halves of theta +- eps v against the bf16 working copy (Eq. 5): lo_p/lo_m[k] = bf16((theta[k] +- eps v[k]) -
  * float(bf16(theta[k]))), eps read from DEVICE eps_ptr. */
 sama_status sama_op_perturb_lo(const float* theta, const float* vdir, const float* eps_ptr, void* lo_p, void* lo_m,

@@ -111,6 +111,9 @@ def load_library():
     L.sama_op_adam.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, f32, f32, f32, f32, vp]
     L.sama_op_adapt_norm.restype = C.c_int
     L.sama_op_adapt_norm.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, f32, f32, vp, vp, vp]
+    L.sama_op_adapt_norm_static.restype = C.c_int
+    L.sama_op_adapt_norm_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, f32, f32, vp, vp, vp]
+    L.sama_op_last_error.restype = C.c_char_p; L.sama_op_last_error.argtypes = []
     L.sama_op_perturb_lo.restype = C.c_int; L.sama_op_perturb_lo.argtypes = [vp, vp, vp, vp, vp, i64, vp]
     L.sama_op_nudge.restype = C.c_int; L.sama_op_nudge.argtypes = [vp, vp, vp, vp, i64, i64, vp]
     _lib = L
@@ -341,6 +344,15 @@ def op_adapt_norm(g, m, v, gmeta, vdir, partial, t, lr, beta1, beta2, eps, alpha
                                            eps, alpha, _p(scalars), _p(status), _stream())
     if rc != 0:
         raise SamaError(rc, "sama_op_adapt_norm rejected the arguments")
+
+
+def op_adapt_norm_static(g, m, v, gmeta, vdir, t, lr, beta1, beta2, eps, alpha, scalars, status, n=None):
+    """sama_op_adapt_norm with the library's own static scratch (allocates nothing); n defaults to g.numel()."""
+    L = load_library()
+    rc = L.sama_op_adapt_norm_static(_p(g), _p(m), _p(v), _p(gmeta), _p(vdir), g.numel() if n is None else n, t, lr, beta1, beta2,
+                                     eps, alpha, _p(scalars), _p(status), _stream())
+    if rc != 0:
+        raise SamaError(rc, L.sama_op_last_error().decode() or "sama_op_adapt_norm_static failed")
 
 
 def op_perturb_lo(theta, vdir, eps_t, lo_p, lo_m, n16):

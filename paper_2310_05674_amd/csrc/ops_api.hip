@@ -1,9 +1,37 @@
 // Op-level C entry points (include/sama_ops.h): thin argument checks around the kernel launchers.
 #include <math.h>
+#include <mutex>
+#include <string>
 #include "../../include/sama_ops.h"
 #include "kernels.h"
 
 using namespace sama;
+
+// Scratch of sama_op_adapt_norm_static: the per-block partial sums of ||v||^2 that sama_op_adapt_norm takes from its
+// caller.  One copy per GPU the library runs on, alive until the process ends; host code never uses the array's name
+// as an address, only the per-device pointers resolved below.
+static __device__ __align__(256) double scratch[EW_MAX_BLOCKS];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[MAX_DEVICES] = {};   // device address of `scratch` on each GPU, resolved at the first call there
+thread_local std::string g_ops_error;
+
+// The current device's copy of `scratch`; null (and g_ops_error set) if it cannot be resolved.
+double* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { g_ops_error = "no current HIP device (or device index above 63)"; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    double* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) { g_ops_error = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e); return nullptr; }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
 
 extern "C" {
 
@@ -73,6 +101,23 @@ sama_status sama_op_adapt_norm(const float* g, const float* m, const float* v, c
   launch_adapt_norm((hipStream_t)hip_stream, g, m, v, gmeta, vdir, partial, n, ad, alpha, scalars, status);
   return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
 }
+
+sama_status sama_op_adapt_norm_static(const float* g, const float* m, const float* v, const float* gmeta, float* vdir, int64_t n,
+                                      int64_t t, float lr, float beta1, float beta2, float eps, float alpha, float* scalars,
+                                      int64_t* status, void* hip_stream) {
+  g_ops_error.clear();
+  if (n > SAMA_OP_STATIC_MAX_N) {
+    g_ops_error = "sama_op_adapt_norm_static: n exceeds SAMA_OP_STATIC_MAX_N (2^29 elements); use sama_op_adapt_norm with a caller-owned scratch";
+    return SAMA_EINVAL;
+  }
+  double* partial = static_scratch();
+  if (partial == nullptr) return SAMA_EHIP;
+  const sama_status s = sama_op_adapt_norm(g, m, v, gmeta, vdir, partial, n, t, lr, beta1, beta2, eps, alpha, scalars, status, hip_stream);
+  if (s == SAMA_EINVAL) g_ops_error = "sama_op_adapt_norm_static: null or misaligned pointer, n < 1 or t < 1";
+  return s;
+}
+
+const char* sama_op_last_error(void) { return g_ops_error.c_str(); }
 
 sama_status sama_op_perturb_lo(const float* theta, const float* vdir, const float* eps_ptr, void* lo_p, void* lo_m, int64_t n16,
                                void* hip_stream) {
