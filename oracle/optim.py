@@ -19,6 +19,15 @@ def sgd_update(theta, g, lr):
     return theta - lr * g
 
 
+def sgd_momentum_update(theta, buf, g, lr, mu):
+    """SGD with heavy-ball momentum mu, the form the common frameworks' SGD takes with a `momentum` argument
+    (no dampening, no Nesterov look-ahead): b' = mu b + g, theta' = theta - lr b'.  The paper's hyperparameter
+    tables (App. B) name only "SGD"; reading: this form.  Returns (theta', b').  In the paper's notation
+    u(g) = lr (mu b + g), so du/dg = lr as for plain SGD (sgd_adaptation)."""
+    b2 = mu * buf + g
+    return theta - lr * b2, b2
+
+
 def adam_adaptation(g, m_post, v_post, t, lr, beta1, beta2, eps, keep_eps_term=False):
     """Diagonal of du_adam/dg (App. C), evaluated with the moments AFTER the step that consumed g
     (m' = beta1 m + (1-beta1) g, v' = beta2 v + (1-beta2) g^2) and that step's bias corrections.

@@ -16,7 +16,7 @@ class SamaOracle:
     def __init__(self, model, theta0, lambda0, *, base_opt=ADAM, base_lr=1e-3, beta1=0.9, beta2=0.999,
                  adam_eps=1e-8, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999, meta_eps=1e-8,
                  alpha=1.0, adapt_mode=optim.ADAPT_ADAM, corr_hidden=0, corr_kappa=4.0, n_classes=None,
-                 weight_decay=0.0):
+                 weight_decay=0.0, momentum=0.0):
         self.model = model
         self.theta = np.array(theta0, dtype=np.float64)
         self.lam = np.array(lambda0, dtype=np.float64)
@@ -32,6 +32,10 @@ class SamaOracle:
         # reading: the base optimizer's weight decay (the "wdecay" column of the hyperparameter tables of App. B) is an L2
         # term, weight_decay * theta added to the gradient before the solver; g, as kept for the adaptation, includes it
         self.weight_decay = float(weight_decay)
+        # reading: "SGD" in the tables of App. B may carry heavy-ball momentum; the velocity lives in self.m
+        self.momentum = float(momentum)
+        if self.momentum != 0.0 and base_opt != SGD:
+            raise ValueError("momentum belongs to the SGD base solver")
         self.status = 0                # 1 after a meta step skipped for ||v|| = 0 / non-finite
         # label correction (Sec. 4.1): lambda = [lambda_r | lambda_c]; corr_hidden = 0 turns it off
         self.Hc, self.kappa, self.C = int(corr_hidden), float(corr_kappa), n_classes
@@ -62,6 +66,8 @@ class SamaOracle:
         if self.base_opt == ADAM:
             self.theta, self.m, self.v = optim.adam_update(self.theta, self.m, self.v, g, self.t, self.base_lr,
                                                            self.beta1, self.beta2, self.adam_eps)
+        elif self.momentum != 0.0:
+            self.theta, self.m = optim.sgd_momentum_update(self.theta, self.m, g, self.base_lr, self.momentum)
         else:
             self.theta = optim.sgd_update(self.theta, g, self.base_lr)
         return float(np.sum(coef * l))

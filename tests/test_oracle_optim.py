@@ -89,3 +89,25 @@ def test_sgd_reduction():
     g = np.arange(5.0)
     assert np.all(optim.sgd_adaptation(g, 0.3) == 0.3)
     assert np.allclose(optim.sgd_update(np.ones(5), g, 0.1), 1.0 - 0.1 * g)
+
+
+def test_sgd_momentum_by_hand_and_its_adaptation():
+    """Heavy-ball SGD (reading of "SGD" in the tables of App. B): two steps on a scalar written out by hand; the update's
+    derivative in the gradient it was given is the learning rate (central difference), as sgd_adaptation says; zero
+    momentum is plain SGD bit for bit."""
+    lr, mu = 0.1, 0.9
+    th, b = 1.0, 0.0
+    b = mu * b + 0.5; th = th - lr * b            # step 1, g = 0.5: b = 0.5, theta = 0.95
+    b = mu * b - 0.25; th = th - lr * b           # step 2, g = -0.25: b = 0.2, theta = 0.93
+    assert abs(b - 0.2) < 1e-15 and abs(th - 0.93) < 1e-15
+    T, B = np.array([1.0]), np.array([0.0])
+    for g in (0.5, -0.25):
+        T, B = optim.sgd_momentum_update(T, B, np.array([g]), lr, mu)
+    assert abs(T[0] - 0.93) < 1e-15 and abs(B[0] - 0.2) < 1e-15
+    r = CounterRNG(11)
+    g, buf, th0 = r.normal(1, 50), r.normal(2, 50), r.normal(3, 50)
+    u = lambda gg: th0 - optim.sgd_momentum_update(th0, buf, gg, lr, mu)[0]
+    fd = (u(g + 1e-4) - u(g - 1e-4)) / 2e-4
+    assert np.allclose(fd, optim.sgd_adaptation(g, lr), rtol=1e-9)
+    t2, b2 = optim.sgd_momentum_update(th0, buf, g, lr, 0.0)
+    assert np.array_equal(t2, optim.sgd_update(th0, g, lr)) and np.array_equal(b2, g)

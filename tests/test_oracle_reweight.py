@@ -111,6 +111,27 @@ def test_sgd_invariant():
     assert np.allclose(rna["h"], r1["h"], rtol=1e-12) and np.allclose(rna["v"], r1["g_meta"], rtol=0, atol=0)
 
 
+def test_sgd_momentum_in_the_assembled_recipe():
+    """Heavy-ball momentum in the SGD base solver: the oracle's trajectory equals steps written out by hand from its own
+    kept gradients (velocity in `m`), the adaptation stays the scalar step size (v = gamma g_meta), and mu = 0 is plain
+    SGD bit for bit."""
+    model, x, y, xm, ym, th, lam = _tiny()
+    o = SamaOracle(model, th, lam, base_opt=SGD, base_lr=0.05, momentum=0.8, alpha=0.3)
+    p = SamaOracle(model, th, lam, base_opt=SGD, base_lr=0.05, alpha=0.3)
+    z = SamaOracle(model, th, lam, base_opt=SGD, base_lr=0.05, momentum=0.0, alpha=0.3)
+    b, t_hand = np.zeros_like(th), np.array(th, dtype=np.float64)
+    for k in range(3):
+        o.base_step(x, y); p.base_step(x, y); z.base_step(x, y)
+        b = 0.8 * b + o.g
+        t_hand = t_hand - 0.05 * b
+        assert np.allclose(o.theta, t_hand, rtol=0, atol=1e-15) and np.allclose(o.m, b, rtol=0, atol=1e-15)
+    assert np.array_equal(z.theta, p.theta) and not np.allclose(o.theta, p.theta)
+    r = o.meta_grad(x, y, xm, ym)
+    assert np.array_equal(r["v"], 0.05 * r["g_meta"])
+    with np.testing.assert_raises(ValueError):
+        SamaOracle(model, th, lam, base_opt=ADAM, momentum=0.5)
+
+
 def test_meta_step_bookkeeping():
     model, x, y, xm, ym, th, lam = _tiny()
     orc = _after_steps(SamaOracle(model, th, lam, base_lr=1e-2, meta_lr=1e-3, alpha=0.7), x, y, k=4)
