@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--workload", type=int, default=5, help="BASELINE.json config number 1..5")
     ap.add_argument("--unroll", type=int, default=1)
     ap.add_argument("--fast-meta-pass", type=int, default=0)
+    ap.add_argument("--fast-base-pass", type=int, default=0,
+                    help="1: the base step contracts with the bf16 working copy alone (ordinary mixed precision) instead of the "
+                         "two-term split of the fp32 master weights; not the configuration the parity tests prove")
     ap.add_argument("--corr-hidden", type=int, default=0,
                     help="label correction (Sec. 4.1) with a corrector of this hidden width; 0 = the headline data-reweighting workload")
     ap.add_argument("--aux", action="store_true",
@@ -90,7 +93,7 @@ def main():
         lam0 = np.concatenate([lam0, init_lambda_corr(wl, args.corr_hidden)])
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=wl.batch, max_meta_batch=wl.meta_batch,
                               base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
-                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass, corr_hidden=args.corr_hidden,
+                              adam_eps=wl.adam_eps, fast_meta_pass=args.fast_meta_pass, fast_base_pass=args.fast_base_pass, corr_hidden=args.corr_hidden,
                               **(dict(aux_mlm=1, max_aux_batch=AUX_TASK["n_pt"], max_aux_masked=AUX_TASK["n_pt"] * (AUX_TASK["dims"][4] // 5 + 1)) if args.aux else {}))
     s = pkg.Sama(cfg, th0, lam0)
     n, n16 = s.n, s.lib.sama_gemm_param_count(__import__("ctypes").byref(cfg))
@@ -169,7 +172,7 @@ def main():
                    ("MLP " + "-".join(map(str, wl.dims)) if wl.kind == "mlp" else
                     "encoder L={} d={} heads={} ffn={} S={} V={} C={}".format(*wl.dims)),
                    "params": int(n), "train_batch": wl.batch, "meta_batch": wl.meta_batch, "unroll": args.unroll,
-                   "launch": "hip graph replay" if args.graph else "eager", "padding": "length mix" if args.length_mix else "none", "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo",
+                   "launch": "hip graph replay" if args.graph else "eager", "padding": "length mix" if args.length_mix else "none", "wnet_hidden": wl.H, "corr_hidden": args.corr_hidden, "n_lambda": int(s.nl), "meta_pass": "bf16" if args.fast_meta_pass else "split hi+lo", "base_pass": "bf16" if args.fast_base_pass else "split hi+lo",
                    "last_step_skipped": bool(skipped),
                    "workspace_bytes": int(s.lib.sama_workspace_bytes(__import__("ctypes").byref(cfg)))},
     }

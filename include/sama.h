@@ -69,7 +69,8 @@ typedef enum {
   SAMA_ESTATE = 2,     /* call order: sama_meta_grad / sama_meta_step before any sama_base_step */
   SAMA_EWORKSPACE = 3, /* workspace missing, misaligned or too small */
   SAMA_EHIP = 4,       /* a HIP runtime call failed; see sama_last_error */
-  SAMA_ENONFINITE = 5  /* reserved for callers that read the device status word */
+  SAMA_ENONFINITE = 5  /* never returned by the library (non-finite values are only visible on the device): the code a
+                          caller may use to report a raised status word */
 } sama_status;
 
 enum { SAMA_MODEL_MLP = 0, SAMA_MODEL_ENCODER = 1 };
@@ -88,6 +89,8 @@ typedef struct {
   float base_lr, beta1, beta2, adam_eps; /* gamma, beta_1, beta_2, epsilon of App. C */
   float weight_decay;  /* L2 coefficient (the wdecay column of App. B): weight_decay * theta is added to the base gradient
                         * before the solver; the G state and the adaptation of Eq. 4 use that sum */
+  float momentum;      /* SGD only: heavy-ball momentum mu in [0, 1), b <- mu b + g, theta <- theta - base_lr b (the velocity b
+                        * is the M state).  du/dg stays base_lr, so the adaptation of Eq. 4 is unchanged.  Must be 0 for Adam */
   float meta_lr, meta_beta1, meta_beta2, meta_eps; /* Adam on lambda (Table 4) */
   float alpha;         /* eps = alpha / ||v||_2, Sec. 3.2 below Eq. 5 */
   int32_t adapt_mode;  /* SAMA_ADAPT_OPTIMIZER: du/dg of base_opt (App. C for Adam, gamma for SGD);
@@ -98,6 +101,12 @@ typedef struct {
                              two-term split hi + lo of the fp32 master weights, so dL_meta/dtheta is taken at theta
                              and not at bf16(theta) (costs two extra forward-equivalents of GEMM work per meta
                              step).  1: that pass uses the bf16 working copy like a base step. */
+  int32_t fast_base_pass; /* BF16 models only.  0 (default): the base step's forward and input-gradient GEMMs contract with the
+                             same two-term split hi + lo, so the base gradient g (and with it the adaptation of Eq. 4) is
+                             taken at the fp32 master theta; this is what matches the float64 reference from any state (costs
+                             two extra forward-equivalents of GEMM work per base step).  1: ordinary mixed precision -- the
+                             base step sees only the bf16 working copy, whose rounding hides updates smaller than half a
+                             bf16 ulp of a weight (every update at learning rates around 1e-5). */
   int32_t corr_hidden;    /* Hc: hidden width of the label corrector, 0 = no label correction, at most 128; needs C <= 16 */
   float corr_kappa;       /* kappa >= 0: fixed prior on the given label inside the corrector */
   int32_t aux_mlm;        /* 1: auxiliary-task reweighting (Sec. 4.3).  ENCODER only; theta gains a masked-token head
@@ -109,7 +118,8 @@ typedef struct {
 } sama_config;
 
 /* One batch.  x: DEVICE, fp32 [n x d0] row-major (MLP) or int32 token ids [n x S] (ENCODER), ids in [0, V).
- * y: DEVICE int32 [n], labels in [0, C).  sample_mask: DEVICE uint8 [n], 1 = use, 0 = ignore, or NULL = use all.
+ * y: DEVICE int32 [n], labels in [0, C).  Token ids and labels outside their range are clamped into it on the device,
+ * not reported (the same rule as for the rows and targets of sama_aux_batch).  sample_mask: DEVICE uint8 [n], 1 = use, 0 = ignore, or NULL = use all.
  * seq_len (ENCODER; ignored by the MLP): DEVICE int32 [n], the number of real tokens of each padded sequence, or NULL =
  * every sequence fills all S positions.  Keys at positions >= seq_len get no attention weight (key-padding mask);
  * values are clamped into [1, S]; what sits in the padded positions of x then has no influence on any result.
@@ -139,7 +149,9 @@ typedef struct {
  * THETA, M, V, G, GMETA, VDIR: n fp32 (M, V = Adam moments m, v of App. C; G = g_base of the last base step,
  * Eq. 4; GMETA = dL_meta/dtheta, Eq. 1; VDIR = the perturbation vector v of Eq. 5);
  * LAMBDA, META_M, META_V, HYPERGRAD, GLAM_PLUS, GLAM_MINUS: n_lambda fp32;
- * COUNTERS: 4 int64 = {base step count t, meta step count, status word (0 ok, 1 = last meta step skipped), 0};
+ * COUNTERS: 4 int64 = {base step count t, meta step count, status word (0 ok, 1 = last meta step skipped: ||v|| was zero or
+ * not finite, or the hypergradient was not finite; lambda, theta and the meta moments are then left as they were, up to
+ * one fp32 rounding of theta's GEMM block, which is nudged early and nudged back), 0};
  * SCALARS: 4 fp32 = {eps of the last meta gradient, ||v||_2, L_base of the last base step, L_meta of the last meta pass};
  * LOSSES: max(max_batch (+ max_aux_batch with aux_mlm), max_meta_batch) fp32, per-sample losses of the most recent
  * forward pass. */
@@ -205,8 +217,8 @@ sama_status sama_aux_meta_step(sama_ctx* ctx, const sama_aux_batch* pt, const sa
  * logits_out [n x C] (row-major), losses_out [n] = l_i (against the corrected soft label when label correction is on),
  * weights_out [n] = w(l_i; lambda) -- the per-sample importance the meta learner has learned (what the reweighting and
  * pruning applications of Sec. 4 read off it).  DEVICE pointers, each may be NULL.  n up to max(max_batch,
- * max_meta_batch); sample_mask is ignored, seq_len honoured.  bf16 models evaluate at the bf16 working copy, as the base
- * step's forward does.  Changes no state (LOSSES and SCALARS keep what the last step left). */
+ * max_meta_batch); sample_mask is ignored, seq_len honoured.  bf16 models evaluate with the weights the base
+ * step's forward uses (fast_base_pass).  Changes no state (LOSSES and SCALARS keep what the last step left). */
 sama_status sama_eval(sama_ctx* ctx, const sama_batch* batch, float* logits_out /*DEVICE*/, float* losses_out /*DEVICE*/,
                       float* weights_out /*DEVICE*/);
 

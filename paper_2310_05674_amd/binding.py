@@ -16,16 +16,16 @@ class SamaConfig(C.Structure):
     _fields_ = [("model_kind", C.c_int32), ("n_dims", C.c_int32), ("dims", C.c_int32 * 8),
                 ("param_dtype", C.c_int32), ("wnet_hidden", C.c_int32), ("base_opt", C.c_int32),
                 ("base_lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("adam_eps", C.c_float),
-                ("weight_decay", C.c_float), ("meta_lr", C.c_float), ("meta_beta1", C.c_float),
+                ("weight_decay", C.c_float), ("momentum", C.c_float), ("meta_lr", C.c_float), ("meta_beta1", C.c_float),
                 ("meta_beta2", C.c_float), ("meta_eps", C.c_float), ("alpha", C.c_float),
                 ("adapt_mode", C.c_int32), ("max_batch", C.c_int32), ("max_meta_batch", C.c_int32),
-                ("fast_meta_pass", C.c_int32), ("corr_hidden", C.c_int32), ("corr_kappa", C.c_float),
+                ("fast_meta_pass", C.c_int32), ("fast_base_pass", C.c_int32), ("corr_hidden", C.c_int32), ("corr_kappa", C.c_float),
                 ("aux_mlm", C.c_int32), ("max_aux_batch", C.c_int32), ("max_aux_masked", C.c_int32)]
 
     @classmethod
     def make(cls, kind, dims, *, H, max_batch, max_meta_batch, base_opt=OPT_ADAM, base_lr=1e-3, beta1=0.9,
              beta2=0.999, adam_eps=1e-8, weight_decay=0.0, meta_lr=1e-3, meta_beta1=0.9, meta_beta2=0.999,
-             meta_eps=1e-8, alpha=1.0, adapt_mode=ADAPT_OPTIMIZER, bf16=None, fast_meta_pass=0, corr_hidden=0,
+             meta_eps=1e-8, alpha=1.0, adapt_mode=ADAPT_OPTIMIZER, bf16=None, fast_meta_pass=0, fast_base_pass=0, momentum=0.0, corr_hidden=0,
              corr_kappa=4.0, aux_mlm=0, max_aux_batch=0, max_aux_masked=0):
         c = cls()
         c.model_kind = MODEL_MLP if kind == "mlp" else MODEL_ENCODER
@@ -39,7 +39,7 @@ class SamaConfig(C.Structure):
         c.base_opt, c.base_lr, c.beta1, c.beta2, c.adam_eps, c.weight_decay = base_opt, base_lr, beta1, beta2, adam_eps, weight_decay
         c.meta_lr, c.meta_beta1, c.meta_beta2, c.meta_eps = meta_lr, meta_beta1, meta_beta2, meta_eps
         c.alpha, c.adapt_mode, c.max_batch, c.max_meta_batch = alpha, adapt_mode, max_batch, max_meta_batch
-        c.fast_meta_pass = fast_meta_pass
+        c.fast_meta_pass, c.fast_base_pass, c.momentum = fast_meta_pass, fast_base_pass, momentum
         c.corr_hidden, c.corr_kappa = corr_hidden, corr_kappa
         c.aux_mlm, c.max_aux_batch, c.max_aux_masked = aux_mlm, max_aux_batch, max_aux_masked
         return c

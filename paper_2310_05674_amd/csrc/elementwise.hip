@@ -115,18 +115,22 @@ __global__ void k_step_scalars(int64_t* counters, int advance, float lr, float b
   step[2] = (float)((double)lr * c1 * c2); step[3] = (float)c2;
 }
 
-// SGD: theta' = theta - lr (g + wd theta)
-__global__ __launch_bounds__(EW_THREADS) void k_sgd(float* __restrict__ g, float* __restrict__ theta,
-                                                    bf16_t* __restrict__ theta16, int64_t n, int64_t n16, float lr,
-                                                    float wd) {
+// SGD: theta' = theta - lr b, b = mu b_prev + (g + wd theta) (heavy-ball momentum; b lives in `buf`, untouched when
+// mu = 0).  Also refreshes the bf16 working copy and its residual half over the first n16 elements.
+__global__ __launch_bounds__(EW_THREADS) void k_sgd(float* __restrict__ g, float* __restrict__ buf, float* __restrict__ theta,
+                                                    bf16_t* __restrict__ theta16, bf16_t* __restrict__ lo, int64_t n,
+                                                    int64_t n16, float lr, float wd, float mu) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += stride) {
     float t = theta[k];
     const float ge = fmaf(wd, t, g[k]);
     if (wd != 0.f) g[k] = ge;   // the gradient the solver was given
-    t = t - lr * ge;
+    float b = ge;
+    if (mu != 0.f) { b = fmaf(mu, buf[k], ge); buf[k] = b; }
+    t = t - lr * b;
     theta[k] = t;
     if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(t);
+    if (lo != nullptr && k < n16) lo[k] = f32_to_bf16(bf16_residual(t));
   }
 }
 
@@ -318,12 +322,13 @@ __global__ __launch_bounds__(EW_THREADS) void k_residual_lo(const float* __restr
   if (k < n16) lo[k] = f32_to_bf16(bf16_residual(theta[k]));
 }
 
-// theta <- theta - eps v (and the bf16 working copy).  eps = 0 (a skipped step) leaves everything as it is.
+// theta <- theta - eps v (and the bf16 working copy with its residual half).  eps = 0 or a raised status word (a
+// skipped step) leaves everything as it is.
 __global__ __launch_bounds__(EW_THREADS) void k_nudge(float* __restrict__ theta, const float* __restrict__ vdir,
-                                                      const float* __restrict__ eps_ptr, bf16_t* __restrict__ theta16,
-                                                      int64_t n, int64_t n16) {
+                                                      const float* __restrict__ eps_ptr, const int64_t* __restrict__ status,
+                                                      bf16_t* __restrict__ theta16, bf16_t* __restrict__ lo, int64_t n, int64_t n16) {
   const float eps = *eps_ptr;
-  if (eps == 0.f) return;
+  if (eps == 0.f || (status != nullptr && *status != 0)) return;
   const int64_t nv = n / EW_VEC, trip = (int64_t)gridDim.x * EW_TRIP;
   for (int64_t base = (int64_t)blockIdx.x * EW_TRIP + threadIdx.x; base < nv; base += trip) {
     f4 T[EW_U], V[EW_U];
@@ -341,6 +346,11 @@ __global__ __launch_bounds__(EW_THREADS) void k_nudge(float* __restrict__ theta,
         t.z = fmaf(-eps, V[u].z, T[u].z); t.w = fmaf(-eps, V[u].w, T[u].w);
         st_nt(theta, j, t);
         st_bf16_prefix(theta16, j, n16, t);
+        if (lo != nullptr) {
+          f4 r;
+          r.x = bf16_residual(t.x); r.y = bf16_residual(t.y); r.z = bf16_residual(t.z); r.w = bf16_residual(t.w);
+          st_bf16_prefix(lo, j, n16, r);
+        }
       }
     }
   }
@@ -349,6 +359,24 @@ __global__ __launch_bounds__(EW_THREADS) void k_nudge(float* __restrict__ theta,
     const float t = fmaf(-eps, vdir[k], theta[k]);
     theta[k] = t;
     if (theta16 != nullptr && k < n16) theta16[k] = f32_to_bf16(t);
+    if (lo != nullptr && k < n16) lo[k] = f32_to_bf16(bf16_residual(t));
+  }
+}
+
+// Takes back the nudge k_perturb_nudge applied to the first n16 elements when the step turned out to be skipped after
+// all (a non-finite hypergradient: status raised although eps > 0): theta <- theta + eps v, with the working copy and
+// its residual half.  Returns at once otherwise, which is the ordinary case.
+__global__ __launch_bounds__(EW_THREADS) void k_unnudge(float* __restrict__ theta, const float* __restrict__ vdir,
+                                                        const float* __restrict__ eps_ptr, const int64_t* __restrict__ status,
+                                                        bf16_t* __restrict__ theta16, bf16_t* __restrict__ lo, int64_t n16) {
+  const float eps = *eps_ptr;
+  if (*status == 0 || eps == 0.f) return;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < n16; k += stride) {
+    const float t = fmaf(eps, vdir[k], theta[k]);
+    theta[k] = t;
+    theta16[k] = f32_to_bf16(t);
+    lo[k] = f32_to_bf16(bf16_residual(t));
   }
 }
 
@@ -394,9 +422,10 @@ void launch_adam(hipStream_t st, float* g, float* m, float* v, float* theta, bf1
 void launch_step_scalars(hipStream_t st, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step) {
   k_step_scalars<<<1, 1, 0, st>>>(counters, advance, lr, beta1, beta2, step);
 }
-void launch_sgd(hipStream_t st, float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd) {
+void launch_sgd(hipStream_t st, float* g, float* buf, float* theta, bf16_t* theta16, bf16_t* lo, int64_t n, int64_t n16,
+                float lr, float wd, float mu) {
   if (n <= 0) return;
-  k_sgd<<<ew_grid(n), EW_THREADS, 0, st>>>(g, theta, theta16, n, n16, lr, wd);
+  k_sgd<<<ew_grid(n), EW_THREADS, 0, st>>>(g, buf, theta, theta16, lo, n, n16, lr, wd, mu);
 }
 void launch_adapt_norm(hipStream_t st, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
                        double* partial, int64_t n, const AdaptArgs& a, float alpha, float* scalars, int64_t* status) {
@@ -434,11 +463,16 @@ void launch_residual_lo(hipStream_t st, const float* theta, bf16_t* lo, int64_t 
   ProfScope ps(st, F_RESIDUAL, 6.0 * n16);
   k_residual_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, lo, n16);
 }
-void launch_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, int64_t n,
-                  int64_t n16) {
+void launch_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status,
+                  bf16_t* theta16, bf16_t* lo, int64_t n, int64_t n16) {
   if (n <= 0) return;
-  ProfScope ps(st, F_NUDGE, 12.0 * n + (theta16 ? 2.0 * n16 : 0.0));
-  k_nudge<<<ew_grid(n), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, theta16, n, n16);
+  ProfScope ps(st, F_NUDGE, 12.0 * n + (theta16 ? 2.0 * n16 : 0.0) + (lo ? 2.0 * n16 : 0.0));
+  k_nudge<<<ew_grid(n), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, status, theta16, lo, n, n16);
+}
+void launch_unnudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status,
+                    bf16_t* theta16, bf16_t* lo, int64_t n16) {
+  if (n16 <= 0) return;
+  k_unnudge<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, status, theta16, lo, n16);
 }
 void launch_fill_f32(hipStream_t st, float* p, float val, int64_t n) {
   if (n <= 0) return;

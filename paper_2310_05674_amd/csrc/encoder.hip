@@ -95,7 +95,7 @@ class EncoderModel : public Model {
     const int B = b.n, M = B * S_, R = nw * M;
     ParamView pv{w[0].theta, w[0].vdir, w[0].eps_ptr, w[0].sign, nw == 2 ? M : 0};
     LnFwdArgs e{};
-    e.x = nullptr; e.ids = (const int32_t*)b.x; e.ids_rows = M; e.S = S_; e.tok_off = tok_; e.pos_off = pos_; e.x_out = keep ? pre0_ : nullptr;
+    e.x = nullptr; e.ids = (const int32_t*)b.x; e.ids_rows = M; e.S = S_; e.V = V_; e.tok_off = tok_; e.pos_off = pos_; e.x_out = keep ? pre0_ : nullptr;
     e.pv = pv; e.g_off = eg_; e.b_off = eb_; e.y = X_[0]; e.y32 = res_[0]; e.mean = keep ? mean0_ : nullptr; e.rstd = keep ? rstd0_ : nullptr;
     e.M = R; e.d = d_;
     launch_ln_fwd(st, e);
@@ -291,7 +291,7 @@ class EncoderModel : public Model {
     launch_ln_bwd(st, n0);
     launch_reduce_rows(st, lnpart_[0][0], nblk, 3 * d_, d_, d_, grad + eg_, grad + eb_, nullptr);
     launch_fill_f32(st, grad + tok_, 0.f, (int64_t)V_ * d_);
-    launch_embedding_bwd(st, ds32_, (const int32_t*)b.x, B, S_, d_, grad + tok_, grad + pos_);
+    launch_embedding_bwd(st, ds32_, (const int32_t*)b.x, B, S_, d_, V_, grad + tok_, grad + pos_);
   }
 
   // second stream (default priority, created at the first backward pass) and the events that order it

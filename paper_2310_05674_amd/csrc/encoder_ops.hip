@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256) void k_ln_fwd(LnFwdArgs a) {
       if (a.x != nullptr) {
         xr[j] = reinterpret_cast<const float4*>(a.x + (int64_t)row * a.d)[q];
       } else {
-        const int64_t to = a.tok_off + (int64_t)a.ids[a.ids_rows > 0 ? row % a.ids_rows : row] * a.d + 4 * q, po = a.pos_off + (int64_t)(row % a.S) * a.d + 4 * q;
+        const int id = min(max(a.ids[a.ids_rows > 0 ? row % a.ids_rows : row], 0), a.V - 1);   // ids outside [0, V) are clamped
+        const int64_t to = a.tok_off + (int64_t)id * a.d + 4 * q, po = a.pos_off + (int64_t)(row % a.S) * a.d + 4 * q;
         float4 t = *reinterpret_cast<const float4*>(a.pv.theta + to), p = *reinterpret_cast<const float4*>(a.pv.theta + po);
         if (sc != 0.f) {
           const float4 tv = *reinterpret_cast<const float4*>(a.pv.vdir + to), pvv = *reinterpret_cast<const float4*>(a.pv.vdir + po);
@@ -564,15 +565,15 @@ __global__ __launch_bounds__(256) void k_pos_grad(const float* __restrict__ demb
 // One block per position m.  The block lists, in ascending order, every position holding the same token id;
 // only the block of the first occurrence goes on, and writes the ordered sum of those rows.
 __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb, const int32_t* __restrict__ ids, int M, int d,
-                                                  float* __restrict__ g_tok) {
+                                                  int V, float* __restrict__ g_tok) {
   __shared__ int s_list[MAX_TOKENS];
   __shared__ int s_cnt, s_wave[4];
-  const int m = blockIdx.x, id = ids[m], lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = blockIdx.x, id = min(max(ids[m], 0), V - 1), lane = threadIdx.x & 63, wave = threadIdx.x >> 6;   // clamped as in the forward pass
   if (threadIdx.x == 0) s_cnt = 0;
   __syncthreads();
   for (int base = 0; base < M; base += 256) {
     const int mm = base + threadIdx.x;
-    const bool hit = (mm < M) && (ids[mm] == id);
+    const bool hit = (mm < M) && (min(max(ids[mm], 0), V - 1) == id);
     const unsigned long long bal = __ballot(hit);
     if (lane == 0) s_wave[wave] = __popcll(bal);
     __syncthreads();
@@ -713,10 +714,10 @@ void launch_head_bwd(hipStream_t st, const float* x, int S, int d, int B, int C,
   k_head_bwd_w<<<(C * d + 255) / 256, 256, 0, st>>>(x, S, d, B, C, dlogits, grad + wc_off, grad + bc_off);
   k_head_bwd_x<<<(B * d + 255) / 256, 256, 0, st>>>(S, d, B, C, theta + wc_off, dlogits, dx);
 }
-void launch_embedding_bwd(hipStream_t st, const float* demb, const int32_t* ids, int B, int S, int d, float* g_tok, float* g_pos) {
+void launch_embedding_bwd(hipStream_t st, const float* demb, const int32_t* ids, int B, int S, int d, int V, float* g_tok, float* g_pos) {
   ProfScope ps(st, F_OTHER, 4.0 * B * S * d);
   k_pos_grad<<<(S * d + 255) / 256, 256, 0, st>>>(demb, B, S, d, g_pos);
-  k_tok_grad<<<B * S, 256, 0, st>>>(demb, ids, B * S, d, g_tok);
+  k_tok_grad<<<B * S, 256, 0, st>>>(demb, ids, B * S, d, V, g_tok);
 }
 
 }  // namespace sama

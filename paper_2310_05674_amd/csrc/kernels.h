@@ -59,7 +59,9 @@ void launch_step_scalars(hipStream_t, int64_t* counters, int advance, float lr, 
 // With a non-zero weight decay the L2 term is added to g in place (g then is the gradient the solver was given).
 void launch_adam(hipStream_t, float* g, float* m, float* v, float* theta, bf16_t* theta16, int64_t n, int64_t n16,
                  const AdamArgs&);
-void launch_sgd(hipStream_t, float* g, float* theta, bf16_t* theta16, int64_t n, int64_t n16, float lr, float wd);
+// SGD with heavy-ball momentum mu (velocity in buf, untouched when mu = 0); lo as in AdamArgs (may be null)
+void launch_sgd(hipStream_t, float* g, float* buf, float* theta, bf16_t* theta16, bf16_t* lo, int64_t n, int64_t n16, float lr,
+                float wd, float mu);
 // v = D . gmeta, then eps = alpha/||v|| -> scalars[0], ||v|| -> scalars[1], status[0] = (norm unusable)
 void launch_adapt_norm(hipStream_t, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
                        double* partial /*[EW_MAX_BLOCKS]*/, int64_t n, const AdaptArgs&, float alpha, float* scalars,
@@ -77,8 +79,13 @@ void launch_perturb_nudge(hipStream_t, float* theta, const float* vdir, const fl
                           bf16_t* lo_m, int64_t n16);
 // lo[k] = bf16(theta[k] - float(bf16(theta[k]))): the part of the master weights the bf16 working copy cannot hold
 void launch_residual_lo(hipStream_t, const float* theta, bf16_t* lo, int64_t n16);
-void launch_nudge(hipStream_t, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, int64_t n,
-                  int64_t n16);
+// theta <- theta - eps v; theta16 / lo (either may be null) receive the rounded copy and its residual half over the first
+// n16 elements; nothing happens when eps = 0 or *status != 0 (status may be null)
+void launch_nudge(hipStream_t, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status, bf16_t* theta16,
+                  bf16_t* lo, int64_t n, int64_t n16);
+// undoes launch_perturb_nudge's nudge of the first n16 elements when *status != 0 although eps > 0 (early exit otherwise)
+void launch_unnudge(hipStream_t, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status, bf16_t* theta16,
+                    bf16_t* lo, int64_t n16);
 void launch_fill_f32(hipStream_t, float* p, float val, int64_t n);
 void launch_copy_f32(hipStream_t, float* dst, const float* src, int64_t n);
 void launch_to_bf16(hipStream_t, bf16_t* dst, const float* src, int64_t n);
@@ -172,6 +179,7 @@ constexpr int COLSUM_ROWS = 16;      // rows per block in the column-sum kernel
 struct LnFwdArgs {
   const float* x;          // [M x d] input, or null: embedding mode (x = tok_emb[id] + pos_emb[m % S])
   const int32_t* ids; int S; int64_t tok_off, pos_off; float* x_out;  // embedding mode; x_out [M x d] may be null
+  int V;                   // embedding mode: vocabulary size, ids are clamped into [0, V)
   int ids_rows;            // embedding mode: row r reads ids[r % ids_rows] (0 = M; stacked passes share one id array)
   ParamView pv; int64_t g_off, b_off;                                 // gamma / beta inside theta
   bf16_t* y; float* y32; float* mean; float* rstd;                    // y32 (fp32 copy for the residual path), mean, rstd may be null
@@ -214,7 +222,8 @@ void launch_head_bwd(hipStream_t, const float* x, int S, int d, int B, int C, co
                      int64_t bc_off, const float* dlogits, float* grad, float* dx);
 // embedding gradients from demb [B*S x d]: pos_emb rows summed over the batch; tok_emb rows summed over the
 // occurrences of each id in ascending position order (the tok_emb part of grad must be zero on entry)
-void launch_embedding_bwd(hipStream_t, const float* demb, const int32_t* ids, int B, int S, int d, float* g_tok, float* g_pos);
+// (ids outside [0, V) are clamped into it, here and in the forward pass)
+void launch_embedding_bwd(hipStream_t, const float* demb, const int32_t* ids, int B, int S, int d, int V, float* g_tok, float* g_pos);
 
 
 // ------------------------------------------------------------------ masked-token head (mlm_head.hip)

@@ -133,7 +133,7 @@ sama_status sama_op_nudge(float* theta, const float* vdir, const float* eps_ptr,
   if (!theta || !vdir || !eps_ptr || n < 0 || n16 < 0 || n16 > n) return SAMA_EINVAL;
   if ((((uintptr_t)theta | (uintptr_t)vdir) & 15) || ((uintptr_t)theta16 & 7)) return SAMA_EINVAL;
   (void)hipGetLastError();
-  launch_nudge((hipStream_t)hip_stream, theta, vdir, eps_ptr, (bf16_t*)theta16, n, theta16 ? n16 : 0);
+  launch_nudge((hipStream_t)hip_stream, theta, vdir, eps_ptr, nullptr, (bf16_t*)theta16, nullptr, n, theta16 ? n16 : 0);
   return hipGetLastError() == hipSuccess ? SAMA_OK : SAMA_EHIP;
 }
 

@@ -66,7 +66,7 @@ struct sama_ctx {
   std::unique_ptr<Model> model;
   // device state (inside the caller's workspace)
   float *theta, *m, *v, *g, *gmeta, *vdir;
-  bf16_t *theta16, *lo_p, *lo_m;
+  bf16_t *theta16, *lo_0, *lo_p, *lo_m;   // bf16 working copy; residual half of the current theta; halves of theta +- eps v
   float *lambda, *meta_m, *meta_v, *hyper, *glam_p32, *glam_m32;
   double *glam_p, *glam_m, *partial, *corr_scratch;
   float* scalars;     // {eps, ||v||, L_base, L_meta}
@@ -77,7 +77,6 @@ struct sama_ctx {
   int32_t *ids_cat, *y_cat, *len_cat; uint8_t* mask_cat; float *loss_pos, *coef_pos;
   int64_t t;  // base step count (host)
   float lr_step = 0.f;           // base_lr of the last base step (a schedule may have moved cfg.base_lr since)
-  bool lo_is_residual = false;   // lo_p holds bf16(theta - bf16(theta)) of the current theta (written by the last Adam step)
   std::string err;
 };
 
@@ -110,6 +109,9 @@ static bool validate(const sama_config* c, std::string& err) {
   if (!(c->beta1 >= 0.f && c->beta1 < 1.f && c->beta2 >= 0.f && c->beta2 < 1.f && c->meta_beta1 >= 0.f &&
         c->meta_beta1 < 1.f && c->meta_beta2 >= 0.f && c->meta_beta2 < 1.f)) { err = "betas must be in [0, 1)"; return false; }
   if (c->fast_meta_pass != 0 && c->fast_meta_pass != 1) { err = "fast_meta_pass must be 0 or 1"; return false; }
+  if (c->fast_base_pass != 0 && c->fast_base_pass != 1) { err = "fast_base_pass must be 0 or 1"; return false; }
+  if (!(c->momentum >= 0.f && c->momentum < 1.f)) { err = "momentum must be in [0, 1)"; return false; }
+  if (c->momentum != 0.f && c->base_opt != SAMA_OPT_SGD) { err = "momentum belongs to the SGD base solver"; return false; }
   if (c->adam_eps < 0.f || c->meta_eps < 0.f || c->weight_decay < 0.f) { err = "negative eps / weight_decay"; return false; }
   if (c->corr_hidden < 0 || c->corr_hidden > MAX_CORR_HIDDEN) { err = "corr_hidden must be 0..128"; return false; }
   if (c->corr_hidden > 0 && c->dims[c->n_dims - 1] > MAX_CORR_CLASSES) { err = "label correction supports at most 16 classes"; return false; }
@@ -133,8 +135,8 @@ static size_t carve(sama_ctx* c, void* base) {
   const int nl = c->nl;
   c->theta = ws.take<float>(n); c->m = ws.take<float>(n); c->v = ws.take<float>(n);
   c->g = ws.take<float>(n); c->gmeta = ws.take<float>(n); c->vdir = ws.take<float>(n);
-  if (c->bf16) { c->theta16 = ws.take<bf16_t>(ng); c->lo_p = ws.take<bf16_t>(ng); c->lo_m = ws.take<bf16_t>(ng); }
-  else { c->theta16 = c->lo_p = c->lo_m = nullptr; }
+  if (c->bf16) { c->theta16 = ws.take<bf16_t>(ng); c->lo_0 = ws.take<bf16_t>(ng); c->lo_p = ws.take<bf16_t>(ng); c->lo_m = ws.take<bf16_t>(ng); }
+  else { c->theta16 = c->lo_0 = c->lo_p = c->lo_m = nullptr; }
   c->lambda = ws.take<float>(nl); c->meta_m = ws.take<float>(nl); c->meta_v = ws.take<float>(nl);
   c->hyper = ws.take<float>(nl); c->glam_p32 = ws.take<float>(nl); c->glam_m32 = ws.take<float>(nl);
   c->glam_p = ws.take<double>(nl); c->glam_m = ws.take<double>(nl);
@@ -196,6 +198,7 @@ static void base_update_range(sama_ctx* c, hipStream_t st, int64_t t, int64_t of
   const sama_config& f = c->cfg;
   const int64_t n16 = off < c->n_gemm ? (off + count <= c->n_gemm ? count : c->n_gemm - off) : 0;   // leading part with a bf16 copy
   bf16_t* t16 = (c->theta16 != nullptr && n16 > 0) ? c->theta16 + off : nullptr;
+  bf16_t* lo0 = t16 != nullptr ? c->lo_0 + off : nullptr;   // every pass that writes theta keeps its residual half current
   if (f.base_opt == SAMA_OPT_ADAM) {
     AdamArgs a{};
     a.beta1 = f.beta1; a.one_m_beta1 = (float)(1.0 - (double)f.beta1);
@@ -204,11 +207,10 @@ static void base_update_range(sama_ctx* c, hipStream_t st, int64_t t, int64_t of
     a.c2 = (float)(1.0 / sqrt(1.0 - pow((double)f.beta2, (double)t)));
     a.eps = f.adam_eps; a.weight_decay = f.weight_decay;
     a.dev = c->step;   // the device's own step count decides (the host values above are what it holds in eager use)
-    // the residual half the next direct-gradient pass contracts with comes out of the same pass over theta
-    a.lo = (t16 != nullptr && !f.fast_meta_pass) ? c->lo_p + off : nullptr;
+    a.lo = lo0;
     launch_adam(st, c->g + off, c->m + off, c->v + off, c->theta + off, t16, count, n16, a);
   } else {
-    launch_sgd(st, c->g + off, c->theta + off, t16, count, n16, f.base_lr, f.weight_decay);
+    launch_sgd(st, c->g + off, c->m + off, c->theta + off, t16, lo0, count, n16, f.base_lr, f.weight_decay, f.momentum);
   }
 }
 
@@ -236,7 +238,6 @@ static void base_update_rest(sama_ctx* c, UpdateSink& sink) {
   if (pos < c->n) base_update_range(c, st, sink.t, pos, c->n - pos);
   c->t = sink.t;   // the device's counter was advanced by launch_step_scalars at the start of the step
   c->lr_step = c->cfg.base_lr;
-  c->lo_is_residual = c->bf16 && c->cfg.base_opt == SAMA_OPT_ADAM && !c->cfg.fast_meta_pass;
 }
 
 // v = D . g_meta and the partial sums of ||v||^2 for the ranges of g_meta the model reports final during its backward
@@ -321,20 +322,24 @@ sama_status sama_init(const sama_config* cfg, void* workspace, size_t workspace_
   launch_fill_f32(st, c->scalars, 0.f, 4);
   launch_fill_f32(st, c->step, 0.f, 8);
   launch_fill_i64x4(st, c->counters, 0, 0, 0, 0, 15);
-  if (c->bf16) launch_to_bf16(st, c->theta16, c->theta, c->n_gemm);
+  if (c->bf16) { launch_to_bf16(st, c->theta16, c->theta, c->n_gemm); launch_residual_lo(st, c->theta, c->lo_0, c->n_gemm); }
   sama_status s = check_hip(nullptr, "sama_init");
   if (s != SAMA_OK) return s;
   *out = c.release();
   return SAMA_OK;
 }
 
-static PassWeights pass_weights(sama_ctx* c, float sign) {
+// How a pass sees theta: sign = 0 with lo = null contracts with the bf16 working copy alone, with lo = lo_0 (the
+// residual half) at theta itself; sign = +-1 with the matching half of theta +- eps v.
+static PassWeights pass_weights(sama_ctx* c, float sign, const bf16_t* lo) {
   PassWeights w{};
   w.theta = c->theta; w.vdir = c->vdir; w.eps_ptr = c->scalars; w.sign = sign;
   w.hi = c->theta16;
-  w.lo = sign > 0.f ? c->lo_p : (sign < 0.f ? c->lo_m : nullptr);
+  w.lo = lo;
   return w;
 }
+// the base step's (and the forward-only evaluation's) view
+static PassWeights base_weights(sama_ctx* c) { return pass_weights(c, 0.f, (c->bf16 && !c->cfg.fast_base_pass) ? c->lo_0 : nullptr); }
 
 sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out) {
   if (!c) return SAMA_EINVAL;
@@ -343,7 +348,7 @@ sama_status sama_base_step(sama_ctx* c, const sama_batch* train, float* loss_out
   hipStream_t st = c->stream;
   (void)hipGetLastError();
   launch_step_scalars(st, c->counters, 1, c->cfg.base_lr, c->cfg.beta1, c->cfg.beta2, c->step);
-  const PassWeights w = pass_weights(c, 0.f);
+  const PassWeights w = base_weights(c);
   c->model->forward(st, w, *train, true, c->logits);
   SampleStageArgs sa{};
   sa.logits = c->logits; sa.ld = c->model->n_classes(); sa.C = sa.ld; sa.B = train->n; sa.H = c->cfg.wnet_hidden;
@@ -365,7 +370,7 @@ sama_status sama_eval(sama_ctx* c, const sama_batch* batch, float* logits_out, f
   if (s != SAMA_OK) return s;
   hipStream_t st = c->stream;
   (void)hipGetLastError();
-  const PassWeights w = pass_weights(c, 0.f);
+  const PassWeights w = base_weights(c);
   float* logits = logits_out != nullptr ? logits_out : c->logits;
   c->model->forward(st, w, *batch, false, logits);
   if (losses_out != nullptr || weights_out != nullptr) {
@@ -385,16 +390,8 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
   hipStream_t st = c->stream;
   const sama_config& f = c->cfg;
   const int C = c->model->n_classes();
-  PassWeights w0 = pass_weights(c, 0.f);
-  if (c->bf16 && !f.fast_meta_pass) {   // hi + lo of the master weights: the gradient is taken at theta, not bf16(theta)
-    // The last Adam step left the residual half in lo_p unless something changed theta or lo_p since (a meta pass, a
-    // state upload).  A stream capture always takes the pass of its own, so that a captured call stands by itself.
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    const bool capturing = hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
-    if (!c->lo_is_residual || capturing) launch_residual_lo(st, c->theta, c->lo_p, c->n_gemm);
-    w0.lo = c->lo_p;
-  }
-  c->lo_is_residual = false;   // the +- halves overwrite lo_p, an applied step moves theta
+  // hi + lo of the master weights: the gradient is taken at theta, not bf16(theta)
+  const PassWeights w0 = pass_weights(c, 0.f, (c->bf16 && !f.fast_meta_pass) ? c->lo_0 : nullptr);
   c->model->forward(st, w0, *meta, true, c->logits);
   SampleStageArgs sa{};
   sa.logits = c->logits; sa.ld = C; sa.C = C; sa.B = meta->n; sa.H = f.wnet_hidden; sa.mode = STAGE_META;
@@ -429,7 +426,8 @@ static bool meta_direction(sama_ctx* c, const sama_batch* meta, bool update) {
   // A step that is applied nudges the GEMM block of theta in the same pass that writes the low halves; the non-GEMM
   // tail is nudged after the two passes, which read it as theta +- eps v.
   const bool fused_nudge = update && c->bf16 && c->n_gemm % 4 == 0;
-  if (fused_nudge) launch_perturb_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->lo_p, c->lo_m, c->n_gemm);
+  // (the low half of theta_old - eps v against the new working copy IS the residual half of the new theta: lo_0)
+  if (fused_nudge) launch_perturb_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->lo_p, c->lo_0, c->n_gemm);
   else if (c->bf16) launch_perturb_lo(st, c->theta, c->vdir, c->scalars, c->lo_p, c->lo_m, c->n_gemm);
   return fused_nudge;
 }
@@ -445,8 +443,14 @@ static void meta_finish(sama_ctx* c, float* hyper_out, float* eps_out, bool upda
   mu.lambda = c->lambda; mu.meta_m = c->meta_m; mu.meta_v = c->meta_v; mu.nl = c->nl; mu.do_update = update ? 1 : 0;
   mu.lr = f.meta_lr; mu.beta1 = f.meta_beta1; mu.beta2 = f.meta_beta2; mu.eps = f.meta_eps;
   launch_meta_update(st, mu);
-  if (update && fused_nudge) launch_nudge(st, c->theta + c->n_gemm, c->vdir + c->n_gemm, c->scalars, nullptr, c->n - c->n_gemm, 0);
-  else if (update) launch_nudge(st, c->theta, c->vdir, c->scalars, c->theta16, c->n, c->n_gemm);
+  // a hypergradient that is not finite skips the step (status word): the tail is then left alone and the GEMM block's
+  // early nudge is taken back
+  if (update && fused_nudge) {
+    launch_unnudge(st, c->theta, c->vdir, c->scalars, c->counters + 2, c->theta16, c->lo_0, c->n_gemm);
+    launch_nudge(st, c->theta + c->n_gemm, c->vdir + c->n_gemm, c->scalars, c->counters + 2, nullptr, nullptr, c->n - c->n_gemm, 0);
+  } else if (update) {
+    launch_nudge(st, c->theta, c->vdir, c->scalars, c->counters + 2, c->theta16, c->lo_0, c->n, c->n_gemm);
+  }
 }
 
 static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_batch* meta, float* hyper_out,
@@ -463,7 +467,7 @@ static sama_status meta_common(sama_ctx* c, const sama_batch* train, const sama_
   const int C = c->model->n_classes();
   const bool fused_nudge = meta_direction(c, meta, update);
   // passes 2 and 3: dL_base/dlambda at theta +- eps v; forward only, then the weight net's backward
-  c->model->forward_pair(st, pass_weights(c, 1.f), pass_weights(c, -1.f), *train, c->logits);
+  c->model->forward_pair(st, pass_weights(c, 1.f, c->lo_p), pass_weights(c, -1.f, fused_nudge ? c->lo_0 : c->lo_m), *train, c->logits);
   for (int pass = 0; pass < 2; ++pass) {
     SampleStageArgs sg{};
     sg.logits = c->logits + (size_t)pass * train->n * C; sg.ld = C; sg.C = C; sg.B = train->n; sg.H = f.wnet_hidden; sg.mode = STAGE_GLAM;
@@ -510,7 +514,7 @@ sama_status sama_aux_base_step(sama_ctx* c, const sama_batch* ft, const sama_aux
   launch_aux_cat(st, (const int32_t*)ft->x, ft->y, ft->sample_mask, n_ft, pt->ids, n_pt, S, c->ids_cat, c->y_cat, c->mask_cat,
                  ft->seq_len, pt->seq_len, padded ? c->len_cat : nullptr);
   const sama_batch cat{c->ids_cat, c->y_cat, c->mask_cat, n_ft + n_pt, padded ? c->len_cat : nullptr};
-  const PassWeights w = pass_weights(c, 0.f);
+  const PassWeights w = base_weights(c);
   c->model->forward(st, w, cat, true, c->logits);
   // finetuning term: mean cross-entropy over the ft rows (the auxiliary rows are masked out of the classifier loss)
   SampleStageArgs sa{};
@@ -538,7 +542,7 @@ sama_status sama_aux_eval(sama_ctx* c, const sama_aux_batch* pt, float* losses_o
   (void)hipGetLastError();
   const int S = c->cfg.dims[4];
   const sama_batch ptb{pt->ids, nullptr, nullptr, pt->n_seq, pt->seq_len};
-  const PassWeights w = pass_weights(c, 0.f);
+  const PassWeights w = base_weights(c);
   c->model->forward(st, w, ptb, true, c->logits);        // the head reads the kept last hidden state
   const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, 0, pt->n_seq * S};
   c->model->mlm_forward(st, &w, 1, pt->n_seq * S, true, mb, c->loss_pos);
@@ -564,7 +568,7 @@ static sama_status aux_meta_common(sama_ctx* c, const sama_aux_batch* pt, const 
   const bool fused_nudge = meta_direction(c, meta, update);
   // passes 2 and 3 on the auxiliary sequences alone: the finetuning term of L_base does not depend on lambda
   const sama_batch ptb{pt->ids, nullptr, nullptr, pt->n_seq, pt->seq_len};
-  const PassWeights w[2] = {pass_weights(c, 1.f), pass_weights(c, -1.f)};
+  const PassWeights w[2] = {pass_weights(c, 1.f, c->lo_p), pass_weights(c, -1.f, fused_nudge ? c->lo_0 : c->lo_m)};
   c->model->forward_pair(st, w[0], w[1], ptb, c->logits);
   const MlmBatch mb{pt->mask_row, pt->mask_tgt, pt->n_mask, 0, pt->n_seq * S};
   c->model->mlm_forward(st, w, 2, pt->n_seq * S, false, mb, c->loss_pos);
@@ -634,8 +638,10 @@ sama_status sama_set_state(sama_ctx* c, int32_t which, const void* src) {
   if (!wr) return fail(c, SAMA_EINVAL, "state selector is read-only");
   if (hipMemcpyAsync(p, src, bytes, hipMemcpyDeviceToDevice, c->stream) != hipSuccess)
     return fail(c, SAMA_EHIP, "sama_set_state: copy failed");
-  if (which == SAMA_STATE_THETA && c->bf16) launch_to_bf16(c->stream, c->theta16, c->theta, c->n_gemm);
-  if (which == SAMA_STATE_THETA) c->lo_is_residual = false;
+  if (which == SAMA_STATE_THETA && c->bf16) {
+    launch_to_bf16(c->stream, c->theta16, c->theta, c->n_gemm);
+    launch_residual_lo(c->stream, c->theta, c->lo_0, c->n_gemm);
+  }
   if (which == SAMA_STATE_COUNTERS) {
     int64_t host[4];
     if (hipMemcpyAsync(host, c->counters, 32, hipMemcpyDeviceToHost, c->stream) != hipSuccess ||

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
     double se = 0.0;
     for (int c = 0; c < C; ++c) se += exp((double)z[c] - zmax);
     const double lse = log(se) + zmax;
-    const int yi = a.y[i];
+    const int yi = min(max(a.y[i], 0), C - 1);   // labels outside [0, C) are clamped
     const double mk = (a.mask == nullptr || a.mask[i] != 0) ? 1.0 : 0.0;
     double l;
     double cs[MAX_CORR_CLASSES];                       // corrected soft label (Hc > 0)
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
     for (int i = 0; i < B; ++i) {
       const double* ds = a.corr_scratch + (int64_t)i * 2 * C;
       const double* p = ds + C;
-      const int yi = a.y[i];
+      const int yi = min(max(a.y[i], 0), C - 1);   // labels outside [0, C) are clamped
       double aj = (double)b1c[j] + (double)W1c[j * 2 * C + yi];
       for (int k = 0; k < C; ++k) aj += (double)W1c[j * 2 * C + C + k] * p[k];
       if (aj > 0.0) {
@@ -217,11 +217,21 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
   }
 }
 
-// h = -(glam+ - glam-) / (2 eps); then (optionally) Adam on lambda.  A raised status word (counters[2]) zeroes h
-// and skips the update.
+// h = -(glam+ - glam-) / (2 eps); then (optionally) Adam on lambda.  A raised status word (counters[2]) or a
+// hypergradient with a non-finite component zeroes h and skips the update; the latter raises the status word itself.
 __global__ __launch_bounds__(256) void k_meta_update(MetaUpdateArgs a) {
   const float eps = a.scalars[0];
-  const bool skip = (a.counters[2] != 0) || !(eps > 0.f);
+  bool skip = (a.counters[2] != 0) || !(eps > 0.f);
+  int bad = 0;
+  if (!skip)
+    for (int i = threadIdx.x; i < a.nl; i += 256) {
+      const double h = -(a.glam_p[i] - a.glam_m[i]) / (2.0 * (double)eps);
+      if (!(fabs(h) <= 3.0e38)) bad = 1;   // NaN, infinite, or beyond what the fp32 outputs hold
+    }
+  if (__syncthreads_or(bad)) {   // every thread has read counters[2] above
+    skip = true;
+    if (threadIdx.x == 0) a.counters[2] = 1;
+  }
   const int64_t t = a.counters[1] + 1;
   const double c1 = 1.0 / (1.0 - pow((double)a.beta1, (double)t));
   const double c2 = 1.0 / sqrt(1.0 - pow((double)a.beta2, (double)t));

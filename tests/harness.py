@@ -17,15 +17,16 @@ def make_pair(wl, theta0, lambda0, **over):
     from oracle.reweight import SamaOracle, ADAM, SGD
     kw = dict(base_lr=wl.base_lr, meta_lr=wl.meta_lr, alpha=wl.alpha, beta1=wl.beta1, beta2=wl.beta2,
               adam_eps=wl.adam_eps)
-    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps", "weight_decay")})
+    kw.update({k: v for k, v in over.items() if k in ("base_lr", "meta_lr", "alpha", "adam_eps", "weight_decay", "momentum")})
     base_opt = over.get("base_opt", "adam")
     adapt = over.get("adapt_mode", 0)
     corr = {k: over[k] for k in ("corr_hidden", "corr_kappa") if k in over}
+    gpu_only = {k: over[k] for k in ("fast_base_pass", "fast_meta_pass") if k in over}   # precision switches of the HIP path
     orc = SamaOracle(models.make_model(wl.kind, wl.dims), theta0, lambda0, base_opt=ADAM if base_opt == "adam" else SGD,
                      adapt_mode=adapt, n_classes=wl.dims[-1] if corr.get("corr_hidden") else None, **corr, **kw)
     cfg = pkg.SamaConfig.make(wl.kind, wl.dims, H=wl.H, max_batch=over.get("max_batch", wl.batch),
                               max_meta_batch=over.get("max_meta_batch", wl.meta_batch),
-                              base_opt=pkg.OPT_ADAM if base_opt == "adam" else pkg.OPT_SGD, adapt_mode=adapt, **corr, **kw)
+                              base_opt=pkg.OPT_ADAM if base_opt == "adam" else pkg.OPT_SGD, adapt_mode=adapt, **corr, **gpu_only, **kw)
     gpu = pkg.Sama(cfg, theta0, lambda0)
     return orc, gpu
 

@@ -1,6 +1,8 @@
 """GPU parity, bf16 encoder workloads: the HIP path through the C ABI against the float64 oracle on the same
-seeded inputs, teacher-forced from the oracle's state.  Bar: relative L2 <= 2e-2 on the hypergradient and the
-updated theta / lambda (bf16 GEMM operands, fp32 accumulation and state)."""
+seeded inputs, from the oracle's unrounded state (teacher-forced) and free-running.  Bar: relative L2 <= 2e-2 on the
+hypergradient and the updated theta / lambda (bf16 GEMM operands, fp32 accumulation and state).  Nothing in this file
+rounds the oracle's state to what the kernels can hold, except the one test of the mixed-precision switch
+(fast_base_pass = 1), which says so."""
 import numpy as np
 import pytest
 from datagen import make_workload, init_theta, init_lambda, round_to_bf16, seq_lengths
@@ -11,15 +13,11 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 SMALL = dict(dims=(2, 192, 3, 320, 128, 600, 3), batch=5, meta_batch=3)      # ragged N tiles, odd batch sizes
-KTOL = 1e-2     # kernel-arithmetic bar of the small-shape tests (GEMM weights snapped to bf16 on both sides)
+KTOL = 1e-2     # bar of the small-shape tests on single gradients: ~10 bf16 roundings (2^-9) of GEMM inputs per layer
 
 
-def _snap(orc):
-    """Make the oracle's GEMM weight block bf16-representable before the compared step, so that the small-shape
-    tests measure the kernels' arithmetic and not the rounding of the working weights (the full-size workload
-    tests below keep the unrounded state)."""
-    ng = sum(int(np.prod(sh)) for nm, (o, sh) in orc.model.slices.items() if nm.split(".")[-1] in ("Wqkv", "Wo", "W1", "W2"))
-    orc.theta[:ng] = round_to_bf16(orc.theta[:ng])
+def _gemm_block(orc):
+    return sum(int(np.prod(sh)) for nm, (o, sh) in orc.model.slices.items() if nm.split(".")[-1] in ("Wqkv", "Wo", "W1", "W2"))
 
 
 def _batches(wl, step):
@@ -41,7 +39,6 @@ def test_small_encoder_base_step(scale):
     orc, gpu = make_pair(wl, init_theta(wl, scale), init_lambda(wl), base_lr=1e-3)
     for s in range(2):
         (x, y), _ = _batches(wl, s)
-        _snap(orc)
         push_state(orc, gpu)
         th_before = orc.theta.copy()
         l_before = orc.model.losses(orc.theta, x, y)
@@ -76,7 +73,6 @@ def test_small_encoder_meta_step(scale):
     for s in range(3, 5):
         (x, y), (xm, ym) = _batches(wl, s)
         orc.base_step(x, y)
-        _snap(orc)
         push_state(orc, gpu)
         tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
         r = orc.meta_step(x, y, xm, ym)
@@ -89,8 +85,9 @@ def test_small_encoder_meta_step(scale):
         print(f"scale {scale} step {s}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()))
         assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["eps"] < KTOL and e["v"] < TOL
         # at scale 0.08 / lr 1e-3 the map v -> h is ill-conditioned (a 1e-2 change of v moves h by 4e-2 in exact
-        # arithmetic as well), so only the representative scale carries the hypergradient bar
-        assert e["h"] < (TOL if scale == 0.02 else 1e-1), e
+        # arithmetic as well), so there h is printed, not asserted: its inputs (g_meta, v, eps, g_lambda^+) carry the bars
+        if scale == 0.02:
+            assert e["h"] < TOL, e
         assert e["theta"] < TOL and e["lam"] < TOL
         assert int(pull(gpu, "COUNTERS")[2]) == 0
     gpu.close()
@@ -107,7 +104,6 @@ def test_meta_grad_is_pure_and_matches_meta_step():
         (x, y), _ = _batches(wl, s)
         orc.base_step(x, y)
     (x, y), (xm, ym) = _batches(wl, 4)
-    _snap(orc)
     push_state(orc, gpu)
     tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
     before = {k: pull(gpu, k).copy() for k in ("THETA", "LAMBDA", "M", "V", "META_M", "META_V")}
@@ -134,52 +130,175 @@ def test_meta_grad_is_pure_and_matches_meta_step():
 
 
 # ------------------------------------------------------------------------------------------ full workloads 3-5
-def _full_workload_parity(cfg, n_train, n_meta):
-    """Real shapes and hyper-parameters of workload `cfg`.  Base step 0 starts from the bf16-representable
-    initial theta on both sides, so its gradient is compared at the kernel-arithmetic bar; then one more oracle
-    base step (history for the adaptation), its state is pushed to the GPU, and one meta step is compared at the
-    end-to-end bar of 2e-2 with nothing snapped."""
+_RUNS = {}
+
+
+def _run_workload(cfg, n_train, n_meta):
+    """Real shapes and hyper-parameters of workload `cfg`, nothing rounded anywhere; one run per workload serves the
+    tests below (the oracle takes a minute on workload 5).
+      a. base step 0 from the initial theta on both sides: the gradient of one pass;
+      b. one more oracle base step (history for the adaptation), its state pushed, one meta step (teacher-forced);
+      c. the oracle's state after that meta step -- a general point: fp32 master weights off the bf16 grid after two
+         Adam steps and a nudge -- pushed once, then ONE WHOLE ITERATION on each side from its own state: base step
+         (gradient compared), then the meta step with the GPU's own g, m', v' in the adaptation of Eq. 4."""
+    if cfg in _RUNS:
+        return _RUNS[cfg]
     import time
     t0 = time.time()
     wl = make_workload(cfg, n_train=n_train, n_meta=n_meta)
     orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    out = {}
     (x, y), _ = _batches(wl, 0)
     orc.base_step(x, y)
     gpu.base_step(dev_batch(gpu, x, y))
     g = pull(gpu, "G")
-    eg = rel_l2(g, orc.g)
     errs = _group_errors(orc, g, orc.g)
     worst = max(errs, key=errs.get)
-    print(f"cfg {cfg}: base step 0 rel-L2 g {eg:.3e}, worst group {worst} {errs[worst]:.1e}  [{time.time() - t0:.0f}s]", flush=True)
-    assert eg < KTOL and errs[worst] < 3e-2, (eg, worst, errs[worst])
-    assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+    out["a"] = dict(g=rel_l2(g, orc.g), worst=errs[worst], theta=rel_l2(pull(gpu, "THETA"), orc.theta))
+    print(f"cfg {cfg} a: base step 0 rel-L2 g {out['a']['g']:.3e}, worst group {worst} {errs[worst]:.1e}  [{time.time() - t0:.0f}s]", flush=True)
+
+    def meta_errors(r):
+        e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+                 eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+                 theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+        e["fd_signal"] = np.linalg.norm(r["glam_p"] - r["glam_m"]) / np.linalg.norm(r["glam_p"])
+        e["glam_p"] = rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"])
+        e["status"] = int(pull(gpu, "COUNTERS")[2])
+        return e
+
     (x, y), (xm, ym) = _batches(wl, 1)
     orc.base_step(x, y)
     push_state(orc, gpu)
+    r = orc.meta_step(x, y, xm, ym)
+    gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
+    out["b"] = meta_errors(r)
+    print(f"cfg {cfg} b: " + " ".join(f"{k}={v:.2e}" for k, v in out["b"].items()) + f"  [{time.time() - t0:.0f}s]", flush=True)
+
+    push_state(orc, gpu)
+    ng = _gemm_block(orc)
+    out["off_grid"] = float(np.mean(round_to_bf16(orc.theta[:ng]) != orc.theta[:ng]))
+    (x, y), (xm, ym) = _batches(wl, 2)
     tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
+    th_before = orc.theta.copy()
+    orc.base_step(x, y)
+    gpu.base_step(tb)
+    g = pull(gpu, "G")
+    errs = _group_errors(orc, g, orc.g)
+    worst = max(errs, key=errs.get)
+    out["c_base"] = dict(g=rel_l2(g, orc.g), worst=errs[worst], theta=rel_l2(pull(gpu, "THETA"), orc.theta),
+                         step=rel_l2(pull(gpu, "THETA").astype(np.float64) - th_before, orc.theta - th_before),
+                         m=rel_l2(pull(gpu, "M"), orc.m), v=rel_l2(pull(gpu, "V"), orc.v))
+    print(f"cfg {cfg} c: off-grid weights {out['off_grid']:.2f}; base step rel-L2 g {out['c_base']['g']:.3e} worst group {worst} "
+          f"{errs[worst]:.1e} update {out['c_base']['step']:.2e}  [{time.time() - t0:.0f}s]", flush=True)
     r = orc.meta_step(x, y, xm, ym)
     gpu.meta_step(tb, mb)
-    e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
-             eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
-             theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
-    e["fd_signal"] = np.linalg.norm(r["glam_p"] - r["glam_m"]) / np.linalg.norm(r["glam_p"])
-    e["glam_p"] = rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"])
-    print(f"cfg {cfg}: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()) + f"  [{time.time() - t0:.0f}s]", flush=True)
-    assert e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL and e["eps"] < TOL and e["gmeta"] < TOL and e["v"] < TOL, e
-    assert int(pull(gpu, "COUNTERS")[2]) == 0
+    out["c_meta"] = meta_errors(r)
+    print(f"cfg {cfg} c: " + " ".join(f"{k}={v:.2e}" for k, v in out["c_meta"].items()) + f"  [{time.time() - t0:.0f}s]", flush=True)
     gpu.close()
+    _RUNS[cfg] = out
+    return out
 
 
-def test_workload3_parity():
-    _full_workload_parity(3, 128, 64)
+SIZES = {3: (128, 64), 4: (96, 64), 5: (48, 32)}
 
 
-def test_workload4_parity():
-    _full_workload_parity(4, 64, 32)
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_workload_parity(cfg):
+    """Steps a and b of _run_workload: the gradient of the first base step, and a teacher-forced meta step."""
+    o = _run_workload(cfg, *SIZES[cfg])
+    assert o["a"]["g"] < KTOL and o["a"]["worst"] < 3e-2 and o["a"]["theta"] < TOL, o["a"]
+    e = o["b"]
+    assert e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL and e["eps"] < TOL and e["gmeta"] < TOL and e["v"] < TOL, e
+    assert e["status"] == 0
 
 
-def test_workload5_parity():
-    _full_workload_parity(5, 32, 16)
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_workload_iteration_from_general_state(cfg):
+    """Step c of _run_workload: one whole iteration (sama_base_step, then sama_meta_step with the GPU's own gradient and
+    moments) from master weights that are NOT bf16-representable, against the oracle doing the same two calls."""
+    o = _run_workload(cfg, *SIZES[cfg])
+    assert o["off_grid"] > 0.5, o["off_grid"]            # the state really is a general one
+    b = o["c_base"]
+    assert b["g"] < TOL and b["worst"] < 5e-2 and b["theta"] < TOL and b["step"] < TOL and b["m"] < TOL and b["v"] < TOL, b
+    e = o["c_meta"]
+    assert e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL and e["eps"] < TOL and e["gmeta"] < TOL and e["v"] < TOL, e
+    assert e["status"] == 0
+
+
+def test_mixed_precision_switch_sees_the_rounded_weights():
+    """fast_base_pass = 1 is ordinary mixed precision: the base step differentiates at bf16(theta).  From a
+    bf16-representable theta it agrees with the default (split) pass and with the oracle; from a general state its
+    gradient equals the oracle's gradient AT THE ROUNDED WEIGHTS (the only place in this file where oracle weights are
+    rounded, to state what the switch computes), while the default pass follows the oracle at theta itself."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    th0 = init_theta(wl, 0.02)
+    orc, fast = make_pair(wl, th0, init_lambda(wl), base_lr=1e-3, fast_base_pass=1)
+    _, split = make_pair(wl, th0, init_lambda(wl), base_lr=1e-3)
+    for s in range(3):
+        (x, y), _ = _batches(wl, s)
+        orc.base_step(x, y)
+    (x, y), _ = _batches(wl, 3)
+    push_state(orc, fast); push_state(orc, split)
+    ng = _gemm_block(orc)
+    th_r = orc.theta.copy(); th_r[:ng] = round_to_bf16(th_r[:ng])
+    target = orc.targets(th_r, x, y)
+    l = orc.model.losses(th_r, x, target)
+    from oracle import wnet
+    coef = wnet.weights(l, orc.lam) / len(y)
+    _, g_rounded = orc.model.loss_grad(th_r, x, target, coef)
+    orc.base_step(x, y)
+    tb = dev_batch(fast, x, y)
+    fast.base_step(tb); split.base_step(dev_batch(split, x, y))
+    e_fast_r, e_fast, e_split = rel_l2(pull(fast, "G"), g_rounded), rel_l2(pull(fast, "G"), orc.g), rel_l2(pull(split, "G"), orc.g)
+    print(f"fast vs oracle at bf16(theta) {e_fast_r:.2e}; fast vs oracle at theta {e_fast:.2e}; split vs oracle at theta {e_split:.2e}")
+    assert e_fast_r < KTOL and e_split < KTOL
+    fast.close(); split.close()
+
+
+# ------------------------------------------------------------------------------------------ unroll > 1
+@pytest.mark.parametrize("where", ["small", "workload3"])
+def test_unrolled_iteration_free_running(where):
+    """Unroll U = 3 (the paper runs U = 10, App. B): three free-running base steps and one meta step on each side from the
+    same start, no state pushed in between; a second iteration follows on the small encoder.
+
+    Asserted at the bars of this file: every base step's gradient, moments and weights, the direct gradient, and the
+    quantities the parity target names -- hypergradient, theta, lambda.  The perturbation vector v and the step size
+    eps are printed only: free-running from zero moments they are ill-conditioned in the method itself.  The adaptation
+    of Eq. 4 (App. C) vanishes identically at t = 1, cancels to a tenth of its terms at t = 2, 3, and peaks at
+    lr c1 (1 - beta1) / (4 eps_A) for entries with c2 sqrt(v') near eps_A = 1e-8 (pinned in closed form in
+    tests/test_oracle_optim.py), i.e. on the few entries whose gradient history is far below the rounding noise of any
+    finite-precision pass; in the float64 oracle itself a relative gradient noise of 1e-3 moves v by more than its norm
+    there.  The small encoder therefore runs with eps_A = 1e-5, where that peak is a thousand times lower."""
+    if where == "small":
+        wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+        orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3, adam_eps=1e-5)
+        iters = 2
+    else:
+        wl = make_workload(3, n_train=128, n_meta=64)
+        orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+        iters = 1
+    k = 0
+    for it in range(iters):
+        for u in range(3):
+            (x, y), (xm, ym) = _batches(wl, k); k += 1
+            tb = dev_batch(gpu, x, y)
+            orc.base_step(x, y); gpu.base_step(tb)
+            e = dict(g=rel_l2(pull(gpu, "G"), orc.g), theta=rel_l2(pull(gpu, "THETA"), orc.theta),
+                     m=rel_l2(pull(gpu, "M"), orc.m), v=rel_l2(pull(gpu, "V"), orc.v))
+            print(f"{where} it {it} base step {u}: " + " ".join(f"{kk}={vv:.2e}" for kk, vv in e.items()))
+            assert e["g"] < KTOL and e["theta"] < TOL and e["m"] < KTOL and e["v"] < KTOL, e
+        r = orc.meta_step(x, y, xm, ym)
+        gpu.meta_step(tb, dev_batch(gpu, xm, ym))
+        e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), v=rel_l2(pull(gpu, "VDIR"), r["v"]),
+                 eps=abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"], h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
+                 theta=rel_l2(pull(gpu, "THETA"), orc.theta), lam=rel_l2(pull(gpu, "LAMBDA"), orc.lam))
+        print(f"{where} it {it} meta step: " + " ".join(f"{kk}={vv:.2e}" for kk, vv in e.items()))
+        assert e["gmeta"] < KTOL and e["h"] < TOL and e["theta"] < TOL and e["lam"] < TOL, e
+        if where == "small":       # well-conditioned there (eps_A = 1e-5): the direction and the step size carry bars too
+            assert e["v"] < TOL and e["eps"] < KTOL, e
+        assert int(pull(gpu, "COUNTERS")[0]) == 3 * (it + 1) and int(pull(gpu, "COUNTERS")[1]) == it + 1
+        assert int(pull(gpu, "COUNTERS")[2]) == 0
+    gpu.close()
 
 
 def test_second_stream_changes_no_result():
@@ -219,11 +338,9 @@ def test_single_sequence_batches():
     x, y, xm, ym = x[:1], y[:1], xm[:1], ym[:1]
     for _ in range(2):
         orc.base_step(x, y)
-    _snap(orc)
     push_state(orc, gpu)
     orc.base_step(x, y); gpu.base_step(dev_batch(gpu, x, y))
     assert rel_l2(pull(gpu, "G"), orc.g) < KTOL
-    _snap(orc)
     push_state(orc, gpu)
     r = orc.meta_step(x, y, xm, ym)
     gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
@@ -255,23 +372,27 @@ def test_free_running_trajectory_is_reproducible_bit_for_bit():
         assert np.array_equal(outs[0][k], outs[1][k]), k
 
 
-@pytest.mark.parametrize("variant", ["sgd", "sama_na"])
+@pytest.mark.parametrize("variant", ["sgd", "sgd_momentum", "sama_na"])
 def test_small_encoder_sgd_and_no_adaptation(variant):
     """The bf16 encoder with an SGD base solver (D = base lr) and with the adaptation switched off (SAMA-NA, D = 1):
     the per-layer update / adaptation slices of the two-stream backward take their other branches here."""
     wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
-    kw = dict(base_opt="sgd", base_lr=0.05) if variant == "sgd" else dict(adapt_mode=1, base_lr=1e-3)
+    kw = {"sgd": dict(base_opt="sgd", base_lr=0.05), "sgd_momentum": dict(base_opt="sgd", base_lr=0.02, momentum=0.9),
+          "sama_na": dict(adapt_mode=1, base_lr=1e-3)}[variant]
     orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), **kw)
     for s in range(2):
         (x, y), _ = _batches(wl, s)
         orc.base_step(x, y)
     (x, y), (xm, ym) = _batches(wl, 2)
-    _snap(orc)
     push_state(orc, gpu)
+    th_before = orc.theta.copy()
     orc.base_step(x, y); gpu.base_step(dev_batch(gpu, x, y))
     assert rel_l2(pull(gpu, "G"), orc.g) < KTOL
     assert rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
-    _snap(orc)
+    if variant != "sama_na":       # SGD's update is linear in g (Adam's divides by sqrt(v'), which magnifies the error of small entries)
+        assert rel_l2(pull(gpu, "THETA").astype(np.float64) - th_before, orc.theta - th_before) < KTOL
+    if variant == "sgd_momentum":
+        assert rel_l2(pull(gpu, "M"), orc.m) < KTOL and rel_l2(orc.m, orc.g) > 0.5                       # the velocity, with history
     push_state(orc, gpu)
     r = orc.meta_step(x, y, xm, ym)
     gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
@@ -299,7 +420,6 @@ def test_padded_batches_small_encoder():
         (x, y), (xm, ym) = _batches(wl, s)
         lt = lens_all[5 * s:5 * s + 5].copy(); lm = lens_all[40 + 3 * s:43 + 3 * s].copy()
         lt[0], lt[1], lm[0] = 1, S, 2
-        _snap(orc)
         push_state(orc, gpu)
         tb, mb = dev_batch(gpu, x, y, lens=lt), dev_batch(gpu, xm, ym, lens=lm)
         # the mask matters on these batches
@@ -311,7 +431,6 @@ def test_padded_batches_small_encoder():
         print(f"padded base step {s}: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
         assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
         assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 2e-2 * abs(lo)
-        _snap(orc)
         push_state(orc, gpu)
         r = orc.meta_step(with_lengths(x, lt), y, with_lengths(xm, lm), ym)
         gpu.meta_step(tb, mb)
@@ -364,7 +483,6 @@ def test_other_sequence_lengths(S, padded, B):
         orc.base_step(inp(x, lens[B * (s + 1):B * (s + 2)]), y)
     (x, y), (xm, ym) = _batches(wl, 3)
     lt, lm = lens[:B], lens[5 * B:5 * B + Bm]
-    _snap(orc)
     push_state(orc, gpu)
     tb = dev_batch(gpu, x, y, lens=lt if padded else None)
     mb = dev_batch(gpu, xm, ym, lens=lm if padded else None)
@@ -375,7 +493,6 @@ def test_other_sequence_lengths(S, padded, B):
     print(f"S={S} padded={padded} base: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
     assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
     assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 2e-2 * abs(lo)
-    _snap(orc)
     push_state(orc, gpu)
     r = orc.meta_step(inp(x, lt), y, inp(xm, lm), ym)
     gpu.meta_step(tb, mb)
@@ -394,7 +511,6 @@ def test_eval_small_encoder_with_padding():
     S = wl.dims[4]
     orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
     (x, y), (xm, ym) = _batches(wl, 0)
-    _snap(orc)
     push_state(orc, gpu)
     orc.t = 1                                            # evaluate needs no history; keep the oracle's guard quiet
     lens = np.array([S, 9, 1, 77, 40], dtype=np.int32)
@@ -448,7 +564,6 @@ def test_wide_encoder(d, heads, ffn):
         (x, y), _ = _batches(wl, s)
         orc.base_step(x, y)
     (x, y), (xm, ym) = _batches(wl, 2)
-    _snap(orc)
     push_state(orc, gpu)
     tb, mb = dev_batch(gpu, x, y), dev_batch(gpu, xm, ym)
     lo = orc.base_step(x, y)
@@ -458,21 +573,21 @@ def test_wide_encoder(d, heads, ffn):
     print(f"d={d} base: rel-L2 g {rel_l2(g, orc.g):.3e}; worst group {max(errs, key=errs.get)} {max(errs.values()):.3e}")
     assert rel_l2(g, orc.g) < KTOL and all(e < TOL for e in errs.values()), errs
     assert abs(float(pull(gpu, "SCALARS")[2]) - lo) < 2e-2 * abs(lo)
-    _snap(orc)
     push_state(orc, gpu)
     r = orc.meta_step(x, y, xm, ym)
     gpu.meta_step(tb, mb)
     e = dict(gmeta=rel_l2(pull(gpu, "GMETA"), r["g_meta"]), h=rel_l2(pull(gpu, "HYPERGRAD"), r["h"]),
              glam_p=rel_l2(pull(gpu, "GLAM_PLUS"), r["glam_p"]), theta=rel_l2(pull(gpu, "THETA"), orc.theta))
-    gp, gm = pull(gpu, "GLAM_PLUS").astype(np.float64), pull(gpu, "GLAM_MINUS").astype(np.float64)
-    e["glam_m"] = rel_l2(gm, r["glam_m"]); e["eps"] = abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"]
-    signal = np.linalg.norm(r["glam_p"] - r["glam_m"])
-    # h = -(g+ - g-) / (2 eps), so its relative error is at most (|dg+| + |dg-|) / |g+ - g-| + the relative error of eps.
-    # On this single-layer wide model at its initial point the two passes differ in the fourth digit only, which turns
-    # the 1e-4 errors of g+ and g- into a few percent of h: the 2e-2 bar of the workloads does not apply here, the
-    # inputs of the difference carry their own bars and the difference itself is checked against this bound.
-    bound = (np.linalg.norm(gp - r["glam_p"]) + np.linalg.norm(gm - r["glam_m"])) / signal + e["eps"]
-    print(f"d={d} meta: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()) + f" signal/|g+|={signal / np.linalg.norm(r['glam_p']):.1e} bound={bound:.2e}")
-    assert e["gmeta"] < KTOL and e["glam_p"] < KTOL and e["glam_m"] < KTOL and e["eps"] < KTOL and e["theta"] < TOL
-    assert e["h"] <= 1.05 * bound + 1e-5 and e["h"] < 1e-1
+    e["glam_m"] = rel_l2(pull(gpu, "GLAM_MINUS"), r["glam_m"]); e["eps"] = abs(pull(gpu, "SCALARS")[0] - r["eps"]) / r["eps"]
+    # h = -(g+ - g-) / (2 eps): with |dg+-| <= GBAR |g+-| and the relative error of eps <= EBAR, the relative error of h is
+    # at most GBAR (|g+| + |g-|) / |g+ - g-| + EBAR -- a bar made of the oracle's numbers and the two fixed bars alone.
+    # On this single-layer wide model at its initial point the two passes differ in the fourth digit only, so the
+    # bar on h is far above the workloads' 2e-2; the inputs of the difference carry the tight bars.
+    GBAR, EBAR = 2e-4, KTOL
+    amplification = (np.linalg.norm(r["glam_p"]) + np.linalg.norm(r["glam_m"])) / np.linalg.norm(r["glam_p"] - r["glam_m"])
+    hbar = GBAR * amplification + EBAR
+    print(f"d={d} meta: " + " ".join(f"{k}={v:.2e}" for k, v in e.items()) + f" amplification={amplification:.1e} hbar={hbar:.2e}")
+    assert e["gmeta"] < KTOL and e["theta"] < TOL
+    assert e["glam_p"] < GBAR and e["glam_m"] < GBAR and e["eps"] < EBAR
+    assert e["h"] < hbar
     gpu.close()

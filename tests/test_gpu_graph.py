@@ -48,6 +48,20 @@ def _run(cfg, small=None, replays=4):
                 assert np.array_equal(a, b), (k, name)
             cnt = graph.get_state("COUNTERS").cpu().numpy()
             assert int(cnt[0]) == 1 + k and int(cnt[1]) == 1 + k and int(cnt[2]) == 0
+        # eager calls and replays interleaved on one context (every pass that writes theta keeps the residual half of the
+        # split weights current, so neither kind of call depends on which kind ran before it)
+        bx, by, bxm, bym = batches(replays + 1)
+        x.copy_(torch.as_tensor(bx)); y.copy_(torch.as_tensor(by)); xm.copy_(torch.as_tensor(bxm)); ym.copy_(torch.as_tensor(bym))
+        graph.base_step(out[graph][0]); eager.base_step(out[eager][0])
+        g.replay()
+        eager.base_step(out[eager][0]); eager.meta_step(*out[eager])
+        graph.meta_grad(*out[graph]); eager.meta_grad(*out[eager])
+        stream.synchronize()
+        assert np.array_equal(graph.get_state("HYPERGRAD").cpu().numpy(), eager.get_state("HYPERGRAD").cpu().numpy())
+        graph.meta_step(*out[graph]); eager.meta_step(*out[eager])
+        stream.synchronize()
+        for name in ("THETA", "LAMBDA", "M", "V", "HYPERGRAD", "COUNTERS"):
+            assert np.array_equal(graph.get_state(name).cpu().numpy(), eager.get_state(name).cpu().numpy()), ("interleaved", name)
         eager.close(); graph.close()
 
 

@@ -129,14 +129,40 @@ def test_degenerate_direction_is_skipped():
     gpu.close()
 
 
-@pytest.mark.parametrize("variant", ["sgd", "sama_na"])
+def test_non_finite_hypergradient_is_skipped():
+    """A lambda-gradient that is not finite although ||v|| is (here: a NaN planted in the weight net's output bias after
+    the base steps, which the direct-gradient pass never reads): hypergradient 0, lambda, theta and the meta moments
+    untouched, status raised, the meta step count not advanced -- as the oracle does."""
+    wl = make_workload(1)
+    orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl))
+    tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
+    for _ in range(3):
+        orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+    lam = pull(gpu, "LAMBDA").copy(); lam[-1] = np.nan
+    gpu.set_state("LAMBDA", lam); orc.lam = lam.astype(np.float64)
+    th, mm = pull(gpu, "THETA"), pull(gpu, "META_M")
+    r = orc.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta)
+    assert orc.status == 1 and orc.meta_t == 0 and r["eps"] > 0 and not np.all(np.isfinite(r["h"]))
+    gpu.meta_step(tb, mb)
+    assert np.all(pull(gpu, "HYPERGRAD") == 0) and np.array_equal(pull(gpu, "THETA"), th)
+    assert np.array_equal(pull(gpu, "LAMBDA"), lam, equal_nan=True) and np.array_equal(pull(gpu, "META_M"), mm)
+    cnt = pull(gpu, "COUNTERS")
+    assert int(cnt[1]) == 0 and int(cnt[2]) == 1 and float(pull(gpu, "SCALARS")[0]) > 0
+    gpu.close()
+
+
+@pytest.mark.parametrize("variant", ["sgd", "sgd_momentum", "sama_na"])
 def test_sgd_and_no_adaptation_variants(variant):
     wl = make_workload(1)
-    kw = dict(base_opt="sgd", base_lr=0.05) if variant == "sgd" else dict(adapt_mode=1)
+    kw = {"sgd": dict(base_opt="sgd", base_lr=0.05), "sgd_momentum": dict(base_opt="sgd", base_lr=0.05, momentum=0.9),
+          "sama_na": dict(adapt_mode=1)}[variant]
     orc, gpu = make_pair(wl, init_theta(wl), init_lambda(wl), **kw)
     tb, mb = dev_batch(gpu, wl.x_train, wl.y_train), dev_batch(gpu, wl.x_meta, wl.y_meta)
-    for _ in range(2):
+    for _ in range(3 if variant == "sgd_momentum" else 2):
         orc.base_step(wl.x_train, wl.y_train); gpu.base_step(tb)
+    if variant == "sgd_momentum":      # free-running velocity (the M state) and weights after three steps
+        assert rel_l2(pull(gpu, "M"), orc.m) < TOL and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
+        assert rel_l2(orc.m, orc.g) > 0.5
     r = orc.meta_step(wl.x_train, wl.y_train, wl.x_meta, wl.y_meta); gpu.meta_step(tb, mb)
     assert rel_l2(pull(gpu, "HYPERGRAD"), r["h"]) < TOL and rel_l2(pull(gpu, "THETA"), orc.theta) < TOL
     gpu.close()

@@ -111,3 +111,22 @@ def test_sgd_momentum_by_hand_and_its_adaptation():
     assert np.allclose(fd, optim.sgd_adaptation(g, lr), rtol=1e-9)
     t2, b2 = optim.sgd_momentum_update(th0, buf, g, lr, 0.0)
     assert np.array_equal(t2, optim.sgd_update(th0, g, lr)) and np.array_equal(b2, g)
+
+
+def test_adaptation_peaks_where_the_second_moment_meets_eps():
+    """Closed form of a special case of App. C: an entry whose last gradient is zero (g = 0, so m' = beta1 m, v' = beta2 v)
+    has D(s) = lr c1 c2 (1 - beta1) s / (c2 s + eps)^2 with s = sqrt(v'), which peaks at c2 s = eps with the value
+    lr c1 (1 - beta1) / (4 eps) -- for eps = 1e-8 seven orders of magnitude above D of an entry with |g| ~ 1.  Around
+    that peak D follows the entry's tiny gradient history with unit relative sensitivity, which is why the perturbation
+    vector of Eq. 4 is ill-conditioned in the first steps of a run (many entries with almost no history)."""
+    lr, b1, b2, eps, t = 1e-3, 0.9, 0.999, 1e-8, 3
+    c1, c2 = 1 / (1 - b1**t), 1 / np.sqrt(1 - b2**t)
+    s = np.logspace(-12, -2, 2001) * 1.0
+    D = optim.adam_adaptation(np.zeros_like(s), np.full_like(s, 0.3), s * s, t, lr, b1, b2, eps)
+    assert np.allclose(D, lr * c1 * c2 * (1 - b1) * s / (c2 * s + eps) ** 2, rtol=1e-12)
+    k = int(np.argmax(D))
+    assert abs(c2 * s[k] / eps - 1.0) < 2e-2 and abs(D[k] / (lr * c1 * (1 - b1) / (4 * eps)) - 1.0) < 1e-3
+    # an entry with a steady gradient of size 1: D is of the order of lr
+    g1 = np.array([1.0])
+    D1 = optim.adam_adaptation(g1, (1 - b1**t) * g1, (1 - b2**t) * g1 * g1, t, lr, b1, b2, eps)
+    assert D[k] / abs(D1[0]) > 1e6
