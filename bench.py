@@ -22,10 +22,20 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0      # dense bf16 MFMA
 PEAK_FP32_MATRIX_TFLOPS = 157.3
-# HBM-side bytes per launch of the dominant kernel family (the hi + lo forward GEMMs) on workload 5, from the two
-# rocprofv3 --pmc runs summarised in profiles/bench_workload5_hbm_traffic.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
-# calibrated on the library's own copy kernel).  Not measured for other workloads / kernels: reported as null there.
-MEASURED_TRAFFIC_BYTES = {(5, "gemm_bf16_nt_hilo"): 99.5e6}
+
+
+def measured_traffic(cfg_id, family):
+    """HBM-side bytes per launch of a kernel family, as the two rocprofv3 --pmc runs of this command measured them
+    (FETCH_SIZE and WRITE_SIZE, calibrated on the library's own copy kernel): read from the line
+    `traffic_bytes_per_launch <family> = <bytes>` of profiles/bench_workload<k>_hbm_traffic.md, which the profile summary
+    carries next to its table.  None where no such profile exists (other workloads, other launch options)."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"bench_workload{cfg_id}_hbm_traffic.md")
+    try:
+        m = re.search(r"traffic_bytes_per_launch\s+" + re.escape(family) + r"\s*=\s*([0-9.eE+]+)", open(path).read())
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
 
 
 def fwd_flops(wl, batch):
@@ -60,6 +70,7 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture each iteration (unroll base steps + meta step) into a HIP graph once per synthetic batch and time "
                          "replays instead of eager calls")
+    ap.add_argument("--no-unroll10", action="store_true", help="skip the extra timed region at unroll 10 (the paper's operating point)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -161,6 +172,25 @@ def main():
     status = s.get_state("COUNTERS").cpu().numpy()
     skipped = int(status[2])
 
+    # The paper's operating point (App. B: unroll step 10): ten base steps per meta step, timed after the headline region
+    unroll10 = None
+    if args.unroll == 1 and not args.no_unroll10:
+        def step10(k):
+            tb, mb = batches[k % nb]
+            for _ in range(10):
+                (s.aux_base_step(tb, aux[k % nb]) if args.aux else s.base_step(tb))
+            (s.aux_meta_step(aux[k % nb], mb) if args.aux else s.meta_step(tb, mb))
+        step10(0)
+        torch.cuda.synchronize(dev)
+        k10 = max(2, min(5, args.steps // 4))
+        t1 = time.perf_counter()
+        for k in range(k10):
+            step10(1 + k)
+        torch.cuda.synchronize(dev)
+        e10 = time.perf_counter() - t1
+        unroll10 = {"unroll": 10, "value": k10 / e10, "unit": "meta-steps/s", "ms_per_step": 1e3 * e10 / k10, "steps": k10, "warmup": 1,
+                    "base_steps_per_s": 10 * k10 / e10, "launch": "eager"}
+
     out = {
         "metric": "SAMA meta-steps/sec on 1 MI355X", "value": args.steps / elapsed, "unit": "meta-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -197,15 +227,19 @@ def main():
             avg_us = 1e3 * ms / cnt
             ent = {"launches_per_step": cnt / prof_steps, "avg_us": avg_us, "ms_per_step": ms / prof_steps}
             if name.startswith("gemm_bf16") or name.startswith("attention"):
-                ent.update(bound="mfma", achieved=units / (ms * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
+                # The library counts a two-term (hi + lo) launch as the contraction over the concatenated operand it
+                # executes, 2 M N (2K); the algorithmic work of the method is 2 M N K per GEMM, whatever the split.
+                alg = 0.5 * units if name.endswith("_hilo") else units
+                ent.update(bound="mfma", achieved=alg / (ms * 1e-3) / 1e12, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s")
+                if name.endswith("_hilo"):
+                    ent["executed"] = {"achieved": units / (ms * 1e-3) / 1e12, "frac": units / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                                       "note": "matrix-core work as issued: both halves of the split weights"}
             elif name == "gemm_f32":
                 ent.update(bound="mfma", achieved=units / (ms * 1e-3) / 1e12, peak=PEAK_FP32_MATRIX_TFLOPS, unit="TFLOP/s")
             elif units > 0:   # every other family is priced in algorithmic bytes
                 ent.update(bound="hbm", achieved=units / (ms * 1e-3) / 1e9, peak=PEAK_HBM_GBS, unit="GB/s")
             if "achieved" in ent:
                 ent["frac"] = ent["achieved"] / ent["peak"]
-            if name.endswith("_hilo"):   # the same launches priced at 2 M N K (one weight term)
-                ent["frac_single_term"] = 0.5 * ent["frac"]
             kernels[name] = ent
         dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
         d = kernels[dom]
@@ -218,14 +252,16 @@ def main():
         ew = [kernels[k] for k in ("adam", "adapt_norm", "perturb_lo", "residual_lo", "nudge") if k in kernels]
         ew_bytes = sum(k["achieved"] * 1e9 * k["ms_per_step"] * 1e-3 for k in ew)
         ew_ms = sum(k["ms_per_step"] for k in ew)
+        default_launch = args.unroll == 1 and not (args.fast_meta_pass or args.fast_base_pass or args.aux or args.corr_hidden or args.length_mix)
         out["roofline"] = {
             "replay": "per-kernel durations from an instrumented replay with every launch on one stream; the timed steps "
                       "run the weight-gradient GEMMs and per-layer update slices on a second stream",
             "kernel": dom, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
             "unit": d.get("unit"), "frac": d.get("frac"),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg_id, dom)) if args.unroll == 1 and not args.fast_meta_pass else None,
+            "work": "algorithmic: 2 M N K per GEMM (bytes the method must move for the HBM-bound families)",
+            "executed": d.get("executed"),   # hi + lo families: the matrix-core work as issued, 2 M N (2K); else null
+            "traffic": measured_traffic(cfg_id, dom) if default_launch else None,
             "avg_us": d["avg_us"],
-            "frac_single_term": d.get("frac_single_term"),   # hi + lo families priced at 2 M N K instead of 2 M N (2K); else null
             "elementwise_chain": {"bound": "hbm", "achieved": ew_bytes / (ew_ms * 1e-3) / 1e9 if ew_ms > 0 else None,
                                   "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                   "frac": ew_bytes / (ew_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if ew_ms > 0 else None,
@@ -234,50 +270,64 @@ def main():
                                  "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS if wl.bf16 else PEAK_FP32_MATRIX_TFLOPS},
             "kernels": kernels,
         }
+    if unroll10 is not None:
+        out["unroll10"] = unroll10
 
     # ---------------------------------------------------------------- oracle on the host cores (bounded sample)
     if not args.no_cpu_baseline:
         from oracle import models
         from oracle.reweight import SamaOracle
-        cb = {1: wl.batch, 2: wl.batch, 3: 8, 4: 2, 5: 1}[cfg_id]       # samples per batch in the CPU sample
-        cm = min(cb, wl.meta_batch)
-        it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
-        x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
-        if args.length_mix:
-            x, xm = models.with_lengths(x, len_train[it]), models.with_lengths(xm, len_meta[im])
-        reps = {1: 20, 2: 10, 3: 3}.get(cfg_id, 1)
-        if args.aux:
-            from oracle.auxtask import AuxTaskOracle
-            orc = AuxTaskOracle(models.make_model(wl.kind, wl.dims, mlm=True), th0, lam0, base_lr=wl.base_lr,
-                                meta_lr=wl.meta_lr, alpha=wl.alpha)
-            pt = make_aux_batch(wl, 0, cb)
-            orc.base_step((x, y), pt)                                     # history (untimed)
-            t0 = time.perf_counter()
-            for _ in range(args.unroll):
-                orc.base_step((x, y), pt)
-            orc.meta_step(pt, (xm, ym))
-        else:
-            orc = SamaOracle(models.make_model(wl.kind, wl.dims), th0, lam0, base_lr=wl.base_lr, meta_lr=wl.meta_lr,
-                             alpha=wl.alpha, corr_hidden=args.corr_hidden,
-                             n_classes=wl.dims[-1] if args.corr_hidden > 0 else None)
-            orc.base_step(x, y)                                           # history (untimed)
-            t0 = time.perf_counter()
-            for _ in range(reps):
+        # One oracle iteration costs a + b * batch seconds (a: the elementwise chain over the n parameters and the fixed
+        # overheads, b: the passes over one sample).  Workloads 1-3 are timed at the benched batch itself; for 4 and 5
+        # that takes minutes, so a and b are measured at two small batch sizes and the benched batch is priced with them.
+        sizes = {1: [wl.batch], 2: [wl.batch], 3: [wl.batch], 4: [1, 3], 5: [1, 2]}[cfg_id]
+        reps = {1: 20, 2: 10, 3: 2}.get(cfg_id, 1)
+        times = []
+        for cb in sizes:
+            cm = min(cb, wl.meta_batch)
+            it, im = wl.train_batch(0)[:cb], wl.meta_batch_idx(0)[:cm]
+            x, y, xm, ym = wl.x_train[it], wl.y_train[it], wl.x_meta[im], wl.y_meta[im]
+            if args.length_mix:
+                x, xm = models.with_lengths(x, len_train[it]), models.with_lengths(xm, len_meta[im])
+            if args.aux:
+                from oracle.auxtask import AuxTaskOracle
+                orc = AuxTaskOracle(models.make_model(wl.kind, wl.dims, mlm=True), th0, lam0, base_lr=wl.base_lr,
+                                    meta_lr=wl.meta_lr, alpha=wl.alpha)
+                pt = make_aux_batch(wl, 0, cb)
+                orc.base_step((x, y), pt)                                     # history (untimed)
+                t0 = time.perf_counter()
                 for _ in range(args.unroll):
-                    orc.base_step(x, y)
-                orc.meta_step(x, y, xm, ym)
-        tcpu = (time.perf_counter() - t0) / reps
-        scale = wl.batch / cb
+                    orc.base_step((x, y), pt)
+                orc.meta_step(pt, (xm, ym))
+            else:
+                orc = SamaOracle(models.make_model(wl.kind, wl.dims), th0, lam0, base_lr=wl.base_lr, meta_lr=wl.meta_lr,
+                                 alpha=wl.alpha, corr_hidden=args.corr_hidden,
+                                 n_classes=wl.dims[-1] if args.corr_hidden > 0 else None)
+                orc.base_step(x, y)                                           # history (untimed)
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    for _ in range(args.unroll):
+                        orc.base_step(x, y)
+                    orc.meta_step(x, y, xm, ym)
+            times.append((time.perf_counter() - t0) / reps)
+            del orc
         try:
             import threadpoolctl
             threads = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
         except Exception:
             threads = os.cpu_count()
-        out["cpu_baseline"] = {
-            "value": 1.0 / (tcpu * scale), "unit": "meta-steps/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{reps} meta step(s) of the float64 NumPy oracle at train/meta batch {cb}/{cm} instead of "
-                      f"{wl.batch}/{wl.meta_batch}; measured {tcpu:.2f} s per step, scaled by {scale:g} "
-                      f"(over-counts the batch-independent elementwise part)"}
+        if len(sizes) == 1:
+            tcpu = times[0]
+            sample = (f"{reps} iteration(s) (unroll {args.unroll}) of the float64 NumPy oracle at the benched train/meta batch "
+                      f"{wl.batch}/{wl.meta_batch}: {tcpu:.3f} s each")
+        else:
+            b_ = (times[1] - times[0]) / (sizes[1] - sizes[0])
+            a_ = times[0] - b_ * sizes[0]
+            tcpu = a_ + b_ * wl.batch
+            sample = (f"one iteration (unroll {args.unroll}) of the float64 NumPy oracle at train = meta batch {sizes[0]} and {sizes[1]}: "
+                      f"{times[0]:.2f} s and {times[1]:.2f} s, i.e. {a_:.2f} s + {b_:.2f} s per sample; the benched batch "
+                      f"{wl.batch}/{wl.meta_batch} priced with that line: {tcpu:.1f} s per iteration")
+        out["cpu_baseline"] = {"value": 1.0 / tcpu, "unit": "meta-steps/s", "cores": int(threads), "kind": "oracle", "sample": sample}
     s.close()
     print(json.dumps(out))
 
