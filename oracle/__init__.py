@@ -21,6 +21,11 @@ Pins (tests/test_oracle_*.py; every function of the package has one):
   auxtask                    masked-token head against torch autograd, base gradient and
                              lambda-gradient against differences of the scalar base loss (Sec. 4.3)
   SGD invariant              adaptation reduces to a scalar step size           (Sec. 3.1-3.2)
+  optim.sgd_momentum_update  heavy-ball steps by hand, du/dg by a central difference, the assembled
+                             trajectory against hand-written steps          (App. B tables, reading)
+  conditioning of Eq. 4      closed form of the adaptation for entries whose last gradient vanishes
+                             and its peak at c2 sqrt(v') = eps_A; sensitivity of v to gradient noise
+                             in the first steps of a run                                   (App. C)
 The pins run at small shapes; the same code then runs the full-size workloads 3-5, for which
 no second reference exists.
 """

@@ -472,7 +472,8 @@ void launch_nudge(hipStream_t st, float* theta, const float* vdir, const float* 
 void launch_unnudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status,
                     bf16_t* theta16, bf16_t* lo, int64_t n16) {
   if (n16 <= 0) return;
-  k_unnudge<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, status, theta16, lo, n16);
+  const int grid = ew_grid(n16) < 2048 ? ew_grid(n16) : 2048;   // almost always an early exit: keep the launch small
+  k_unnudge<<<grid, EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, status, theta16, lo, n16);
 }
 void launch_fill_f32(hipStream_t st, float* p, float val, int64_t n) {
   if (n <= 0) return;
