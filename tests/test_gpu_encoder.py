@@ -503,6 +503,28 @@ def test_other_sequence_lengths(S, padded, B):
     gpu.close()
 
 
+def test_out_of_range_ids_and_labels_are_clamped():
+    """Token ids outside [0, V) and labels outside [0, C) are clamped on the device by every kernel that indexes with
+    them (embedding gather, token-gradient scatter, per-sample stage): a batch carrying such values gives the bits of
+    the batch with the clamped values, for the base step and for the meta step."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    V, C = wl.dims[5], wl.dims[6]
+    (x, y), (xm, ym) = _batches(wl, 0)
+    bad_x, bad_y = x.copy(), y.copy()
+    bad_x[0, 3], bad_x[1, 7], bad_x[2, 0], bad_x[4, 127] = V + 5, -3, 2 ** 30, -2 ** 31
+    bad_y[0], bad_y[3] = C + 2, -1
+    res = []
+    for xx, yy in ((bad_x, bad_y), (np.clip(bad_x, 0, V - 1), np.clip(bad_y, 0, C - 1))):
+        _, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+        tb, mb = dev_batch(gpu, xx, yy), dev_batch(gpu, xm, ym)
+        gpu.base_step(tb); gpu.base_step(tb); gpu.meta_step(tb, mb)
+        res.append({k: pull(gpu, k).copy() for k in ("G", "THETA", "HYPERGRAD", "LAMBDA", "LOSSES")})
+        assert np.all(np.isfinite(res[-1]["THETA"])) and int(pull(gpu, "COUNTERS")[2]) == 0
+        gpu.close()
+    for k in res[0]:
+        assert np.array_equal(res[0][k], res[1][k]), k
+
+
 def test_eval_small_encoder_with_padding():
     """sama_eval on the bf16 encoder, padded batch: logits, losses and weights against the oracle at the bf16 working
     weights (what the base step's forward sees)."""
