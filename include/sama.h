@@ -253,9 +253,9 @@ const char* sama_last_error(const sama_ctx* ctx);
  * sama_profile_read synchronises with the recorded events and returns, for kernel family `family`
  * (0 .. sama_profile_family_count()-1): its name (HOST string owned by the library), the number of launches, their
  * summed duration in milliseconds and their summed algorithmic work: flops for the GEMM and attention families,
- * bytes for the others (Adam 28 B per parameter + 2 B per GEMM weight; adaptation 20 B; +-eps halves 12 B per
- * GEMM weight, or 18 B when sama_meta_step nudges the GEMM block in the same pass; residual half 6 B; nudge 12 B +
- * 2 B over the elements it covers).  Two-term (hi + lo) GEMM launches are families of their own
+ * bytes for the others (Adam 28 B per parameter + 4 B per GEMM weight -- the bf16 working copy and its residual half;
+ * adaptation 20 B; +-eps halves 12 B per GEMM weight, or 18 B when sama_meta_step nudges the GEMM block in the same
+ * pass; residual half alone 6 B; nudge 12 B + 2 B per bf16 array it refreshes over the elements it covers).  Two-term (hi + lo) GEMM launches are families of their own
  * ("..._hilo") and count 2 M N (2K): they contract over the concatenated operand. */
 int32_t sama_profile_family_count(void);
 sama_status sama_profile_enable(sama_ctx* ctx, int32_t on);
