@@ -106,5 +106,15 @@ def test_bad_configs_rejected(lib):
                 pkg.SamaConfig.make("mlp", (4, 3), corr_hidden=4, corr_kappa=float("nan"), **good)):
         assert lib.sama_lambda_count(C.byref(bad)) == 0
         assert lib.sama_workspace_bytes(C.byref(bad)) == 0
+    # SGD momentum in [0, 1) and only with the SGD solver; the precision switches are 0 / 1
+    assert lib.sama_workspace_bytes(C.byref(pkg.SamaConfig.make("mlp", (4, 3), base_opt=pkg.OPT_SGD, momentum=0.9, **good))) > 0
+    for bad in (pkg.SamaConfig.make("mlp", (4, 3), base_opt=pkg.OPT_SGD, momentum=1.0, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), base_opt=pkg.OPT_SGD, momentum=-0.1, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), base_opt=pkg.OPT_SGD, momentum=float("nan"), **good),
+                pkg.SamaConfig.make("mlp", (4, 3), base_opt=pkg.OPT_ADAM, momentum=0.5, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), fast_base_pass=2, **good),
+                pkg.SamaConfig.make("mlp", (4, 3), fast_meta_pass=-1, **good)):
+        assert lib.sama_workspace_bytes(C.byref(bad)) == 0
+        assert lib.sama_last_error(None) != b""
     h = C.c_void_p()
     assert lib.sama_init(C.byref(c), None, 0, None, None, None, C.byref(h)) != 0
