@@ -417,7 +417,7 @@ void launch_adam(hipStream_t st, float* g, float* m, float* v, float* theta, bf1
                  int64_t n16, const AdamArgs& a) {
   if (n <= 0) return;
   ProfScope ps(st, F_ADAM, 28.0 * n + (theta16 ? 2.0 * n16 : 0.0) + (a.lo ? 2.0 * n16 : 0.0));
-  k_adam<<<ew_grid(n), EW_THREADS, 0, st>>>(g, m, v, theta, theta16, n, n16, a);
+  launch_kernel(ps, k_adam, ew_grid(n), EW_THREADS, 0, st, g, m, v, theta, theta16, n, n16, a);
 }
 void launch_step_scalars(hipStream_t st, int64_t* counters, int advance, float lr, float beta1, float beta2, float* step) {
   k_step_scalars<<<1, 1, 0, st>>>(counters, advance, lr, beta1, beta2, step);
@@ -431,7 +431,7 @@ void launch_adapt_norm(hipStream_t st, const float* g, const float* m, const flo
                        double* partial, int64_t n, const AdaptArgs& a, float alpha, float* scalars, int64_t* status) {
   const int grid = ew_grid(n);
   ProfScope ps(st, F_ADAPT_NORM, (a.mode == 0 ? 20.0 : 8.0) * n);
-  k_adapt_norm<<<grid, EW_THREADS, 0, st>>>(g, m, v, gmeta, vdir, partial, n, a);
+  launch_kernel(ps, k_adapt_norm, grid, EW_THREADS, 0, st, g, m, v, gmeta, vdir, partial, n, a);
   k_eps_from_partials<<<1, 1024, 0, st>>>(partial, grid, alpha, scalars, status);
 }
 int launch_adapt_slice(hipStream_t st, const float* g, const float* m, const float* v, const float* gmeta, float* vdir,
@@ -440,7 +440,7 @@ int launch_adapt_slice(hipStream_t st, const float* g, const float* m, const flo
   int grid = ew_grid(n);
   if (grid > max_blocks) grid = max_blocks;
   ProfScope ps(st, F_ADAPT_NORM, (a.mode == 0 ? 20.0 : 8.0) * n);
-  k_adapt_norm<<<grid, EW_THREADS, 0, st>>>(g, m, v, gmeta, vdir, partial, n, a);
+  launch_kernel(ps, k_adapt_norm, grid, EW_THREADS, 0, st, g, m, v, gmeta, vdir, partial, n, a);
   return grid;
 }
 void launch_eps_from_partials(hipStream_t st, const double* partial, int count, float alpha, float* scalars, int64_t* status) {
@@ -450,24 +450,24 @@ void launch_perturb_lo(hipStream_t st, const float* theta, const float* vdir, co
                        bf16_t* lo_m, int64_t n16) {
   if (n16 <= 0) return;
   ProfScope ps(st, F_PERTURB, 12.0 * n16);
-  k_perturb_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, lo_p, lo_m, n16);
+  launch_kernel(ps, k_perturb_lo, ew_grid(n16), EW_THREADS, 0, st, theta, vdir, eps_ptr, lo_p, lo_m, n16);
 }
 void launch_perturb_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, bf16_t* theta16, bf16_t* lo_p,
                           bf16_t* lo_m, int64_t n16) {
   if (n16 <= 0) return;
   ProfScope ps(st, F_PERTURB, 18.0 * n16);
-  k_perturb_nudge<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, theta16, lo_p, lo_m, n16);
+  launch_kernel(ps, k_perturb_nudge, ew_grid(n16), EW_THREADS, 0, st, theta, vdir, eps_ptr, theta16, lo_p, lo_m, n16);
 }
 void launch_residual_lo(hipStream_t st, const float* theta, bf16_t* lo, int64_t n16) {
   if (n16 <= 0) return;
   ProfScope ps(st, F_RESIDUAL, 6.0 * n16);
-  k_residual_lo<<<ew_grid(n16), EW_THREADS, 0, st>>>(theta, lo, n16);
+  launch_kernel(ps, k_residual_lo, ew_grid(n16), EW_THREADS, 0, st, theta, lo, n16);
 }
 void launch_nudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status,
                   bf16_t* theta16, bf16_t* lo, int64_t n, int64_t n16) {
   if (n <= 0) return;
   ProfScope ps(st, F_NUDGE, 12.0 * n + (theta16 ? 2.0 * n16 : 0.0) + (lo ? 2.0 * n16 : 0.0));
-  k_nudge<<<ew_grid(n), EW_THREADS, 0, st>>>(theta, vdir, eps_ptr, status, theta16, lo, n, n16);
+  launch_kernel(ps, k_nudge, ew_grid(n), EW_THREADS, 0, st, theta, vdir, eps_ptr, status, theta16, lo, n, n16);
 }
 void launch_unnudge(hipStream_t st, float* theta, const float* vdir, const float* eps_ptr, const int64_t* status,
                     bf16_t* theta16, bf16_t* lo, int64_t n16) {
@@ -478,7 +478,7 @@ void launch_unnudge(hipStream_t st, float* theta, const float* vdir, const float
 void launch_fill_f32(hipStream_t st, float* p, float val, int64_t n) {
   if (n <= 0) return;
   ProfScope ps(st, F_OTHER, 4.0 * n);
-  k_fill_f32<<<ew_grid(n), EW_THREADS, 0, st>>>(p, val, n);
+  launch_kernel(ps, k_fill_f32, ew_grid(n), EW_THREADS, 0, st, p, val, n);
 }
 void launch_copy_f32(hipStream_t st, float* dst, const float* src, int64_t n) {
   if (n <= 0) return;

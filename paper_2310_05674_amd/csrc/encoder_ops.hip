@@ -609,13 +609,13 @@ __global__ __launch_bounds__(256) void k_tok_grad(const float* __restrict__ demb
 
 void launch_ln_fwd(hipStream_t st, const LnFwdArgs& a) {
   ProfScope ps(st, F_LN_FWD, 6.0 * a.M * a.d);
-  if (a.d <= 1024) k_ln_fwd<4><<<(a.M + 3) / 4, 256, 0, st>>>(a);
-  else k_ln_fwd<8><<<(a.M + 3) / 4, 256, 0, st>>>(a);
+  if (a.d <= 1024) launch_kernel(ps, k_ln_fwd<4>, (a.M + 3) / 4, 256, 0, st, a);
+  else launch_kernel(ps, k_ln_fwd<8>, (a.M + 3) / 4, 256, 0, st, a);
 }
 void launch_ln_bwd(hipStream_t st, const LnBwdArgs& a) {
   ProfScope ps(st, F_LN_BWD, 14.0 * a.M * a.d);
-  if (a.d <= 1024) k_ln_bwd<4><<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
-  else k_ln_bwd<8><<<(a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st>>>(a);
+  if (a.d <= 1024) launch_kernel(ps, k_ln_bwd<4>, (a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st, a);
+  else launch_kernel(ps, k_ln_bwd<8>, (a.M + LN_BWD_ROWS - 1) / LN_BWD_ROWS, 256, 0, st, a);
 }
 void launch_reduce_rows_multi(hipStream_t st, const ReduceRowsJob* jobs, int count) {
   ReduceRowsMulti m{};
@@ -631,7 +631,7 @@ void launch_reduce_rows_multi(hipStream_t st, const ReduceRowsJob* jobs, int cou
   }
   for (int k = count; k <= REDUCE_MAX_JOBS; ++k) m.first_block[k] = nb;
   ProfScope ps(st, F_OTHER, bytes);
-  k_reduce_rows<<<nb, 256, 0, st>>>(m);
+  launch_kernel(ps, k_reduce_rows, nb, 256, 0, st, m);
 }
 void launch_reduce_rows(hipStream_t st, const float* partial, int nrows, int64_t stride, int64_t vstride, int N, float* out0,
                         float* out1, float* out2) {
@@ -651,7 +651,7 @@ void launch_colsum_partial_multi(hipStream_t st, const ColsumJob* jobs, int coun
   }
   for (int k = count; k < 3; ++k) m.first_block[k] = nb;
   ProfScope ps(st, F_OTHER, bytes);
-  k_colsum_partial_bf16<<<nb, 256, 0, st>>>(m);
+  launch_kernel(ps, k_colsum_partial_bf16, nb, 256, 0, st, m);
 }
 void launch_colsum_bf16(hipStream_t st, const bf16_t* X, int M, int N, float* partial, float* out) {
   const int nrb = (M + COLSUM_ROWS - 1) / COLSUM_ROWS;
@@ -668,16 +668,16 @@ void launch_attention_fwd(hipStream_t st, const bf16_t* qkv, bf16_t* out, float*
   const int lp = lens_period > 0 ? lens_period : 1;
   switch (S) {
     case 64:
-      if (lens) k_attn_fwd<2, true><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
-      else k_attn_fwd<2, false><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      if (lens) launch_kernel(ps, k_attn_fwd<2, true>, grid, 256, 0, st, qkv, out, lse, heads, d, lens, lp);
+      else launch_kernel(ps, k_attn_fwd<2, false>, grid, 256, 0, st, qkv, out, lse, heads, d, lens, lp);
       break;
     case 128:
-      if (lens) k_attn_fwd<4, true><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
-      else k_attn_fwd<4, false><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      if (lens) launch_kernel(ps, k_attn_fwd<4, true>, grid, 256, 0, st, qkv, out, lse, heads, d, lens, lp);
+      else launch_kernel(ps, k_attn_fwd<4, false>, grid, 256, 0, st, qkv, out, lse, heads, d, lens, lp);
       break;
     case 256:
-      if (lens) k_attn_fwd<8, true><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
-      else k_attn_fwd<8, false><<<grid, 256, 0, st>>>(qkv, out, lse, heads, d, lens, lp);
+      if (lens) launch_kernel(ps, k_attn_fwd<8, true>, grid, 256, 0, st, qkv, out, lse, heads, d, lens, lp);
+      else launch_kernel(ps, k_attn_fwd<8, false>, grid, 256, 0, st, qkv, out, lse, heads, d, lens, lp);
       break;
     default: break;   // make_encoder admits no other length
   }
@@ -689,16 +689,16 @@ void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, 
   const int lp = lens_period > 0 ? lens_period : 1;
   switch (S) {
     case 64:
-      if (lens) k_attn_bwd<2, true><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
-      else k_attn_bwd<2, false><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      if (lens) launch_kernel(ps, k_attn_bwd<2, true>, grid, 512, 0, st, qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      else launch_kernel(ps, k_attn_bwd<2, false>, grid, 512, 0, st, qkv, out, dout, lse, dqkv, heads, d, lens, lp);
       break;
     case 128:
-      if (lens) k_attn_bwd<4, true><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
-      else k_attn_bwd<4, false><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      if (lens) launch_kernel(ps, k_attn_bwd<4, true>, grid, 512, 0, st, qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      else launch_kernel(ps, k_attn_bwd<4, false>, grid, 512, 0, st, qkv, out, dout, lse, dqkv, heads, d, lens, lp);
       break;
     case 256:
-      if (lens) k_attn_bwd<8, true><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
-      else k_attn_bwd<8, false><<<grid, 512, 0, st>>>(qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      if (lens) launch_kernel(ps, k_attn_bwd<8, true>, grid, 512, 0, st, qkv, out, dout, lse, dqkv, heads, d, lens, lp);
+      else launch_kernel(ps, k_attn_bwd<8, false>, grid, 512, 0, st, qkv, out, dout, lse, dqkv, heads, d, lens, lp);
       break;
     default: break;
   }
@@ -706,18 +706,18 @@ void launch_attention_bwd(hipStream_t st, const bf16_t* qkv, const bf16_t* out, 
 void launch_head_fwd(hipStream_t st, const float* x, int S, int d, int B, int C, ParamView pv, int64_t wc_off, int64_t bc_off,
                      float* logits) {
   ProfScope ps(st, F_OTHER, 0.0);
-  k_head_fwd<<<(B * C + 3) / 4, 256, 0, st>>>(x, S, d, B, C, pv, wc_off, bc_off, logits);
+  launch_kernel(ps, k_head_fwd, (B * C + 3) / 4, 256, 0, st, x, S, d, B, C, pv, wc_off, bc_off, logits);
 }
 void launch_head_bwd(hipStream_t st, const float* x, int S, int d, int B, int C, const float* theta, int64_t wc_off,
                      int64_t bc_off, const float* dlogits, float* grad, float* dx) {
   ProfScope ps(st, F_OTHER, 0.0);
-  k_head_bwd_w<<<(C * d + 255) / 256, 256, 0, st>>>(x, S, d, B, C, dlogits, grad + wc_off, grad + bc_off);
-  k_head_bwd_x<<<(B * d + 255) / 256, 256, 0, st>>>(S, d, B, C, theta + wc_off, dlogits, dx);
+  launch_kernel(ps, k_head_bwd_w, (C * d + 255) / 256, 256, 0, st, x, S, d, B, C, dlogits, grad + wc_off, grad + bc_off);
+  launch_kernel(ps, k_head_bwd_x, (B * d + 255) / 256, 256, 0, st, S, d, B, C, theta + wc_off, dlogits, dx);
 }
 void launch_embedding_bwd(hipStream_t st, const float* demb, const int32_t* ids, int B, int S, int d, int V, float* g_tok, float* g_pos) {
   ProfScope ps(st, F_OTHER, 4.0 * B * S * d);
-  k_pos_grad<<<(S * d + 255) / 256, 256, 0, st>>>(demb, B, S, d, g_pos);
-  k_tok_grad<<<B * S, 256, 0, st>>>(demb, ids, B * S, d, V, g_tok);
+  launch_kernel(ps, k_pos_grad, (S * d + 255) / 256, 256, 0, st, demb, B, S, d, g_pos);
+  launch_kernel(ps, k_tok_grad, B * S, 256, 0, st, demb, ids, B * S, d, V, g_tok);
 }
 
 }  // namespace sama

@@ -419,7 +419,7 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
 }
 
 template <typename T, bool A_KC, bool B_KC>
-void launch_tile(hipStream_t st, const GemmBf16Args* p, int count, int group) {
+void launch_tile(ProfScope& ps, hipStream_t st, const GemmBf16Args* p, int count, int group) {
   static bool configured = false;      // per instantiation: raise the dynamic LDS limit once
   if (!configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_bf16<T, A_KC, B_KC>), hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
@@ -435,7 +435,7 @@ void launch_tile(hipStream_t st, const GemmBf16Args* p, int count, int group) {
   }
   for (int k = count; k <= GEMM_MAX_BATCH; ++k) b.first_tile[k] = nt;
   const int per_xcd = (nt + 7) / 8;
-  k_gemm_bf16<T, A_KC, B_KC><<<8 * per_xcd, T::THREADS, T::LDS_BYTES, st>>>(b, nt, per_xcd);
+  launch_kernel(ps, k_gemm_bf16<T, A_KC, B_KC>, 8 * per_xcd, T::THREADS, T::LDS_BYTES, st, b, nt, per_xcd);
 }
 
 // Tile configurations <BM, BN, BK, waves in M, waves in N, stages, DUAL>
@@ -482,24 +482,24 @@ int pick_tile(const GemmBf16Args* p, int count, bool dual) {
 }
 
 template <bool A_KC, bool B_KC>
-void launch_class(hipStream_t st, const GemmBf16Args* p, int count) {
+void launch_class(ProfScope& ps, hipStream_t st, const GemmBf16Args* p, int count) {
   const bool dual = p[0].B2 != nullptr;
   int shape = g_force_shape;
   if (shape >= 11 && !dual) shape = 0;   // DUAL tiles read B2
   if (shape == 0) shape = pick_tile(p, count, dual);
   switch (shape) {
-    case 1: launch_tile<TL, A_KC, B_KC>(st, p, count, g_group); break;
-    case 2: launch_tile<TM, A_KC, B_KC>(st, p, count, g_group); break;
-    case 4: launch_tile<TX, A_KC, B_KC>(st, p, count, g_group); break;
-    case 5: launch_tile<TX4, A_KC, B_KC>(st, p, count, g_group); break;
-    case 6: launch_tile<TX8, A_KC, B_KC>(st, p, count, g_group); break;
-    case 7: launch_tile<TS8, A_KC, B_KC>(st, p, count, g_group); break;
-    case 11: launch_tile<DL, A_KC, B_KC>(st, p, count, g_group); break;
-    case 12: launch_tile<DM, A_KC, B_KC>(st, p, count, g_group); break;
-    case 13: launch_tile<DS, A_KC, B_KC>(st, p, count, g_group); break;
-    case 14: launch_tile<DX, A_KC, B_KC>(st, p, count, g_group); break;
-    case 15: launch_tile<DX4, A_KC, B_KC>(st, p, count, g_group); break;
-    default: launch_tile<TS, A_KC, B_KC>(st, p, count, g_group); break;
+    case 1: launch_tile<TL, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 2: launch_tile<TM, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 4: launch_tile<TX, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 5: launch_tile<TX4, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 6: launch_tile<TX8, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 7: launch_tile<TS8, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 11: launch_tile<DL, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 12: launch_tile<DM, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 13: launch_tile<DS, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 14: launch_tile<DX, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    case 15: launch_tile<DX4, A_KC, B_KC>(ps, st, p, count, g_group); break;
+    default: launch_tile<TS, A_KC, B_KC>(ps, st, p, count, g_group); break;
   }
 }
 }  // namespace
@@ -541,10 +541,10 @@ void launch_gemm_bf16_batch(hipStream_t st, const GemmBf16Args* p, int count) {
   const bool hilo = p[0].B2 != nullptr;
   ProfScope ps(st, p[0].a_trans ? F_GEMM_TN : (p[0].b_trans ? (hilo ? F_GEMM_NT_HILO : F_GEMM_NT) : (hilo ? F_GEMM_NN_HILO : F_GEMM_NN)), flops);
   // a_trans = 0: A is [M][K], contraction contiguous.  b_trans = 1: B is [N][K], contraction contiguous.
-  if (!p[0].a_trans && p[0].b_trans) launch_class<true, true>(st, p, count);
-  else if (!p[0].a_trans && !p[0].b_trans) launch_class<true, false>(st, p, count);
-  else if (p[0].a_trans && !p[0].b_trans) launch_class<false, false>(st, p, count);
-  else launch_class<false, true>(st, p, count);
+  if (!p[0].a_trans && p[0].b_trans) launch_class<true, true>(ps, st, p, count);
+  else if (!p[0].a_trans && !p[0].b_trans) launch_class<true, false>(ps, st, p, count);
+  else if (p[0].a_trans && !p[0].b_trans) launch_class<false, false>(ps, st, p, count);
+  else launch_class<false, true>(ps, st, p, count);
 }
 
 void launch_gemm_bf16(hipStream_t st, const GemmBf16Args& a) { launch_gemm_bf16_batch(st, &a, 1); }

@@ -103,7 +103,7 @@ void launch_gemm_f32(hipStream_t st, const GemmF32Args& a) {
   if (a.M <= 0 || a.N <= 0) return;
   dim3 grid((a.N + TN - 1) / TN, (a.M + TM - 1) / TM);
   ProfScope ps(st, F_GEMM_F32, 2.0 * a.M * a.N * a.K);
-  k_gemm_f32<<<grid, 256, 0, st>>>(a);
+  launch_kernel(ps, k_gemm_f32, grid, 256, 0, st, a);
 }
 void launch_colsum_f32(hipStream_t st, const float* X, int64_t ld, int M, int N, float* out) {
   if (N <= 0) return;

@@ -1,24 +1,55 @@
 // Host-side launchers of every gfx950 kernel in libsama.  Internal; the C ABI is include/sama.h.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
+#include <tuple>
+#include <utility>
 #include "common.h"
 
 namespace sama {
+namespace detail {
+template <typename Tuple, size_t... I>
+inline void arg_pointers(Tuple& t, void** out, std::index_sequence<I...>) {
+  ((out[I] = const_cast<void*>(static_cast<const void*>(&std::get<I>(t)))), ...);
+}
+}  // namespace detail
 
 // ------------------------------------------------------------------ optional per-launch timing (profile.hip)
 enum Family {
   F_GEMM_NT = 0, F_GEMM_NN, F_GEMM_TN, F_GEMM_NT_HILO, F_GEMM_NN_HILO, F_GEMM_F32, F_ATTN_FWD, F_ATTN_BWD, F_LN_FWD, F_LN_BWD, F_ADAM, F_ADAPT_NORM,
   F_PERTURB, F_RESIDUAL, F_NUDGE, F_SAMPLE_STAGE, F_MLM_SOFTMAX, F_OTHER, F_COUNT
 };
-// While profiling is enabled every launcher brackets its kernel with two HIP events on the launch stream.
-// `units` = algorithmic flops (GEMM, attention) or algorithmic bytes (everything else) of that launch.
+// While profiling is enabled every launch made through launch_kernel carries a start and a stop event that take the
+// kernel's own begin and end timestamps (hipExtLaunchKernel), so a recorded duration is the kernel's execution time as
+// a kernel trace shows it, without the dispatch gap in front of it.  A scope names the family and the work of what its
+// launcher enqueues; `units` = algorithmic flops (GEMM, attention) or algorithmic bytes (everything else), credited to
+// the scope's first launch.
 struct ProfScope {
   ProfScope(hipStream_t st, int family, double units);
-  ~ProfScope();
+  bool on() const { return on_; }
+  void next_events(hipEvent_t* start, hipEvent_t* stop);   // registers one more launch of this scope (profiling on only)
   hipStream_t st_;
-  int idx_;
+  int family_;
+  double units_;
+  bool on_;
 };
+// kernel<<<grid, block, lds, st>>>(args...), timed when the scope is live.  The actual arguments are converted to the
+// kernel's formal parameter types first, as the launch syntax would.
+template <typename... P, typename... A>
+inline void launch_kernel(ProfScope& ps, void (*kernel)(P...), dim3 grid, dim3 block, unsigned lds, hipStream_t st, A&&... a) {
+  static_assert(sizeof...(P) == sizeof...(A), "argument count");
+  std::tuple<P...> params(std::forward<A>(a)...);
+  void* ptrs[sizeof...(P) > 0 ? sizeof...(P) : 1];
+  detail::arg_pointers(params, ptrs, std::index_sequence_for<P...>{});
+  if (ps.on()) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ps.next_events(&e0, &e1);
+    (void)hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, st, e0, e1, 0);
+  } else {
+    (void)hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds, st);
+  }
+}
 void prof_enable(bool on);
 bool prof_read(int family, const char** name, int64_t* launches, double* total_ms, double* units);
 

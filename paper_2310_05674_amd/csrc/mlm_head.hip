@@ -156,33 +156,33 @@ void launch_aux_cat(hipStream_t st, const int32_t* ids_ft, const int32_t* y_ft, 
                     const int32_t* ids_pt, int n_pt, int S, int32_t* ids_out, int32_t* y_out, uint8_t* mask_out,
                     const int32_t* len_ft, const int32_t* len_pt, int32_t* len_out) {
   ProfScope ps(st, F_OTHER, 8.0 * (n_ft + n_pt) * S);
-  k_aux_cat<<<((n_ft + n_pt) * S + 255) / 256, 256, 0, st>>>(ids_ft, y_ft, mask_ft, n_ft, ids_pt, n_pt, S, ids_out, y_out, mask_out,
+  launch_kernel(ps, k_aux_cat, ((n_ft + n_pt) * S + 255) / 256, 256, 0, st, ids_ft, y_ft, mask_ft, n_ft, ids_pt, n_pt, S, ids_out, y_out, mask_out,
                                                              len_ft, len_pt, len_out);
 }
 void launch_gather_rows(hipStream_t st, const bf16_t* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
                         int n_mask, int P, int d, int nw, bf16_t* out) {
   ProfScope ps(st, F_OTHER, 4.0 * nw * P * d);
-  k_gather_rows<<<dim3(P, nw), 128, 0, st>>>(X, pass_rows, row_base, rows_in_batch, rows, n_mask, P, d, out);
+  launch_kernel(ps, k_gather_rows, dim3(P, nw), 128, 0, st, X, pass_rows, row_base, rows_in_batch, rows, n_mask, P, d, out);
 }
 void launch_gather_rows_split(hipStream_t st, const float* X, int pass_rows, int row_base, int rows_in_batch, const int32_t* rows,
                               int n_mask, int P, int d, int nw, bf16_t* hi, bf16_t* lo) {
   ProfScope ps(st, F_OTHER, 8.0 * nw * P * d);
-  k_gather_rows_split<<<dim3(P, nw), 128, 0, st>>>(X, pass_rows, row_base, rows_in_batch, rows, n_mask, P, d, hi, lo);
+  launch_kernel(ps, k_gather_rows_split, dim3(P, nw), 128, 0, st, X, pass_rows, row_base, rows_in_batch, rows, n_mask, P, d, hi, lo);
 }
 void launch_mlm_ce(hipStream_t st, const float* Z, int V, int P, const int32_t* tgt, int n_mask, int nw, float* loss_pos,
                    float* lse_pos) {
   ProfScope ps(st, F_MLM_SOFTMAX, 4.0 * nw * n_mask * (double)V);
-  k_mlm_ce<<<dim3(n_mask, nw), CE_THREADS, 0, st>>>(Z, V, P, tgt, n_mask, loss_pos, lse_pos);
+  launch_kernel(ps, k_mlm_ce, dim3(n_mask, nw), CE_THREADS, 0, st, Z, V, P, tgt, n_mask, loss_pos, lse_pos);
 }
 void launch_mlm_dz(hipStream_t st, const float* Z, int V, const int32_t* tgt, const float* coef_pos, const float* lse_pos,
                    int n_mask, int P, bf16_t* dZ) {
   ProfScope ps(st, F_MLM_SOFTMAX, 6.0 * n_mask * (double)V + 2.0 * (P - n_mask) * (double)V);
-  k_mlm_dz<<<P, CE_THREADS, 0, st>>>(Z, V, tgt, coef_pos, lse_pos, n_mask, dZ);
+  launch_kernel(ps, k_mlm_dz, P, CE_THREADS, 0, st, Z, V, tgt, coef_pos, lse_pos, n_mask, dZ);
 }
 void launch_scatter_add_rows(hipStream_t st, const float* part, int nparts, int64_t part_stride, int row_base, int rows_in_batch,
                              const int32_t* rows, int n_mask, int d, float* dx) {
   ProfScope ps(st, F_OTHER, 4.0 * (nparts + 2) * n_mask * d);
-  k_scatter_add_rows<<<n_mask, 256, 0, st>>>(part, nparts, part_stride, row_base, rows_in_batch, rows, d, dx);
+  launch_kernel(ps, k_scatter_add_rows, n_mask, 256, 0, st, part, nparts, part_stride, row_base, rows_in_batch, rows, d, dx);
 }
 
 }  // namespace sama

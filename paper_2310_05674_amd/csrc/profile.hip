@@ -1,5 +1,6 @@
-// Per-launch timing with HIP events on the launch stream, aggregated per kernel family.  Off by default: the
-// two event records per launch cost a few microseconds each, so timed throughput runs keep it disabled.
+// Per-launch timing, aggregated per kernel family: each launch carries a start and a stop event bound to the kernel
+// itself (hipExtLaunchKernel), whose difference is the kernel's execution time.  Off by default: the events cost a few
+// microseconds per launch, so timed throughput runs keep it disabled.
 #include <mutex>
 #include <vector>
 #include "kernels.h"
@@ -22,19 +23,15 @@ hipEvent_t take_event() {
 }
 }  // namespace
 
-ProfScope::ProfScope(hipStream_t st, int family, double units) : st_(st), idx_(-1) {
-  if (!g_on) return;
+ProfScope::ProfScope(hipStream_t st, int family, double units) : st_(st), family_(family), units_(units), on_(g_on) {}
+
+void ProfScope::next_events(hipEvent_t* start, hipEvent_t* stop) {
   std::lock_guard<std::mutex> lk(g_mu);
-  Rec r{family, units, take_event(), take_event()};
-  if (r.start == nullptr || r.stop == nullptr) return;
-  (void)hipEventRecord(r.start, st);
-  g_recs.push_back(r);
-  idx_ = (int)g_recs.size() - 1;
-}
-ProfScope::~ProfScope() {
-  if (idx_ < 0) return;
-  std::lock_guard<std::mutex> lk(g_mu);
-  (void)hipEventRecord(g_recs[idx_].stop, st_);
+  Rec r{family_, units_, take_event(), take_event()};
+  units_ = 0.0;   // a scope's work is credited once
+  *start = r.start; *stop = r.stop;
+  if (r.start != nullptr && r.stop != nullptr) g_recs.push_back(r);
+  else { *start = nullptr; *stop = nullptr; }
 }
 
 void prof_enable(bool on) {

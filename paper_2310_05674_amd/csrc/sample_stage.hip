@@ -260,7 +260,7 @@ __global__ __launch_bounds__(256) void k_meta_update(MetaUpdateArgs a) {
 
 void launch_sample_stage(hipStream_t st, const SampleStageArgs& a) {
   ProfScope ps(st, F_SAMPLE_STAGE, 0.0);
-  k_sample_stage<<<1, 256, 0, st>>>(a);
+  launch_kernel(ps, k_sample_stage, 1, 256, 0, st, a);
 }
 void launch_meta_update(hipStream_t st, const MetaUpdateArgs& a) { k_meta_update<<<1, 256, 0, st>>>(a); }
 
