@@ -525,6 +525,41 @@ def test_out_of_range_ids_and_labels_are_clamped():
         assert np.array_equal(res[0][k], res[1][k]), k
 
 
+def test_non_finite_hypergradient_takes_back_the_early_nudge():
+    """bf16 models nudge the GEMM block of theta in the pass that writes the +- halves, before the hypergradient exists.
+    When the hypergradient then turns out not to be finite (a NaN planted in the weight net's output bias, which the
+    direct-gradient pass never reads), the step is skipped like the oracle's: hypergradient 0, lambda and the meta
+    moments untouched, the non-GEMM tail of theta untouched bit for bit, the GEMM block back at its old value up to one
+    fp32 rounding -- and the working copy and its residual half follow, so the next base step gives the gradient of a
+    context that never saw the skipped step."""
+    wl = make_workload(3, n_train=40, n_meta=12, **SMALL)
+    orc, gpu = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    _, ref = make_pair(wl, init_theta(wl, 0.02), init_lambda(wl), base_lr=1e-3)
+    for s in range(3):
+        (x, y), (xm, ym) = _batches(wl, s)
+        gpu.base_step(dev_batch(gpu, x, y)); ref.base_step(dev_batch(ref, x, y)); orc.base_step(x, y)
+    lam = pull(gpu, "LAMBDA").copy(); lam_bad = lam.copy(); lam_bad[-1] = np.nan
+    gpu.set_state("LAMBDA", lam_bad); orc.lam = lam_bad.astype(np.float64)
+    th, mm = pull(gpu, "THETA").copy(), pull(gpu, "META_M").copy()
+    r = orc.meta_step(x, y, xm, ym)
+    assert orc.status == 1 and orc.meta_t == 0 and r["eps"] > 0
+    gpu.meta_step(dev_batch(gpu, x, y), dev_batch(gpu, xm, ym))
+    cnt = pull(gpu, "COUNTERS")
+    assert int(cnt[1]) == 0 and int(cnt[2]) == 1 and float(pull(gpu, "SCALARS")[0]) > 0
+    assert np.all(pull(gpu, "HYPERGRAD") == 0) and np.array_equal(pull(gpu, "META_M"), mm)
+    assert np.array_equal(pull(gpu, "LAMBDA"), lam_bad, equal_nan=True)
+    th2 = pull(gpu, "THETA")
+    ng = _gemm_block(orc)
+    assert np.array_equal(th2[ng:], th[ng:])
+    assert np.max(np.abs(th2[:ng].astype(np.float64) - th[:ng])) <= 2.0 ** -23 * np.max(np.abs(th[:ng]))
+    assert not np.array_equal(pull(gpu, "VDIR"), np.zeros_like(th))          # the direction itself was computed
+    gpu.set_state("LAMBDA", lam)
+    (x, y), _ = _batches(wl, 3)
+    gpu.base_step(dev_batch(gpu, x, y)); ref.base_step(dev_batch(ref, x, y))
+    assert rel_l2(pull(gpu, "G"), pull(ref, "G")) < 1e-4, rel_l2(pull(gpu, "G"), pull(ref, "G"))
+    gpu.close(); ref.close()
+
+
 def test_eval_small_encoder_with_padding():
     """sama_eval on the bf16 encoder, padded batch: logits, losses and weights against the oracle at the bf16 working
     weights (what the base step's forward sees)."""
