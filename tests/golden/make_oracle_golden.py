@@ -43,6 +43,7 @@ def build():
     wl1, wl2 = make_workload(1), make_workload(2)
     out["workload1_adam"] = run_plain(wl1, 3)
     out["workload1_sgd_wd"] = run_plain(wl1, 3, base_opt=SGD, weight_decay=0.01)
+    out["workload1_sgd_momentum"] = run_plain(wl1, 3, base_opt=SGD, momentum=0.9)
     out["workload1_no_adaptation"] = run_plain(wl1, 3, adapt_mode=1)
     out["workload2_adam_wd"] = run_plain(wl2, 2, weight_decay=0.01)
     out["workload2_label_correction"] = run_plain(wl2, 2, lam0=np.concatenate([init_lambda(wl2), init_lambda_corr(wl2, 5)]),
