@@ -195,7 +195,10 @@ sama_status sama_meta_grad(sama_ctx* ctx, const sama_batch* train, const sama_ba
                            float* hypergrad_out /*DEVICE*/, float* eps_out /*DEVICE*/);
 
 /* sama_meta_grad, then one Adam step on lambda with h (Table 4), then theta <- theta - eps v (end of
- * Sec. 3.2).  The base moments and step count are not touched. */
+ * Sec. 3.2).  The base moments and step count are not touched.
+ * Note for Adam base solvers: after the very first base step from zero moments the update is lr * sign(g), so the
+ * adaptation of Eq. 4 vanishes analytically and v holds nothing but rounding noise, which eps = alpha / ||v|| scales to
+ * a step of norm alpha.  Only an exactly zero ||v|| is skipped; run at least two base steps before the first meta step. */
 sama_status sama_meta_step(sama_ctx* ctx, const sama_batch* train, const sama_batch* meta);
 
 /* Auxiliary-task reweighting (Sec. 4.3): L_base = L_ft(ft) + (1/n_seq) sum_x w(L_pt(x); lambda) L_pt(x) over the

@@ -160,21 +160,35 @@ __global__ __launch_bounds__(256) void k_sample_stage(SampleStageArgs a) {
     return;
   }
   __syncthreads();
-  // weight-net backward: thread h owns hidden unit h and walks the samples in order
-  for (int h = tid; h < H; h += 256) {
-    const double w1 = W1[h], bb = b1[h], w2 = W2[h];
-    double dW1 = 0.0, db1 = 0.0, dW2 = 0.0;
-    for (int i = 0; i < B; ++i) {
-      const double l = s_l[i], dz = s_dz[i];
-      const double pre = w1 * l + bb;
-      if (pre > 0.0) {
-        const double da = dz * w2;
-        dW1 += da * l;
-        db1 += da;
-        dW2 += dz * pre;
+  // weight-net backward: hidden unit h is shared by nch consecutive lanes of a wave (the largest power of two <= 256 / H,
+  // at most 64), each walking a contiguous run of the samples in order; every lane then adds the nch partial sums of its
+  // unit in chunk order through shuffles (fixed order, no atomics)
+  {
+    int nch = 1;
+    while (2 * nch * H <= 256 && nch < 64) nch *= 2;
+    const int run = (B + nch - 1) / nch;
+    const int h = tid / nch, c = tid % nch;              // 256 / nch >= H units in one trip
+    double part[3] = {0.0, 0.0, 0.0};                    // dW1, db1, dW2
+    if (h < H) {
+      const double w1 = W1[h], bb = b1[h], w2 = W2[h];
+      const int i1 = (c + 1) * run < B ? (c + 1) * run : B;
+      for (int i = c * run; i < i1; ++i) {
+        const double l = s_l[i], dz = s_dz[i];
+        const double pre = w1 * l + bb;
+        if (pre > 0.0) {
+          const double da = dz * w2;
+          part[0] += da * l;
+          part[1] += da;
+          part[2] += dz * pre;
+        }
       }
     }
-    a.glam[h] = dW1; a.glam[H + h] = db1; a.glam[2 * H + h] = dW2;
+    const int base = (tid & 63) & ~(nch - 1);
+    double tot[3] = {0.0, 0.0, 0.0};
+    for (int k = 0; k < nch; ++k)
+#pragma unroll
+      for (int q = 0; q < 3; ++q) tot[q] += __shfl(part[q], base + k, 64);
+    if (h < H && c == 0) { a.glam[h] = tot[0]; a.glam[H + h] = tot[1]; a.glam[2 * H + h] = tot[2]; }
   }
   double dsum = 0.0;
   for (int i = tid; i < B; i += 256) dsum += s_dz[i];
