@@ -205,7 +205,7 @@ void gemm_bf16_force_shape(int shape);  // tuning hook: 0 = heuristic, else 100 
 
 // ------------------------------------------------------------------ encoder ops (encoder_ops.hip)
 constexpr int LN_MAX_D = 2048;       // LayerNorm kernels keep a row in registers (4 or 8 16-byte pieces per lane)
-constexpr int LN_BWD_ROWS = 4;       // rows per block in the LayerNorm backward (size of its partial sums)
+constexpr int LN_BWD_ROWS = 8;       // rows per block in the LayerNorm backward (size of its partial sums)
 constexpr int COLSUM_ROWS = 16;      // rows per block in the column-sum kernel
 struct LnFwdArgs {
   const float* x;          // [M x d] input, or null: embedding mode (x = tok_emb[id] + pos_emb[m % S])
