@@ -116,7 +116,7 @@ class EncoderModel : public Model {
       n1.mean = keep ? mean1_[s] : nullptr; n1.rstd = keep ? rstd1_[s] : nullptr; n1.M = R; n1.d = d_;
       launch_ln_fwd(st, n1);
       g = GemmBf16Args{};
-      g.act = GEMM_ACT_GELU_FWD; g.C16_pre = fpre_[s]; g.C16 = fact_[s];
+      g.act = GEMM_ACT_GELU_FWD; g.C16_pre = keep ? fpre_[s] : nullptr; g.C16 = fact_[s];   // only a backward pass reads the pre-activation
       fwd_linear(st, w, nw, x1_[s], d_, o.W1, ffn_, o.b1, M, g);
       g = GemmBf16Args{};
       g.res32 = res_[1]; g.C32 = pre2_[s];

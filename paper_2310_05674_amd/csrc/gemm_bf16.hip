@@ -339,7 +339,7 @@ __global__ __launch_bounds__(T::THREADS) void k_gemm_bf16(GemmBatch batch, int n
       uint2 pk;
       pk.x = pack_bf16x2(c[0], c[1]);
       pk.y = pack_bf16x2(c[2], c[3]);
-      *reinterpret_cast<uint2*>(C16_pre + o) = pk;
+      if (C16_pre != nullptr) *reinterpret_cast<uint2*>(C16_pre + o) = pk;   // forward-only passes do not keep it
       // the backward pass sees the rounded pre-activation, so the activation is taken from it too
       c[0] = gelu_f(bf16_to_f32((bf16_t)pk.x)); c[1] = gelu_f(bf16_to_f32((bf16_t)(pk.x >> 16)));
       c[2] = gelu_f(bf16_to_f32((bf16_t)pk.y)); c[3] = gelu_f(bf16_to_f32((bf16_t)(pk.y >> 16)));

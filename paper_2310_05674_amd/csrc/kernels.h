@@ -181,7 +181,7 @@ enum { GEMM_ACT_NONE = 0, GEMM_ACT_GELU_FWD = 1, GEMM_ACT_GELU_BWD = 2 };
 // C[M x N] = A . (B + B2).  a_trans = 0: A stored [M][K]; 1: stored [K][M].  b_trans = 1: B stored [N][K]
 // (a weight matrix [out x in] used forward); 0: stored [K][N].  B2 (same storage as B) may be null.
 // Epilogue, in this order: + bias[j] (+ bsign * *beps * bias_v[j]); + res16 / res32 [i*ldc + j];
-// GELU_FWD: C16_pre = bf16(c), c = gelu(that);  GELU_BWD: c *= gelu'(aux16[i*ldc + j]);  stores to C32 and/or C16.
+// GELU_FWD: C16_pre = bf16(c) (stored when C16_pre is given), c = gelu(that);  GELU_BWD: c *= gelu'(aux16[i*ldc + j]);  stores to C32 and/or C16.
 struct GemmBf16Args {
   const bf16_t* A; int64_t lda; int a_trans;
   const bf16_t* B; const bf16_t* B2; int64_t ldb; int b_trans;
